@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the EF-compress hot path (Algorithm 4 of arxiv 1905.10936) on one MI355X.
+
+One "step" = ef_worker_step for all M workers + ef_server_step + ef_apply over
+one batch of synthetic gradients that are already resident in HBM.  Prints ONE
+JSON line: throughput in Gelem/s counted as (M+1)*d elements through a
+compressor per step, the HBM roofline of the dominant kernel (measured with
+HIP events on the launch stream), and the CPU oracle timed on a bounded sample
+of the same workload on this host.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import ef_workloads as wl  # noqa: E402
+import paper_1905_10936_amd as ef  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE +
+# WRITE_SIZE, scaled by a copy kernel of known size); None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(d, B, M):
+    """Bytes the method itself must move per element of d (fp32 state read
+    once and written once, sign bits, scales)."""
+    worker = M * (20.0 * d + d / 8.0 + 4.0 * B)             # g,m,e in; m,e out; signs; scales
+    server = 8.0 * d + (M + 1) * d / 8.0 + 4.0 * B * (M + 1)
+    apply_ = 8.0 * d + d / 8.0 + 4.0 * B
+    return worker, server, apply_
+
+
+def cpu_baseline(w, grads0, n_blocks, steps):
+    """The oracle, as it stands, on the first n_blocks blocks of the workload
+    (the method is block-separable), single thread."""
+    import oracle
+    offs = w.offsets[:n_blocks + 1].copy()
+    ds = int(offs[-1])
+    M = w.M
+    g = np.ascontiguousarray(grads0[:, :ds].cpu().numpy())
+    m = np.zeros((M, ds), np.float32)
+    e = np.zeros((M, ds), np.float32)
+    te = np.zeros(ds, np.float32)
+    x = np.zeros(ds, np.float32)
+    first = oracle.step(g, m, e, te, x, offs, np.float32(w.mu), np.float32(0.0), np.float32(w.eta))
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        oracle.step(g, m, e, te, x, offs, np.float32(w.mu), np.float32(w.eta), np.float32(w.eta))
+    dt = (time.perf_counter() - t0) / steps
+    return (M + 1) * ds / dt / 1e9, ds, first
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="flat_2p28", choices=sorted(wl.WORKLOADS))
+    ap.add_argument("--grad-sets", type=int, default=0, help="distinct gradient sets kept in HBM (0 = auto)")
+    ap.add_argument("--cpu-blocks", type=int, default=0, help="blocks in the CPU oracle sample (0 = auto)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs M simulated workers and the server on ONE GPU; "
+              "--gpus N with N > 1 is not supported (no collectives are part of it).", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = wl.get(args.workload)
+    d, B, M = w.d, w.B, w.M
+    W = (d + 63) // 64
+    plan = ef.ef_plan_create(w.offsets, M)
+
+    # gradient sets resident in HBM, cycled over the steps
+    n_sets = args.grad_sets or max(1, min(args.steps + args.warmup, int(64e9 // (4.0 * d * M)), 4))
+    grads = torch.empty((n_sets, M, d), dtype=torch.float32, device=dev)
+    for s in range(n_sets):
+        for i in range(M):
+            w.grad(s, i, device=dev, out=grads[s, i])
+    mom = torch.zeros((M, d), dtype=torch.float32, device=dev)
+    err = torch.zeros((M, d), dtype=torch.float32, device=dev)
+    te = torch.zeros(d, dtype=torch.float32, device=dev)
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
+    wc = torch.zeros((M, B), dtype=torch.float32, device=dev)
+    ss = torch.zeros(W, dtype=torch.int64, device=dev)
+    sc = torch.zeros(B, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    state = {"eta_prev": 0.0, "t": 0}
+
+    def step(ev=None):
+        g = grads[state["t"] % n_sets]
+        if ev:
+            ev[0].record(stream)
+        ef.ef_worker_step(plan, g, mom, err, w.mu, state["eta_prev"], w.eta, ws, wc)
+        if ev:
+            ev[1].record(stream)
+        ef.ef_server_step(plan, M, ws, wc, te, state["eta_prev"], w.eta, ss, sc)
+        if ev:
+            ev[2].record(stream)
+        ef.ef_apply(plan, x, ss, sc, w.eta)
+        if ev:
+            ev[3].record(stream)
+        state["eta_prev"] = w.eta
+        state["t"] += 1
+
+    first_payload = None
+    for k in range(args.warmup):
+        step()
+        if k == 0:
+            torch.cuda.synchronize()
+            first_payload = (ws.cpu().numpy().view(np.uint64).copy(), ss.cpu().numpy().view(np.uint64).copy())
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    t_worker = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    t_server = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    t_apply = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    bw, bs, ba = algorithmic_bytes(d, B, M)
+    step_bytes = bw + bs + ba
+    achieved = bw / (t_worker * 1e-3) / 1e9
+
+    value = (M + 1) * d / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "EF-compress step Gelem/s (worker+server, M workers) and % of HBM roofline",
+        "value": round(value, 3),
+        "unit": "Gelem/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": dict(w.describe(), grad_sets_in_hbm=n_sets, elements_counted="(M+1)*d per step",
+                       d_per_step_Gelem_s=round(d / (ms_per_step * 1e-3) / 1e9, 3)),
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "ef_worker_step (k_worker_pass1 + k_residual_pass2), all M workers in one call",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+            "algorithmic_bytes_per_launch": bw,
+            "ms_per_launch": round(t_worker, 4),
+        },
+        "per_call_ms": {"ef_worker_step": round(t_worker, 4), "ef_server_step": round(t_server, 4),
+                        "ef_apply": round(t_apply, 4)},
+        "step_hbm_frac_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+
+    if not args.no_cpu:
+        # bounded sample: a prefix of blocks sized for roughly 10-30 s of single-thread work
+        avg_block = d / B
+        n_blocks = args.cpu_blocks or int(max(1, min(B, round(2.4e7 / avg_block))))
+        cpu_steps = 2
+        g0 = grads[0]
+        cpu_val, ds, first = cpu_baseline(w, g0, n_blocks, cpu_steps)
+        # the oracle's first step on the sample must reproduce the GPU's first payload there
+        check = None
+        if first_payload is not None and args.warmup >= 1:
+            nw = ds // 64
+            check = bool(np.array_equal(first[0][:, :nw], first_payload[0][:, :nw]) and
+                         np.array_equal(first[2][:nw], first_payload[1][:nw]))
+        out["cpu_baseline"] = {
+            "value": round(cpu_val, 4), "unit": "Gelem/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d blocks (%d elements) of the same workload, all M=%d workers + server + apply, "
+                      "%d steps after one warm-up, single thread; host has %d logical cores"
+                      % (n_blocks, ds, M, cpu_steps, os.cpu_count()),
+            "first_step_signs_match_gpu": check,
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,146 @@
+/*
+ * ef.h -- C ABI of libef: the per-iteration hot path of dist-EF-blockSGDM
+ * (Zheng, Huang, Kwok: "Communication-Efficient Distributed Blockwise Momentum
+ * SGD with Error-Feedback", arxiv 1905.10936), hand-written HIP for gfx950.
+ *
+ * One training iteration t of Algorithm 4 is, for M workers on one GPU:
+ *
+ *     ef_worker_step   (all M workers in one call)   "on each worker i"
+ *     ef_server_step                                 "on server"
+ *     ef_apply                                       x_{t+1} = x_t - eta_t * Delta~_t
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Pointers.  Unless a parameter is marked HOST, every pointer is a DEVICE
+ *   pointer into memory owned by the caller.  The library neither frees nor
+ *   retains caller memory beyond the call.  fp32 arrays must be 16-byte aligned,
+ *   sign-word arrays 8-byte aligned (EF_ERR_ALIGN otherwise).
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *   stream).  Calls enqueue work and return without synchronising.  All calls
+ *   that share one plan must be ordered on the device (same stream, or ordered
+ *   by events): the plan owns scratch memory that the kernels of a call use.
+ * Block partition {G_1..G_B} (Section 3.2).  Block b is the contiguous index
+ *   range [block_offsets[b], block_offsets[b+1]) of the flat d-vector;
+ *   block_offsets[0] = 0, strictly increasing (every d_b >= 1, since d_b is a
+ *   denominator), block_offsets[B] = d.
+ * Payload (Section 3.2, Appendix A).  A compressed vector is
+ *     packed_signs : uint64[W], W = ceil(d/64).  Flat index j lives in bit
+ *                    (j mod 64) of word floor(j/64), least significant bit
+ *                    first; bit = 1 encodes sign +1, bit = 0 encodes -1;
+ *                    bits at positions >= d of the last word are written as 0.
+ *     scales       : float[B], scales[b] = ||v_Gb||_1 / d_b.
+ *   sign(0) is read as +1 (both +0 and -0 give bit 1).
+ * Arithmetic.  fp32, round-to-nearest-even, one rounding per written operation,
+ *   left to right, never fused.  The L1 norm of a block is accumulated in fp64
+ *   and rounded once to fp32 after the division by d_b.  Non-finite inputs are
+ *   outside the contract.
+ * Errors.  Every int-returning function returns EF_OK (0) or a negative code;
+ *   on error nothing has been enqueued unless the code is EF_ERR_HIP.
+ */
+#ifndef EF_H
+#define EF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EF_OK 0
+#define EF_ERR_NULL -1    /* a required pointer is NULL */
+#define EF_ERR_OFFSETS -2 /* block_offsets is not a partition as described above */
+#define EF_ERR_ARG -3     /* scalar out of range: M < 1 or > max_workers, mu not in [0,1),
+                             eta <= 0, eta_prev < 0, non-finite, stride < d or not a multiple of 4 */
+#define EF_ERR_ALIGN -4   /* pointer not aligned as required */
+#define EF_ERR_HIP -5     /* the HIP runtime reported an error (allocation, launch, no device) */
+
+#define EF_MAX_WORKERS 64
+
+typedef struct ef_plan ef_plan; /* opaque */
+
+/*
+ * Build the per-layout plan: a device copy of the partition, the tile -> block
+ * table the kernels use to find which blocks a tile touches, and the scratch
+ * memory of the cross-tile block reductions (fp64 partial sums and arrival
+ * counters for max_workers workers and the server).  Blocks follow Section 3.2
+ * ("each parameter tensor/matrix/vector as a block" is the usual choice).
+ *
+ *   out                 HOST  receives the plan; caller releases it with ef_plan_destroy
+ *   block_offsets_host  HOST  int64[B+1], copied; need not outlive the call
+ *   B                         number of blocks, >= 1
+ *   max_workers               largest M / n_workers later calls may pass, 1..EF_MAX_WORKERS
+ *   stream                    unused for ordering: creation synchronises
+ *
+ * Offsets are validated first (EF_ERR_OFFSETS) before any GPU call is made, so
+ * the check also works on a host without a GPU.  Allocates device memory with
+ * hipMalloc on the current device; the plan must be used on that device only.
+ */
+int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, int max_workers,
+                   void *stream);
+int ef_plan_destroy(ef_plan *plan);
+
+int64_t ef_plan_d(const ef_plan *plan);          /* d = block_offsets[B] */
+int64_t ef_plan_blocks(const ef_plan *plan);     /* B */
+int64_t ef_plan_sign_words(const ef_plan *plan); /* W = ceil(d/64) */
+int64_t ef_sign_words(int64_t d);                /* same, without a plan */
+
+/*
+ * Worker side of iteration t of Algorithm 4, for n_workers workers at once
+ * (n_workers = 1 is the per-worker call of the paper).  For worker i, element j:
+ *     m_i   <- mu * m_i + g_i                                  (momentum)
+ *     p_i    = mu * m_i + g_i + (eta_prev / eta) * e_i          (updated m_i)
+ *     push   Delta_i = C_B(p_i)  -> packed_signs[i], scales[i]  (Section 3.2)
+ *     e_i   <- p_i - Delta_i                                   (error feedback)
+ * mu = 0 gives Algorithm 3.  eta_prev = eta_{t-1} with eta_{-1} = 0 on the first
+ * iteration; only the ratio eta_prev/eta (one fp32 division) enters.
+ *
+ *   grad          in      float[n_workers][grad_stride], first d of each row used
+ *   mom, err      in/out  float[n_workers][state_stride], updated in place
+ *   packed_signs  out     uint64[n_workers][W]
+ *   scales        out     float[n_workers][B]
+ * Strides are in elements, >= d and multiples of 4.  Outputs must not overlap
+ * inputs or each other.
+ */
+int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride,
+                   float *mom, float *err, int64_t state_stride, float mu, float eta_prev,
+                   float eta, uint64_t *packed_signs, float *scales, void *stream);
+
+/*
+ * Server side of iteration t of Algorithm 4:
+ *     p~   = (1/M) * sum_i Delta_i + (eta_prev / eta) * e~
+ *     push  Delta~ = C_B(p~)  -> out_signs, out_scales
+ *     e~  <- p~ - Delta~
+ * The sum over workers runs in fp32 in worker order i = 0..M-1 starting from
+ * +0, followed by one fp32 division by (float)M.
+ *
+ *   packed_signs  in      uint64[M][W]   the M worker payloads as ef_worker_step wrote them
+ *   scales        in      float[M][B]
+ *   server_err    in/out  float[d]
+ *   out_signs     out     uint64[W]
+ *   out_scales    out     float[B]
+ */
+int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, const float *scales,
+                   float *server_err, float eta_prev, float eta, uint64_t *out_signs,
+                   float *out_scales, void *stream);
+
+/*
+ * Parameter update of Algorithm 4 with the payload pulled from the server:
+ *     x <- x - eta * Delta~          (eta * scale rounded once, then subtracted)
+ *
+ *   params        in/out  float[d]
+ *   packed_signs  in      uint64[W]
+ *   scales        in      float[B]
+ */
+int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, const float *scales,
+             float eta, void *stream);
+
+/* Static text for an error code; for EF_ERR_HIP the text of the last HIP error
+ * seen by this thread is appended.  The returned pointer stays valid until the
+ * same thread calls ef_strerror again. */
+const char *ef_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EF_H */

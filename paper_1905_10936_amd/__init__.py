@@ -1,0 +1,182 @@
+"""Python binding of libef (include/ef.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI; this module
+turns torch tensors into device pointers and raises on error codes.  There is
+no CPU fallback: if libef.so is missing or cannot be loaded, importing the
+entry points fails loudly.
+
+Names follow the C ABI: ef_plan_create / ef_worker_step / ef_server_step /
+ef_apply (Algorithm 4 of arxiv 1905.10936).
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libef.so")
+
+EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1, -2, -3, -4, -5
+EF_MAX_WORKERS = 64
+
+ABI_SYMBOLS = (
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
+    "ef_sign_words", "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
+)
+
+
+class EfError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libef error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libef.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        _build.build(force=True)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, c_int, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+    L.ef_plan_create.restype = c_int
+    L.ef_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(i64), i64, c_int, vp]
+    L.ef_plan_destroy.restype = c_int
+    L.ef_plan_destroy.argtypes = [vp]
+    for name in ("ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words"):
+        getattr(L, name).restype = i64
+        getattr(L, name).argtypes = [vp]
+    L.ef_sign_words.restype = i64
+    L.ef_sign_words.argtypes = [i64]
+    L.ef_worker_step.restype = c_int
+    L.ef_worker_step.argtypes = [vp, c_int, vp, i64, vp, vp, i64, f32, f32, f32, vp, vp, vp]
+    L.ef_server_step.restype = c_int
+    L.ef_server_step.argtypes = [vp, c_int, vp, vp, vp, f32, f32, vp, vp, vp]
+    L.ef_apply.restype = c_int
+    L.ef_apply.argtypes = [vp, vp, vp, vp, f32, vp]
+    L.ef_strerror.restype = ctypes.c_char_p
+    L.ef_strerror.argtypes = [c_int]
+    _lib = L
+    return L
+
+
+def ef_strerror(code):
+    return lib().ef_strerror(int(code)).decode()
+
+
+def _check(rc):
+    if rc != EF_OK:
+        raise EfError(rc, ef_strerror(rc))
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t, dtype, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a CUDA/HIP torch tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise TypeError("%s must be contiguous" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stride(t, d, name):
+    """Row stride in elements of a [n][d'] (or [d']) tensor holding rows of d."""
+    if t.dim() == 1:
+        return t.numel()
+    if t.dim() != 2:
+        raise TypeError("%s must be 1-D or 2-D" % name)
+    return t.stride(0)
+
+
+def ef_sign_words(d):
+    return int(lib().ef_sign_words(int(d)))
+
+
+class Plan:
+    """ef_plan: the per-layout object of the C ABI (block partition of
+    Section 3.2 + scratch).  Use on the device that was current at creation."""
+
+    def __init__(self, block_offsets, max_workers, stream=None):
+        offs = np.ascontiguousarray(block_offsets, dtype=np.int64)
+        if offs.ndim != 1 or offs.size < 2:
+            raise EfError(EF_ERR_OFFSETS, "block_offsets must hold B+1 >= 2 entries")
+        self._h = ctypes.c_void_p()
+        rc = lib().ef_plan_create(ctypes.byref(self._h), offs.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                  offs.size - 1, int(max_workers), None)
+        _check(rc)
+        self.d = int(lib().ef_plan_d(self._h))
+        self.B = int(lib().ef_plan_blocks(self._h))
+        self.W = int(lib().ef_plan_sign_words(self._h))
+        self.max_workers = int(max_workers)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().ef_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def ef_plan_create(block_offsets, max_workers, stream=None):
+    return Plan(block_offsets, max_workers, stream)
+
+
+def ef_plan_destroy(plan):
+    plan.close()
+
+
+def ef_worker_step(plan, grad, mom, err, mu, eta_prev, eta, packed_signs, scales, stream=None):
+    """grad/mom/err: float32 [n][>=d] (or [d]); packed_signs int64|uint64 [n][W];
+    scales float32 [n][B].  mom, err, packed_signs, scales are written."""
+    n = 1 if grad.dim() == 1 else grad.shape[0]
+    gs, ss = _stride(grad, plan.d, "grad"), _stride(mom, plan.d, "mom")
+    if _stride(err, plan.d, "err") != ss or mom.shape != err.shape:
+        raise TypeError("mom and err must share shape and stride")
+    if packed_signs.numel() != n * plan.W or scales.numel() != n * plan.B:
+        raise TypeError("packed_signs must hold n*W words and scales n*B floats")
+    rc = lib().ef_worker_step(plan._h, n, _ptr(grad, torch.float32, "grad"), gs,
+                              _ptr(mom, torch.float32, "mom"), _ptr(err, torch.float32, "err"), ss,
+                              float(mu), float(eta_prev), float(eta),
+                              _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                              _ptr(scales, torch.float32, "scales"), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_server_step(plan, M, packed_signs, scales, server_err, eta_prev, eta, out_signs, out_scales,
+                   stream=None):
+    if packed_signs.numel() != M * plan.W or scales.numel() != M * plan.B:
+        raise TypeError("packed_signs must hold M*W words and scales M*B floats")
+    if server_err.numel() != plan.d or out_signs.numel() != plan.W or out_scales.numel() != plan.B:
+        raise TypeError("server_err/out_signs/out_scales must hold d/W/B entries")
+    rc = lib().ef_server_step(plan._h, int(M), _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                              _ptr(scales, torch.float32, "scales"),
+                              _ptr(server_err, torch.float32, "server_err"), float(eta_prev), float(eta),
+                              _ptr(out_signs, out_signs.dtype, "out_signs"),
+                              _ptr(out_scales, torch.float32, "out_scales"), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_apply(plan, params, packed_signs, scales, eta, stream=None):
+    if params.numel() != plan.d or packed_signs.numel() != plan.W or scales.numel() != plan.B:
+        raise TypeError("params/packed_signs/scales must hold d/W/B entries")
+    rc = lib().ef_apply(plan._h, _ptr(params, torch.float32, "params"),
+                        _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                        _ptr(scales, torch.float32, "scales"), float(eta), _stream_ptr(stream))
+    _check(rc)

@@ -1,0 +1,257 @@
+// Host side of libef: plan construction, argument checks and kernel launches
+// behind the C ABI declared in include/ef.h.
+#include "ef.h"
+#include "ef_device.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+struct ef_plan {
+    ef::Layout L;
+    ef::Scratch X;
+    int max_workers;
+    int device;
+    std::vector<int64_t> offs_host;
+    // device allocations owned by the plan
+    int64_t *d_offs;
+    int32_t *d_tile_fb;
+    int32_t *d_tile_lb;
+    unsigned long long *d_part;
+    unsigned int *d_cnt;
+};
+
+namespace {
+
+thread_local char g_errbuf[512];
+thread_local hipError_t g_last_hip = hipSuccess;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip = e;
+    return EF_ERR_HIP;
+}
+
+#define EF_HIP(call)                                  \
+    do {                                              \
+        hipError_t e_ = (call);                       \
+        if (e_ != hipSuccess) return hip_fail(e_);    \
+    } while (0)
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_offsets(const int64_t *offs, int64_t B)
+{
+    if (!offs) return EF_ERR_NULL;
+    if (B < 1 || B > (int64_t)0x7fffffff - 1) return EF_ERR_OFFSETS;
+    if (offs[0] != 0) return EF_ERR_OFFSETS;
+    for (int64_t b = 0; b < B; ++b)
+        if (offs[b + 1] <= offs[b]) return EF_ERR_OFFSETS;
+    // tiles are indexed with 32-bit integers
+    if ((offs[B] + ef::TILE - 1) / ef::TILE > (int64_t)0x7fffffff) return EF_ERR_OFFSETS;
+    return EF_OK;
+}
+
+bool good_eta(float eta_prev, float eta)
+{
+    return std::isfinite(eta) && std::isfinite(eta_prev) && eta > 0.0f && eta_prev >= 0.0f;
+}
+
+void destroy_device(ef_plan *p)
+{
+    if (p->d_offs) (void)hipFree(p->d_offs);
+    if (p->d_tile_fb) (void)hipFree(p->d_tile_fb);
+    if (p->d_tile_lb) (void)hipFree(p->d_tile_lb);
+    if (p->d_part) (void)hipFree(p->d_part);
+    if (p->d_cnt) (void)hipFree(p->d_cnt);
+}
+
+int build_device(ef_plan *p)
+{
+    const int64_t B = p->L.B, d = p->L.d;
+    const int32_t ntiles = p->L.ntiles;
+    const int nsets = p->max_workers + 1;    // workers 0..max_workers-1, then the server
+    std::vector<int32_t> fb(ntiles), lb(ntiles);
+    {
+        // block of the first and of the last valid element of every tile
+        int64_t b = 0;
+        const int64_t *o = p->offs_host.data();
+        for (int32_t t = 0; t < ntiles; ++t) {
+            const int64_t first = (int64_t)t * ef::TILE;
+            int64_t last = first + ef::TILE - 1;
+            if (last > d - 1) last = d - 1;
+            while (o[b + 1] <= first) ++b;
+            fb[t] = (int32_t)b;
+            int64_t c = b;
+            while (o[c + 1] <= last) ++c;
+            lb[t] = (int32_t)c;
+        }
+    }
+    EF_HIP(hipGetDevice(&p->device));
+    EF_HIP(hipMalloc(&p->d_offs, sizeof(int64_t) * (B + 1)));
+    EF_HIP(hipMalloc(&p->d_tile_fb, sizeof(int32_t) * ntiles));
+    EF_HIP(hipMalloc(&p->d_tile_lb, sizeof(int32_t) * ntiles));
+    EF_HIP(hipMalloc(&p->d_part, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
+    EF_HIP(hipMalloc(&p->d_cnt, sizeof(unsigned int) * (size_t)B * nsets));
+    EF_HIP(hipMemcpy(p->d_offs, p->offs_host.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice));
+    EF_HIP(hipMemcpy(p->d_tile_fb, fb.data(), sizeof(int32_t) * ntiles, hipMemcpyHostToDevice));
+    EF_HIP(hipMemcpy(p->d_tile_lb, lb.data(), sizeof(int32_t) * ntiles, hipMemcpyHostToDevice));
+    EF_HIP(hipMemset(p->d_part, 0, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
+    EF_HIP(hipMemset(p->d_cnt, 0, sizeof(unsigned int) * (size_t)B * nsets));
+    EF_HIP(hipDeviceSynchronize());
+    p->L.offs = p->d_offs;
+    p->L.tile_fb = p->d_tile_fb;
+    p->L.tile_lb = p->d_tile_lb;
+    p->X.part = p->d_part;
+    p->X.cnt = p->d_cnt;
+    return EF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t ef_sign_words(int64_t d) { return d < 0 ? 0 : (d + 63) / 64; }
+
+int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, int max_workers, void *stream)
+{
+    (void)stream;
+    if (!out) return EF_ERR_NULL;
+    *out = nullptr;
+    int rc = check_offsets(block_offsets_host, B);
+    if (rc) return rc;
+    if (max_workers < 1 || max_workers > EF_MAX_WORKERS) return EF_ERR_ARG;
+    ef_plan *p = new (std::nothrow) ef_plan();
+    if (!p) return EF_ERR_ARG;
+    p->offs_host.assign(block_offsets_host, block_offsets_host + B + 1);
+    p->max_workers = max_workers;
+    p->L.B = B;
+    p->L.d = block_offsets_host[B];
+    p->L.W = ef_sign_words(p->L.d);
+    p->L.ntiles = (int32_t)((p->L.d + ef::TILE - 1) / ef::TILE);
+    p->d_offs = nullptr;
+    p->d_tile_fb = p->d_tile_lb = nullptr;
+    p->d_part = nullptr;
+    p->d_cnt = nullptr;
+    rc = build_device(p);
+    if (rc) {
+        destroy_device(p);
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return EF_OK;
+}
+
+int ef_plan_destroy(ef_plan *plan)
+{
+    if (!plan) return EF_ERR_NULL;
+    (void)hipDeviceSynchronize();
+    destroy_device(plan);
+    delete plan;
+    return EF_OK;
+}
+
+int64_t ef_plan_d(const ef_plan *plan) { return plan ? plan->L.d : 0; }
+int64_t ef_plan_blocks(const ef_plan *plan) { return plan ? plan->L.B : 0; }
+int64_t ef_plan_sign_words(const ef_plan *plan) { return plan ? plan->L.W : 0; }
+
+int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
+                   float *err, int64_t state_stride, float mu, float eta_prev, float eta,
+                   uint64_t *packed_signs, float *scales, void *stream)
+{
+    if (!plan || !grad || !mom || !err || !packed_signs || !scales) return EF_ERR_NULL;
+    if (n_workers < 1 || n_workers > plan->max_workers) return EF_ERR_ARG;
+    if (!(mu >= 0.0f && mu < 1.0f) || !good_eta(eta_prev, eta)) return EF_ERR_ARG;
+    if (grad_stride < plan->L.d || state_stride < plan->L.d || grad_stride % 4 || state_stride % 4)
+        return EF_ERR_ARG;
+    if ((const void *)grad == (const void *)mom || (const void *)grad == (const void *)err || mom == err)
+        return EF_ERR_ARG;
+    if (!aligned(grad, 16) || !aligned(mom, 16) || !aligned(err, 16) || !aligned(scales, 4) ||
+        !aligned(packed_signs, 8))
+        return EF_ERR_ALIGN;
+    ef::WorkerArgs A;
+    A.grad = grad;
+    A.grad_stride = grad_stride;
+    A.mom = mom;
+    A.err = err;
+    A.state_stride = state_stride;
+    A.mu = mu;
+    A.r = eta_prev / eta;
+    A.signs = packed_signs;
+    A.scales = scales;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)plan->L.ntiles, (unsigned)n_workers);
+    hipLaunchKernelGGL(ef::k_worker_pass1, grid, dim3(ef::THREADS), 0, s, plan->L, plan->X, A);
+    EF_HIP(hipGetLastError());
+    hipLaunchKernelGGL(ef::k_residual_pass2, grid, dim3(ef::THREADS), 0, s, plan->L, err, state_stride,
+                       (const float *)scales);
+    EF_HIP(hipGetLastError());
+    return EF_OK;
+}
+
+int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, const float *scales,
+                   float *server_err, float eta_prev, float eta, uint64_t *out_signs, float *out_scales,
+                   void *stream)
+{
+    if (!plan || !packed_signs || !scales || !server_err || !out_signs || !out_scales) return EF_ERR_NULL;
+    if (M < 1 || M > plan->max_workers) return EF_ERR_ARG;
+    if (!good_eta(eta_prev, eta)) return EF_ERR_ARG;
+    if (packed_signs == out_signs || scales == out_scales) return EF_ERR_ARG;
+    if (!aligned(server_err, 16) || !aligned(packed_signs, 8) || !aligned(out_signs, 8) ||
+        !aligned(scales, 4) || !aligned(out_scales, 4))
+        return EF_ERR_ALIGN;
+    ef::ServerArgs A;
+    A.M = M;
+    A.signs_in = packed_signs;
+    A.scales_in = scales;
+    A.err = server_err;
+    A.r = eta_prev / eta;
+    A.Mf = (float)M;
+    A.signs = out_signs;
+    A.scales = out_scales;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)plan->L.ntiles, 1u);
+    hipLaunchKernelGGL(ef::k_server_pass1, grid, dim3(ef::THREADS), 0, s, plan->L, plan->X, A,
+                       plan->max_workers);
+    EF_HIP(hipGetLastError());
+    hipLaunchKernelGGL(ef::k_residual_pass2, grid, dim3(ef::THREADS), 0, s, plan->L, server_err,
+                       (int64_t)0, (const float *)out_scales);
+    EF_HIP(hipGetLastError());
+    return EF_OK;
+}
+
+int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, const float *scales, float eta,
+             void *stream)
+{
+    if (!plan || !params || !packed_signs || !scales) return EF_ERR_NULL;
+    if (!(std::isfinite(eta) && eta > 0.0f)) return EF_ERR_ARG;
+    if (!aligned(params, 16) || !aligned(packed_signs, 8) || !aligned(scales, 4)) return EF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)plan->L.ntiles, 1u);
+    hipLaunchKernelGGL(ef::k_apply, grid, dim3(ef::THREADS), 0, s, plan->L, params, packed_signs, scales, eta);
+    EF_HIP(hipGetLastError());
+    return EF_OK;
+}
+
+const char *ef_strerror(int code)
+{
+    const char *t;
+    switch (code) {
+    case EF_OK: t = "ok"; break;
+    case EF_ERR_NULL: t = "a required pointer is NULL"; break;
+    case EF_ERR_OFFSETS: t = "block_offsets is not a partition (0 = o[0] < o[1] < ... < o[B] = d)"; break;
+    case EF_ERR_ARG: t = "argument out of range"; break;
+    case EF_ERR_ALIGN: t = "pointer not aligned (fp32 arrays 16 bytes, sign words 8 bytes)"; break;
+    case EF_ERR_HIP:
+        snprintf(g_errbuf, sizeof g_errbuf, "HIP runtime error: %s", hipGetErrorString(g_last_hip));
+        return g_errbuf;
+    default: t = "unknown error code"; break;
+    }
+    snprintf(g_errbuf, sizeof g_errbuf, "%s", t);
+    return g_errbuf;
+}
+
+}  // extern "C"

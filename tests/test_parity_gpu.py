@@ -1,0 +1,185 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element
+by element on the same seeded inputs.
+
+Bar: sign words, packed payloads and momentum bit-exact; scales within 1e-6
+relative; residuals and parameters bit-exact wherever the block's scale is
+bit-equal, else within 1e-6 of that scale (see tests/parity_util.py).  Sizes are
+chosen so that the oracle finishes in seconds while the layouts still span
+several 4096-element tiles, ragged tails and blocks from 1 element up.
+"""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+import ef_workloads as wl
+import oracle
+import paper_1905_10936_amd as ef
+from tests.parity_util import F, GpuState, synced_step, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _offs(sizes):
+    return np.concatenate([[0], np.cumsum(np.asarray(sizes, dtype=np.int64))])
+
+
+def _layouts():
+    rng = np.random.default_rng(42)
+    tiny = np.clip(np.floor(np.exp(rng.uniform(0, np.log(65), 3000))), 1, 64).astype(np.int64)
+    mixed = np.concatenate([tiny[:700], [20000], tiny[700:1500], [4096 * 3], tiny[1500:], [9000]])
+    return {
+        "one_elem": [1],
+        "d3": [2, 1],
+        "d63": [63],
+        "d64": [64],
+        "d65_two": [1, 64],
+        "tile_minus1": [4095],
+        "tile_exact": [4096],
+        "tile_plus1": [4097],
+        "single_block_5tiles_ragged": [5 * 4096 + 77],
+        "aligned_tiles": [4096] * 6,
+        "blocks_1000": [1000] * 37 + [123],
+        "all_ones": [1] * 9000,
+        "tiny_blocks": tiny,
+        "mixed_tiny_and_big": mixed,
+        "two_big": [3 * 4096 + 5, 7 * 4096 - 5],
+        "straddle_65": [4064, 65, 4063, 130, 12000],
+    }
+
+
+LAYOUTS = _layouts()
+
+
+def _grads(rng, T, M, d, zeros=0.0, scale=1.0):
+    g = (scale * rng.standard_normal((T, M, d))).astype(F)
+    if zeros:
+        g[rng.random((T, M, d)) < zeros] = 0.0
+    return g
+
+
+@pytest.mark.parametrize("name", list(LAYOUTS))
+def test_step_parity_small_layouts(name):
+    offs = _offs(LAYOUTS[name])
+    d = int(offs[-1])
+    M, T = 3, 3
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    g = _grads(rng, T, M, d, zeros=0.05)
+    st = GpuState(offs, M, x0=rng.standard_normal(d).astype(F))
+    etas = [0.1, 0.1, 0.05]
+    eta_prev = 0.0
+    stats = {}
+    for t in range(T):
+        st.set_grads(g[t])
+        synced_step(st, 0.9, eta_prev, etas[t], stats, "%s step %d" % (name, t))
+        eta_prev = etas[t]
+    assert stats["scales_not_bit_equal"] == 0
+
+
+@pytest.mark.parametrize("M", [1, 2, 5, 8, 16])
+def test_server_worker_counts(M):
+    offs = _offs(LAYOUTS["mixed_tiny_and_big"])
+    d = int(offs[-1])
+    rng = np.random.default_rng(M)
+    st = GpuState(offs, M)
+    eta_prev = 0.0
+    for t in range(2):
+        st.set_grads(_grads(rng, 1, M, d)[0])
+        synced_step(st, 0.9, eta_prev, 0.1, None, "M=%d step %d" % (M, t))
+        eta_prev = 0.1
+
+
+def test_strided_state_rows_and_mu_zero():
+    """Row stride larger than d (padding untouched) and Algorithm 3 (mu = 0)."""
+    offs = _offs([5000, 3, 4100, 1])
+    d = int(offs[-1])
+    rng = np.random.default_rng(5)
+    st = GpuState(offs, 2, pad=3)
+    eta_prev = 0.0
+    for t, eta in enumerate([0.2, 0.05, 0.1]):
+        st.set_grads(_grads(rng, 1, 2, d)[0])
+        synced_step(st, 0.0, eta_prev, eta, None, "strided step %d" % t)
+        eta_prev = eta
+
+
+def test_zero_gradients_and_zero_blocks():
+    """All-zero blocks: scale 0, every bit 1, residual 0 (zero-sign reading)."""
+    offs = _offs([100, 5000, 64, 9000])
+    d = int(offs[-1])
+    st = GpuState(offs, 2)
+    g = np.zeros((2, d), F)
+    g[:, 100:5100] = np.random.default_rng(1).standard_normal((2, 5000)).astype(F)
+    g[0, 200] = -0.0
+    st.set_grads(g)
+    synced_step(st, 0.9, 0.0, 0.1, None, "zeros")
+    wc, ws = to_np(st.wc), to_np(st.ws)
+    assert wc[0, 0] == 0 and wc[0, 2] == 0 and wc[0, 3] == 0
+    bits = np.unpackbits(ws[0].view(np.uint8), bitorder="little")[:d]
+    assert bits[:100].all() and bits[5100:].all()
+    assert not to_np(st.e[:, :100]).any()
+
+
+def test_resnet20_like_config_free_running():
+    """Configuration 1 (ResNet-20-like layout, M = 2, 5 steps) step by step,
+    plus a free-running oracle that is never re-synchronised: when every scale
+    of every step is bit-equal, the two trajectories must be identical."""
+    w = wl.get("resnet20_like")
+    st = GpuState(w.offsets, w.M)
+    d, M = w.d, w.M
+    m = np.zeros((M, d), F)
+    e = np.zeros((M, d), F)
+    te = np.zeros(d, F)
+    x = np.zeros(d, F)
+    eta_prev = 0.0
+    stats = {}
+    for t in range(w.steps):
+        g = np.stack([w.grad(t, i).numpy() for i in range(M)])
+        st.set_grads(g)
+        synced_step(st, w.mu, eta_prev, w.eta, stats, "resnet20 step %d" % t)
+        oracle.step(g, m, e, te, x, w.offsets, F(w.mu), F(eta_prev), F(w.eta))
+        eta_prev = w.eta
+    if stats["scales_not_bit_equal"] == 0:
+        h = st.host()
+        assert np.array_equal(h["x"], x) and np.array_equal(h["te"], te)
+        assert np.array_equal(h["m"], m) and np.array_equal(h["e"], e)
+
+
+def test_repeat_call_is_deterministic():
+    """Same inputs twice -> identical payload bits (no order-dependent sums)."""
+    offs = _offs(LAYOUTS["mixed_tiny_and_big"])
+    d = int(offs[-1])
+    rng = np.random.default_rng(77)
+    g = _grads(rng, 1, 4, d)[0]
+    outs = []
+    for _ in range(2):
+        st = GpuState(offs, 4)
+        st.set_grads(g)
+        ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.9, 0.0, 0.1, st.ws, st.wc)
+        ef.ef_server_step(st.plan, 4, st.ws, st.wc, st.te, 0.0, 0.1, st.ss, st.sc)
+        torch.cuda.synchronize()
+        outs.append([to_np(t).copy() for t in (st.ws, st.wc, st.ss, st.sc, st.e, st.te)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+def test_abi_error_codes_on_device():
+    offs = _offs([100, 200])
+    st = GpuState(offs, 2)
+    with pytest.raises(ef.EfError) as ei:
+        ef.ef_worker_step(st.plan, st.g, st.m, st.e, 1.0, 0.0, 0.1, st.ws, st.wc)      # mu = 1
+    assert ei.value.code == ef.EF_ERR_ARG
+    with pytest.raises(ef.EfError) as ei:
+        ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.9, 0.0, 0.0, st.ws, st.wc)      # eta = 0
+    assert ei.value.code == ef.EF_ERR_ARG
+    with pytest.raises(ef.EfError) as ei:
+        ef.ef_server_step(st.plan, 3, torch.zeros(3 * st.W, dtype=torch.int64, device="cuda"),
+                          torch.zeros(3 * st.B, device="cuda"), st.te, 0.0, 0.1, st.ss, st.sc)  # M > max
+    assert ei.value.code == ef.EF_ERR_ARG
+    with pytest.raises(ef.EfError) as ei:
+        ef.ef_apply(st.plan, st.x, st.ss, st.sc, float("nan"))
+    assert ei.value.code == ef.EF_ERR_ARG
+    big = torch.zeros(st.d + 8, device="cuda")
+    with pytest.raises(ef.EfError) as ei:
+        ef.ef_apply(st.plan, big[1:st.d + 1], st.ss, st.sc, 0.1)                          # misaligned
+    assert ei.value.code == ef.EF_ERR_ALIGN
