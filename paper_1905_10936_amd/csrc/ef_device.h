@@ -158,10 +158,20 @@ __device__ __forceinline__ void publish_open_segment(double partial, int which, 
     const int64_t bs = L.offs[b], be = L.offs[b + 1];
     const int64_t t0 = bs / TILE, t1 = (be - 1) / TILE;
     if (threadIdx.x == 0) {
-        __hip_atomic_store(part + 2 * (int64_t)tile + which, (unsigned long long)__double_as_longlong(partial),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned old = __hip_atomic_fetch_add(cnt + b, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = (old + 1u == (unsigned)(t1 - t0 + 1)) ? 1 : 0;
+        // All traffic of this hand-off is relaxed agent-scope atomics, which the
+        // hardware performs at the point where the 8 XCDs' L2 caches meet.  The
+        // exchange returns only once the partial is there, and the counter bump
+        // is made to depend on its return value, so a workgroup that sees the
+        // final count also sees every partial.  (An agent-scope release fence
+        // would order them too, but it writes back the whole L2 of streaming
+        // stores on every tile.)
+        unsigned long long old =
+            __hip_atomic_exchange(part + 2 * (int64_t)tile + which, (unsigned long long)__double_as_longlong(partial),
+                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned inc = 1u;
+        asm volatile("" : "+v"(inc) : "v"((unsigned)old), "v"((unsigned)(old >> 32)) : "memory");
+        unsigned prev = __hip_atomic_fetch_add(cnt + b, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *flag = (prev + 1u == (unsigned)(t1 - t0 + 1)) ? 1 : 0;
     }
     __syncthreads();
     const int last = *flag;
