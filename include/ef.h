@@ -80,6 +80,20 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
                    void *stream);
 int ef_plan_destroy(ef_plan *plan);
 
+/*
+ * Tuning knobs of the one-pass residual update (e <- p - Delta of Algorithm 4
+ * needs the whole block's scale): workgroups of a block spanning at most
+ * fuse_limit tiles of 4096 elements keep p in registers and wait for the scale,
+ * polling at most spin_limit times before they fall back to the two-pass route
+ * that larger blocks always take.  Results are identical on either route.
+ * Negative values leave a setting unchanged; fuse_limit = 0 sends every block
+ * through two passes, spin_limit = 0 makes every wait give up at once (used by
+ * tests to exercise the fallback).  Synchronises the device.  The default
+ * fuse_limit is half the number of workgroups resident on the device at once.
+ */
+int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
+int ef_plan_fuse_limit(const ef_plan *plan);
+
 int64_t ef_plan_d(const ef_plan *plan);          /* d = block_offsets[B] */
 int64_t ef_plan_blocks(const ef_plan *plan);     /* B */
 int64_t ef_plan_sign_words(const ef_plan *plan); /* W = ceil(d/64) */

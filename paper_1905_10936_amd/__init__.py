@@ -23,7 +23,7 @@ EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1
 EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
-    "ef_plan_create", "ef_plan_destroy", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
     "ef_sign_words", "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
 )
 
@@ -53,6 +53,10 @@ def lib():
     for name in ("ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words"):
         getattr(L, name).restype = i64
         getattr(L, name).argtypes = [vp]
+    L.ef_plan_tune.restype = c_int
+    L.ef_plan_tune.argtypes = [vp, c_int, c_int]
+    L.ef_plan_fuse_limit.restype = c_int
+    L.ef_plan_fuse_limit.argtypes = [vp]
     L.ef_sign_words.restype = i64
     L.ef_sign_words.argtypes = [i64]
     L.ef_worker_step.restype = c_int
@@ -122,6 +126,13 @@ class Plan:
         self.W = int(lib().ef_plan_sign_words(self._h))
         self.max_workers = int(max_workers)
 
+    def tune(self, fuse_limit=-1, spin_limit=-1):
+        _check(lib().ef_plan_tune(self._h, int(fuse_limit), int(spin_limit)))
+
+    @property
+    def fuse_limit(self):
+        return int(lib().ef_plan_fuse_limit(self._h))
+
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:
             lib().ef_plan_destroy(self._h)
@@ -136,6 +147,14 @@ class Plan:
 
 def ef_plan_create(block_offsets, max_workers, stream=None):
     return Plan(block_offsets, max_workers, stream)
+
+
+def ef_plan_tune(plan, fuse_limit=-1, spin_limit=-1):
+    plan.tune(fuse_limit, spin_limit)
+
+
+def ef_plan_fuse_limit(plan):
+    return plan.fuse_limit
 
 
 def ef_plan_destroy(plan):

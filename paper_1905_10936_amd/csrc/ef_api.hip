@@ -14,13 +14,21 @@ struct ef_plan {
     ef::Scratch X;
     int max_workers;
     int device;
+    int spin_limit;
+    unsigned int epoch;             // last epoch handed to a call
     std::vector<int64_t> offs_host;
+    std::vector<int32_t> fb_host, lb_host;
+    uint32_t n_static;              // open segments of blocks larger than fuse_limit
     // device allocations owned by the plan
     int64_t *d_offs;
     int32_t *d_tile_fb;
     int32_t *d_tile_lb;
     unsigned long long *d_part;
     unsigned int *d_cnt;
+    unsigned long long *d_ready;
+    unsigned int *d_defer_cnt;      // [2], alternating between calls
+    unsigned long long *d_defer_list;
+    uint32_t *d_static;             // [2*ntiles] capacity
 };
 
 namespace {
@@ -66,6 +74,36 @@ void destroy_device(ef_plan *p)
     if (p->d_tile_lb) (void)hipFree(p->d_tile_lb);
     if (p->d_part) (void)hipFree(p->d_part);
     if (p->d_cnt) (void)hipFree(p->d_cnt);
+    if (p->d_ready) (void)hipFree(p->d_ready);
+    if (p->d_defer_cnt) (void)hipFree(p->d_defer_cnt);
+    if (p->d_defer_list) (void)hipFree(p->d_defer_list);
+    if (p->d_static) (void)hipFree(p->d_static);
+}
+
+int64_t tiles_of_block(const ef_plan *p, int64_t b)
+{
+    const int64_t *o = p->offs_host.data();
+    return (o[b + 1] - 1) / ef::TILE - o[b] / ef::TILE + 1;
+}
+
+// The open segments that the one-pass path leaves to the second kernel: those
+// of blocks spanning more than fuse_limit tiles.
+int upload_static_list(ef_plan *p)
+{
+    std::vector<uint32_t> items;
+    const int64_t *o = p->offs_host.data();
+    for (int32_t t = 0; t < p->L.ntiles; ++t) {
+        const int64_t start = (int64_t)t * ef::TILE, end = start + ef::TILE;
+        const int32_t fb = p->fb_host[t], lb = p->lb_host[t];
+        const bool first_open = (o[fb] < start) || (o[fb + 1] > end);
+        if (first_open && tiles_of_block(p, fb) > p->L.fuse_limit) items.push_back(((uint32_t)t << 1) | 0u);
+        if (lb != fb && o[lb + 1] > end && tiles_of_block(p, lb) > p->L.fuse_limit)
+            items.push_back(((uint32_t)t << 1) | 1u);
+    }
+    p->n_static = (uint32_t)items.size();
+    if (!items.empty())
+        EF_HIP(hipMemcpy(p->d_static, items.data(), sizeof(uint32_t) * items.size(), hipMemcpyHostToDevice));
+    return EF_OK;
 }
 
 int build_device(ef_plan *p)
@@ -73,7 +111,9 @@ int build_device(ef_plan *p)
     const int64_t B = p->L.B, d = p->L.d;
     const int32_t ntiles = p->L.ntiles;
     const int nsets = p->max_workers + 1;    // workers 0..max_workers-1, then the server
-    std::vector<int32_t> fb(ntiles), lb(ntiles);
+    std::vector<int32_t> &fb = p->fb_host, &lb = p->lb_host;
+    fb.resize(ntiles);
+    lb.resize(ntiles);
     {
         // block of the first and of the last valid element of every tile
         int64_t b = 0;
@@ -100,13 +140,53 @@ int build_device(ef_plan *p)
     EF_HIP(hipMemcpy(p->d_tile_lb, lb.data(), sizeof(int32_t) * ntiles, hipMemcpyHostToDevice));
     EF_HIP(hipMemset(p->d_part, 0, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
     EF_HIP(hipMemset(p->d_cnt, 0, sizeof(unsigned int) * (size_t)B * nsets));
-    EF_HIP(hipDeviceSynchronize());
+    EF_HIP(hipMalloc(&p->d_ready, sizeof(unsigned long long) * (size_t)B * nsets));
+    EF_HIP(hipMalloc(&p->d_defer_cnt, sizeof(unsigned int) * 2));
+    EF_HIP(hipMalloc(&p->d_defer_list, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
+    EF_HIP(hipMalloc(&p->d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
+    EF_HIP(hipMemset(p->d_ready, 0, sizeof(unsigned long long) * (size_t)B * nsets));
+    EF_HIP(hipMemset(p->d_defer_cnt, 0, sizeof(unsigned int) * 2));
     p->L.offs = p->d_offs;
     p->L.tile_fb = p->d_tile_fb;
     p->L.tile_lb = p->d_tile_lb;
     p->X.part = p->d_part;
     p->X.cnt = p->d_cnt;
+    p->X.ready = p->d_ready;
+    p->X.defer_list = p->d_defer_list;
+    p->X.defer_cnt = p->d_defer_cnt;
+    // A block finishes in one pass if its tiles fit twice over into the
+    // workgroups resident at once (see ef_device.h).
+    {
+        hipDeviceProp_t prop;
+        EF_HIP(hipGetDeviceProperties(&prop, p->device));
+        int occ_w = 0, occ_s = 0;
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_w, ef::k_worker, ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server, ef::THREADS, 0));
+        const int occ = occ_w < occ_s ? occ_w : occ_s;
+        int64_t lim = (int64_t)prop.multiProcessorCount * occ / 2;
+        if (lim < 1) lim = 1;
+        p->L.fuse_limit = (int32_t)lim;
+    }
+    p->spin_limit = 1 << 14;
+    p->epoch = 0;
+    int rc = upload_static_list(p);
+    if (rc) return rc;
+    EF_HIP(hipDeviceSynchronize());
     return EF_OK;
+}
+
+// Scratch view of one call: a fresh epoch and the deferral counter of its parity.
+ef::Scratch next_call(const ef_plan *plan_c, unsigned int **next_cnt)
+{
+    ef_plan *plan = const_cast<ef_plan *>(plan_c);   // calls on one plan are ordered by contract
+    plan->epoch += 1;
+    if (plan->epoch == 0) plan->epoch = 2;           // keep the odd/even alternation across the wrap
+    ef::Scratch X = plan->X;
+    X.epoch = plan->epoch;
+    X.spin_limit = plan->spin_limit;
+    X.defer_cnt = plan->d_defer_cnt + (plan->epoch & 1u);
+    *next_cnt = plan->d_defer_cnt + ((plan->epoch + 1u) & 1u);
+    return X;
 }
 
 }  // namespace
@@ -135,6 +215,11 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_tile_fb = p->d_tile_lb = nullptr;
     p->d_part = nullptr;
     p->d_cnt = nullptr;
+    p->d_ready = nullptr;
+    p->d_defer_cnt = nullptr;
+    p->d_defer_list = nullptr;
+    p->d_static = nullptr;
+    p->n_static = 0;
     rc = build_device(p);
     if (rc) {
         destroy_device(p);
@@ -153,6 +238,21 @@ int ef_plan_destroy(ef_plan *plan)
     delete plan;
     return EF_OK;
 }
+
+int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
+{
+    if (!plan) return EF_ERR_NULL;
+    EF_HIP(hipDeviceSynchronize());
+    if (spin_limit >= 0) plan->spin_limit = spin_limit;
+    if (fuse_limit >= 0) {
+        plan->L.fuse_limit = fuse_limit;
+        int rc = upload_static_list(plan);
+        if (rc) return rc;
+    }
+    return EF_OK;
+}
+
+int ef_plan_fuse_limit(const ef_plan *plan) { return plan ? plan->L.fuse_limit : 0; }
 
 int64_t ef_plan_d(const ef_plan *plan) { return plan ? plan->L.d : 0; }
 int64_t ef_plan_blocks(const ef_plan *plan) { return plan ? plan->L.B : 0; }
@@ -184,10 +284,18 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
     A.scales = scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)plan->L.ntiles, (unsigned)n_workers);
-    hipLaunchKernelGGL(ef::k_worker_pass1, grid, dim3(ef::THREADS), 0, s, plan->L, plan->X, A);
+    unsigned int *next_cnt;
+    const ef::Scratch X = next_call(plan, &next_cnt);
+    hipLaunchKernelGGL(ef::k_worker, grid, dim3(ef::THREADS), 0, s, plan->L, X, A);
     EF_HIP(hipGetLastError());
-    hipLaunchKernelGGL(ef::k_residual_pass2, grid, dim3(ef::THREADS), 0, s, plan->L, err, state_stride,
-                       (const float *)scales);
+    if (plan->n_static) {
+        hipLaunchKernelGGL(ef::k_residual_static, dim3(plan->n_static, (unsigned)n_workers), dim3(ef::THREADS), 0, s,
+                           plan->L, (const uint32_t *)plan->d_static, err, state_stride, (const float *)scales);
+        EF_HIP(hipGetLastError());
+    }
+    hipLaunchKernelGGL(ef::k_residual_deferred, dim3(ef::DEFER_WGS), dim3(ef::THREADS), 0, s, plan->L,
+                       (const unsigned int *)X.defer_cnt, next_cnt, (const unsigned long long *)X.defer_list, 0, err,
+                       state_stride, (const float *)scales);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
@@ -214,11 +322,18 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
     A.scales = out_scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)plan->L.ntiles, 1u);
-    hipLaunchKernelGGL(ef::k_server_pass1, grid, dim3(ef::THREADS), 0, s, plan->L, plan->X, A,
-                       plan->max_workers);
+    unsigned int *next_cnt;
+    const ef::Scratch X = next_call(plan, &next_cnt);
+    hipLaunchKernelGGL(ef::k_server, grid, dim3(ef::THREADS), 0, s, plan->L, X, A, plan->max_workers);
     EF_HIP(hipGetLastError());
-    hipLaunchKernelGGL(ef::k_residual_pass2, grid, dim3(ef::THREADS), 0, s, plan->L, server_err,
-                       (int64_t)0, (const float *)out_scales);
+    if (plan->n_static) {
+        hipLaunchKernelGGL(ef::k_residual_static, dim3(plan->n_static, 1u), dim3(ef::THREADS), 0, s, plan->L,
+                           (const uint32_t *)plan->d_static, server_err, (int64_t)0, (const float *)out_scales);
+        EF_HIP(hipGetLastError());
+    }
+    hipLaunchKernelGGL(ef::k_residual_deferred, dim3(ef::DEFER_WGS), dim3(ef::THREADS), 0, s, plan->L,
+                       (const unsigned int *)X.defer_cnt, next_cnt, (const unsigned long long *)X.defer_list,
+                       plan->max_workers, server_err, (int64_t)0, (const float *)out_scales);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }

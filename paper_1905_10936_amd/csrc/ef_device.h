@@ -1,6 +1,6 @@
 // Device side of libef: tile-based kernels for the worker, server and apply
 // steps of Algorithm 4 (dist-EF-blockSGDM, arxiv 1905.10936), written for
-// gfx950 (64-lane wavefronts, 256 CUs, HBM-bound streaming passes).
+// gfx950 (64-lane wavefronts, 256 CUs in 8 XCDs, HBM-bound streaming passes).
 //
 // Work decomposition
 // ------------------
@@ -16,13 +16,23 @@
 // The blocks of the partition (Section 3.2) cut a tile into segments.  A
 // segment whose block lies entirely inside the tile is "closed": its L1 norm,
 // scale and residual are finished by the tile alone.  At most two segments of
-// a tile are "open" (the block continues into a neighbouring tile): their fp64
+// a tile are "open" (the block continues into a neighbouring tile).  Their fp64
 // partial sums go to a per-(tile, slot) scratch word, an arrival counter per
-// block is bumped, and the workgroup that arrives last adds the partials in a
-// fixed order (so the scale does not depend on which workgroup that was) and
-// writes the block's scale.  Elements of open segments have their corrected
-// value p parked in the residual buffer; a second pass subtracts the decoded
-// value once the scale exists.
+// block is bumped, and the workgroup that arrives last adds the partials in
+// ascending tile order (so the scale does not depend on which workgroup that
+// was), writes the block's scale and posts it in a per-block "ready" word.
+//
+// One pass over the state
+// -----------------------
+// e <- p - Delta needs the block's scale, i.e. every tile of the block.  For a
+// block of at most `fuse_limit` tiles the workgroups keep p in registers, wait
+// (bounded) for the ready word and write the finished residual, so every fp32
+// tensor is read once and written once.  The wait cannot starve: all partials
+// of a tile are published before its first wait, workgroups are dispatched in
+// grid order, and fuse_limit keeps a block's tiles well inside what is resident
+// at once.  Should a wait still run out of its spin budget, or for blocks
+// larger than fuse_limit, the workgroup parks p in the residual buffer instead
+// and a second, short kernel subtracts the decoded value there.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -35,20 +45,28 @@ constexpr int NWAVES = THREADS / 64;
 constexpr int SUBROWS = 4;      // float4 per thread
 constexpr int SMALL_SEG = 64;   // segments up to this length are summed by one thread
 constexpr int MAX_LONG = TILE / SMALL_SEG;
+constexpr int DEFER_WGS = 64;   // workgroups of the kernel that finishes deferred segments
 
 struct Layout {
     int64_t d;                  // elements
     int64_t B;                  // blocks
     int64_t W;                  // sign words
     int32_t ntiles;
+    int32_t fuse_limit;         // blocks of up to this many tiles finish in one pass
     const int64_t *offs;        // [B+1] device copy of block_offsets
     const int32_t *tile_fb;     // [ntiles] block holding the tile's first element
     const int32_t *tile_lb;     // [ntiles] block holding the tile's last valid element
 };
 
-struct Scratch {                // one set per worker (+1 for the server)
+// Scratch of one call.  A "set" is one worker, or the server.
+struct Scratch {
     unsigned long long *part;   // [nsets][2*ntiles] fp64 partial sums of open segments (bit patterns)
     unsigned int *cnt;          // [nsets][B] arrivals per block, 0 between calls
+    unsigned long long *ready;  // [nsets][B] (epoch << 32) | scale bits, posted by the last arriver
+    unsigned int *defer_cnt;    // entries in defer_list for this call
+    unsigned long long *defer_list;  // (set << 33) | (tile << 1) | slot
+    unsigned int epoch;         // differs from every earlier call on this plan
+    int spin_limit;             // polls before a waiting workgroup gives up and parks p
 };
 
 struct WorkerArgs {
@@ -115,6 +133,8 @@ __device__ __forceinline__ double block_sum(double v, double *red)
 
 // value the payload stands for: +s if bit else -s (negation is exact)
 __device__ __forceinline__ float signed_scale(float s, bool plus) { return plus ? s : -s; }
+// e' = p - Delta for one element whose block has scale s
+__device__ __forceinline__ float residual(float p, float s) { return p - signed_scale(s, p >= 0.f); }
 
 // Pack the signs of this thread's 16 values into the wavefront's 16 sign words
 // and store them.  nib[k] holds the 4 sign bits of sub-row k (bit c = element c).
@@ -144,16 +164,57 @@ __device__ __forceinline__ void pack_and_store_signs(const unsigned nib[SUBROWS]
     }
 }
 
+struct TileShared {
+    float val[TILE];            // |p| per element, then the element's scale (closed segments)
+    double red[NWAVES];
+    double open_sum[2];
+    int long_list[MAX_LONG];
+    int n_long;
+    int flag[2];
+};
+
+// Per-call view of one set's scratch and outputs.
+struct SetCtx {
+    unsigned long long *part;   // [2*ntiles]
+    unsigned int *cnt;          // [B]
+    unsigned long long *ready;  // [B]
+    unsigned int *defer_cnt;
+    unsigned long long *defer_list;
+    unsigned int epoch;
+    int spin_limit;
+    int set;
+    float *scales_out;          // [B]
+};
+
+__device__ __forceinline__ SetCtx make_ctx(const Scratch &X, const Layout &L, int set, float *scales_out)
+{
+    SetCtx c;
+    c.part = X.part + (int64_t)set * 2 * L.ntiles;
+    c.cnt = X.cnt + (int64_t)set * L.B;
+    c.ready = X.ready + (int64_t)set * L.B;
+    c.defer_cnt = X.defer_cnt;
+    c.defer_list = X.defer_list;
+    c.epoch = X.epoch;
+    c.spin_limit = X.spin_limit;
+    c.set = set;
+    c.scales_out = scales_out;
+    return c;
+}
+
 // ------------------------------------------ cross-tile block reductions ---
+
+__device__ __forceinline__ int block_tiles(const Layout &L, int64_t b)
+{
+    return (int)((L.offs[b + 1] - 1) / TILE - L.offs[b] / TILE + 1);
+}
 
 // Called by every thread of the workgroup with the same arguments.  Publishes
 // the partial sum of an open segment of block b and, in the workgroup that
-// arrives last, adds all partials of b in ascending tile order and writes the
-// scale.  slot: 0 = the tile's first (or only) segment, 1 = its last segment.
+// arrives last, adds all partials of b in ascending tile order, writes the
+// scale and posts it.  slot: 0 = the tile's first (or only) segment, 1 = its
+// last segment.  Never waits for another workgroup.
 __device__ __forceinline__ void publish_open_segment(double partial, int which, int32_t tile, int64_t b,
-                                                     const Layout &L, unsigned long long *part,
-                                                     unsigned int *cnt, float *scales_out,
-                                                     double *red, int *flag)
+                                                     const Layout &L, const SetCtx &C, TileShared &S)
 {
     const int64_t bs = L.offs[b], be = L.offs[b + 1];
     const int64_t t0 = bs / TILE, t1 = (be - 1) / TILE;
@@ -166,47 +227,75 @@ __device__ __forceinline__ void publish_open_segment(double partial, int which, 
         // would order them too, but it writes back the whole L2 of streaming
         // stores on every tile.)
         unsigned long long old =
-            __hip_atomic_exchange(part + 2 * (int64_t)tile + which, (unsigned long long)__double_as_longlong(partial),
+            __hip_atomic_exchange(C.part + 2 * (int64_t)tile + which, (unsigned long long)__double_as_longlong(partial),
                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned inc = 1u;
         asm volatile("" : "+v"(inc) : "v"((unsigned)old), "v"((unsigned)(old >> 32)) : "memory");
-        unsigned prev = __hip_atomic_fetch_add(cnt + b, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = (prev + 1u == (unsigned)(t1 - t0 + 1)) ? 1 : 0;
+        unsigned prev = __hip_atomic_fetch_add(C.cnt + b, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        S.flag[0] = (prev + 1u == (unsigned)(t1 - t0 + 1)) ? 1 : 0;
     }
     __syncthreads();
-    const int last = *flag;
+    const int last = S.flag[0];
     __syncthreads();
     if (!last) return;
     const int first_slot = (bs % TILE != 0) ? 1 : 0;   // b is the last segment of tile t0 unless it starts there
     double acc = 0.0;
     for (int64_t t = t0 + threadIdx.x; t <= t1; t += THREADS) {
         const int sl = (t == t0) ? first_slot : 0;
-        unsigned long long bits = __hip_atomic_load(part + 2 * t + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long bits = __hip_atomic_load(C.part + 2 * t + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         acc += __longlong_as_double((long long)bits);
     }
-    const double total = block_sum(acc, red);
+    const double total = block_sum(acc, S.red);
     if (threadIdx.x == 0) {
-        scales_out[b] = (float)(total / (double)(be - bs));
-        __hip_atomic_store(cnt + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float s = (float)(total / (double)(be - bs));
+        C.scales_out[b] = s;
+        __hip_atomic_store(C.cnt + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(C.ready + b, ((unsigned long long)C.epoch << 32) | (unsigned long long)__float_as_uint(s),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-struct TileShared {
-    float val[TILE];            // |p| per element, then the element's scale (closed segments)
-    double red[NWAVES];
-    double open_sum[2];
-    int long_list[MAX_LONG];
-    int n_long;
-    int flag;
-};
+// Wait (bounded) until block b's scale of this call has been posted.  Called by
+// every thread of the workgroup; returns the same answer to all of them.
+__device__ __forceinline__ bool wait_scale(int64_t b, const SetCtx &C, TileShared &S, float *s)
+{
+    if (threadIdx.x == 0) {
+        int found = 0;
+        unsigned bits = 0;
+        for (int it = 0; it < C.spin_limit; ++it) {
+            unsigned long long w = __hip_atomic_load(C.ready + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((unsigned)(w >> 32) == C.epoch) {
+                found = 1;
+                bits = (unsigned)w;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        S.flag[0] = found;
+        S.flag[1] = (int)bits;
+    }
+    __syncthreads();
+    const bool ok = S.flag[0] != 0;
+    *s = __uint_as_float((unsigned)S.flag[1]);
+    __syncthreads();
+    return ok;
+}
+
+// Leave an open segment whose p was parked in the residual buffer to the
+// kernel that runs after this one.
+__device__ __forceinline__ void defer_segment(int32_t tile, int which, const SetCtx &C)
+{
+    if (threadIdx.x == 0) {
+        unsigned i = atomicAdd(C.defer_cnt, 1u);
+        C.defer_list[i] = ((unsigned long long)C.set << 33) | ((unsigned long long)tile << 1) | (unsigned)which;
+    }
+}
 
 // Compress the tile whose corrected values are in p[][] (Section 3.2): sign
-// words, block sums, scales of closed blocks, residual e' = p - Delta for closed
-// segments, p itself for open ones (finished by k_residual_pass2).
+// words, block sums, scales, and the residual e' = p - Delta (Algorithm 4).
 template <bool FULL>
 __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
-                                              uint64_t *signs, float *scales_out, float *err_tile,
-                                              unsigned long long *part, unsigned int *cnt, TileShared &S)
+                                              uint64_t *signs, float *err_tile, const SetCtx &C, TileShared &S)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
@@ -241,22 +330,28 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
         const double total = block_sum(acc, S.red);
         const int64_t bs = L.offs[fb], be = L.offs[fb + 1];
         const bool closed = (bs >= tile_start) && (be <= tile_start + TILE);
+        float s = 0.f;
+        bool have_scale = closed;
         if (closed) {
-            const float s = (float)(total / (double)(be - bs));
-            if (threadIdx.x == 0) scales_out[fb] = s;
-#pragma unroll
-            for (int k = 0; k < SUBROWS; ++k) {
-                float4 e;
-                e.x = p[k].x - signed_scale(s, p[k].x >= 0.f);
-                e.y = p[k].y - signed_scale(s, p[k].y >= 0.f);
-                e.z = p[k].z - signed_scale(s, p[k].z >= 0.f);
-                e.w = p[k].w - signed_scale(s, p[k].w >= 0.f);
-                store4<FULL>(err_tile, local_base(k), n_valid, e);
-            }
+            s = (float)(total / (double)(be - bs));
+            if (threadIdx.x == 0) C.scales_out[fb] = s;
         } else {
+            publish_open_segment(total, 0, tile, fb, L, C, S);
+            if (block_tiles(L, fb) <= L.fuse_limit) {
+                have_scale = wait_scale(fb, C, S, &s);
+                if (!have_scale) defer_segment(tile, 0, C);
+            }
+        }
 #pragma unroll
-            for (int k = 0; k < SUBROWS; ++k) store4<FULL>(err_tile, local_base(k), n_valid, p[k]);
-            publish_open_segment(total, 0, tile, fb, L, part, cnt, scales_out, S.red, &S.flag);
+        for (int k = 0; k < SUBROWS; ++k) {
+            float4 e = p[k];
+            if (have_scale) {
+                e.x = residual(p[k].x, s);
+                e.y = residual(p[k].y, s);
+                e.z = residual(p[k].z, s);
+                e.w = residual(p[k].w, s);
+            }
+            store4<FULL>(err_tile, local_base(k), n_valid, e);
         }
         return;
     }
@@ -272,49 +367,63 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
     __syncthreads();
     const bool head_open = L.offs[fb] < tile_start;
     const bool tail_open = L.offs[lb + 1] > tile_start + TILE;
-    for (int s = threadIdx.x; s < nseg; s += THREADS) {
-        const int64_t b = fb + s;
+    for (int sg = threadIdx.x; sg < nseg; sg += THREADS) {
+        const int64_t b = fb + sg;
         const int64_t bs = L.offs[b], be = L.offs[b + 1];
         const int lo = (int)max(bs - tile_start, (int64_t)0);
         const int hi = (int)min(be - tile_start, (int64_t)n_valid);
         if (hi - lo > SMALL_SEG) {
-            S.long_list[atomicAdd(&S.n_long, 1)] = s;
+            S.long_list[atomicAdd(&S.n_long, 1)] = sg;
             continue;
         }
         double acc = 0.0;
         for (int j = lo; j < hi; ++j) acc += (double)S.val[j];
-        const bool open = (s == 0 && head_open) || (s == nseg - 1 && tail_open);
+        const bool open = (sg == 0 && head_open) || (sg == nseg - 1 && tail_open);
         if (open) {
-            S.open_sum[s == 0 ? 0 : 1] = acc;
+            S.open_sum[sg == 0 ? 0 : 1] = acc;
         } else {
             const float sc = (float)(acc / (double)(be - bs));
-            scales_out[b] = sc;
+            C.scales_out[b] = sc;
             for (int j = lo; j < hi; ++j) S.val[j] = sc;
         }
     }
     __syncthreads();
     const int n_long = S.n_long;
     for (int q = wave_id(); q < n_long; q += NWAVES) {
-        const int s = S.long_list[q];
-        const int64_t b = fb + s;
+        const int sg = S.long_list[q];
+        const int64_t b = fb + sg;
         const int64_t bs = L.offs[b], be = L.offs[b + 1];
         const int lo = (int)max(bs - tile_start, (int64_t)0);
         const int hi = (int)min(be - tile_start, (int64_t)n_valid);
         double acc = 0.0;
         for (int j = lo + lane_id(); j < hi; j += 64) acc += (double)S.val[j];
         acc = wave_sum(acc);
-        const bool open = (s == 0 && head_open) || (s == nseg - 1 && tail_open);
+        const bool open = (sg == 0 && head_open) || (sg == nseg - 1 && tail_open);
         if (open) {
-            if (lane_id() == 0) S.open_sum[s == 0 ? 0 : 1] = acc;
+            if (lane_id() == 0) S.open_sum[sg == 0 ? 0 : 1] = acc;
         } else {
             const float sc = (float)(acc / (double)(be - bs));
-            if (lane_id() == 0) scales_out[b] = sc;
+            if (lane_id() == 0) C.scales_out[b] = sc;
             for (int j = lo + lane_id(); j < hi; j += 64) S.val[j] = sc;
         }
     }
     __syncthreads();
     const int head_end = head_open ? (int)min(L.offs[fb + 1] - tile_start, (int64_t)n_valid) : 0;
     const int tail_begin = tail_open ? (int)(L.offs[lb] - tile_start) : TILE;
+    // publish everything this tile owes to others before waiting for anything
+    const double head_sum = S.open_sum[0], tail_sum = S.open_sum[1];
+    if (head_open) publish_open_segment(head_sum, 0, tile, fb, L, C, S);
+    if (tail_open) publish_open_segment(tail_sum, 1, tile, lb, L, C, S);
+    float s_head = 0.f, s_tail = 0.f;
+    bool have_head = false, have_tail = false;
+    if (head_open && block_tiles(L, fb) <= L.fuse_limit) {
+        have_head = wait_scale(fb, C, S, &s_head);
+        if (!have_head) defer_segment(tile, 0, C);
+    }
+    if (tail_open && block_tiles(L, lb) <= L.fuse_limit) {
+        have_tail = wait_scale(lb, C, S, &s_tail);
+        if (!have_tail) defer_segment(tile, 1, C);
+    }
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         const int lb0 = local_base(k);
@@ -325,13 +434,12 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int j = lb0 + c;
-            const bool is_open = (j < head_end) || (j >= tail_begin);
-            ev[c] = is_open ? pv[c] : pv[c] - signed_scale(sv[c], pv[c] >= 0.f);
+            if (j < head_end) ev[c] = have_head ? residual(pv[c], s_head) : pv[c];
+            else if (j >= tail_begin) ev[c] = have_tail ? residual(pv[c], s_tail) : pv[c];
+            else ev[c] = residual(pv[c], sv[c]);
         }
         store4<FULL>(err_tile, lb0, n_valid, make_float4(ev[0], ev[1], ev[2], ev[3]));
     }
-    if (head_open) publish_open_segment(S.open_sum[0], 0, tile, fb, L, part, cnt, scales_out, S.red, &S.flag);
-    if (tail_open) publish_open_segment(S.open_sum[1], 1, tile, lb, L, part, cnt, scales_out, S.red, &S.flag);
 }
 
 // Fill S.val (read as int) with the segment index of every element of a tile
@@ -343,30 +451,30 @@ __device__ __forceinline__ void build_segment_index(const Layout &L, int32_t til
     int *seg = reinterpret_cast<int *>(S.val);
     if (threadIdx.x == 0) S.n_long = 0;
     __syncthreads();
-    for (int s = threadIdx.x; s < nseg; s += THREADS) {
-        const int lo = (int)max(L.offs[fb + s] - tile_start, (int64_t)0);
-        const int hi = (int)min(L.offs[fb + s + 1] - tile_start, (int64_t)n_valid);
+    for (int sg = threadIdx.x; sg < nseg; sg += THREADS) {
+        const int lo = (int)max(L.offs[fb + sg] - tile_start, (int64_t)0);
+        const int hi = (int)min(L.offs[fb + sg + 1] - tile_start, (int64_t)n_valid);
         if (hi - lo > SMALL_SEG) {
-            S.long_list[atomicAdd(&S.n_long, 1)] = s;
+            S.long_list[atomicAdd(&S.n_long, 1)] = sg;
             continue;
         }
-        for (int j = lo; j < hi; ++j) seg[j] = s;
+        for (int j = lo; j < hi; ++j) seg[j] = sg;
     }
     __syncthreads();
     const int n_long = S.n_long;
     for (int q = wave_id(); q < n_long; q += NWAVES) {
-        const int s = S.long_list[q];
-        const int lo = (int)max(L.offs[fb + s] - tile_start, (int64_t)0);
-        const int hi = (int)min(L.offs[fb + s + 1] - tile_start, (int64_t)n_valid);
-        for (int j = lo + lane_id(); j < hi; j += 64) seg[j] = s;
+        const int sg = S.long_list[q];
+        const int lo = (int)max(L.offs[fb + sg] - tile_start, (int64_t)0);
+        const int hi = (int)min(L.offs[fb + sg + 1] - tile_start, (int64_t)n_valid);
+        for (int j = lo + lane_id(); j < hi; j += 64) seg[j] = sg;
     }
     __syncthreads();
 }
 
 // ------------------------------------------------------------- kernels ---
 
-// Worker, first pass (Algorithm 4, "on each worker i"): momentum, corrected
-// value p, sign words, block sums; see compress_tile for what is left open.
+// Worker (Algorithm 4, "on each worker i"): momentum, corrected value p, sign
+// words, block scales, residual.
 template <bool FULL>
 __device__ __forceinline__ void worker_tile(const Layout &L, const Scratch &X, const WorkerArgs &A, int32_t tile,
                                             int worker, int n_valid, TileShared &S)
@@ -397,11 +505,11 @@ __device__ __forceinline__ void worker_tile(const Layout &L, const Scratch &X, c
         p[k].z = (mu * mn.z + gv[k].z) + r * ev[k].z;
         p[k].w = (mu * mn.w + gv[k].w) + r * ev[k].w;
     }
-    compress_tile<FULL>(p, L, tile, n_valid, A.signs + (int64_t)worker * L.W, A.scales + (int64_t)worker * L.B, e,
-                        X.part + (int64_t)worker * 2 * L.ntiles, X.cnt + (int64_t)worker * L.B, S);
+    const SetCtx C = make_ctx(X, L, worker, A.scales + (int64_t)worker * L.B);
+    compress_tile<FULL>(p, L, tile, n_valid, A.signs + (int64_t)worker * L.W, e, C, S);
 }
 
-__global__ __launch_bounds__(THREADS) void k_worker_pass1(Layout L, Scratch X, WorkerArgs A)
+__global__ __launch_bounds__(THREADS) void k_worker(Layout L, Scratch X, WorkerArgs A)
 {
     __shared__ TileShared S;
     const int32_t tile = blockIdx.x;
@@ -411,8 +519,8 @@ __global__ __launch_bounds__(THREADS) void k_worker_pass1(Layout L, Scratch X, W
     else worker_tile<false>(L, X, A, tile, worker, (int)left, S);
 }
 
-// Server, first pass (Algorithm 4, "on server"): decode and add the M payloads
-// in worker order, divide by M, add the rescaled server residual, compress.
+// Server (Algorithm 4, "on server"): decode and add the M payloads in worker
+// order, divide by M, add the rescaled server residual, compress.
 template <bool FULL>
 __device__ __forceinline__ void server_tile(const Layout &L, const Scratch &X, const ServerArgs &A, int32_t tile,
                                             int set, int n_valid, TileShared &S)
@@ -474,11 +582,11 @@ __device__ __forceinline__ void server_tile(const Layout &L, const Scratch &X, c
         p[k].z = acc[k][2] / Mf + r * tv[k].z;
         p[k].w = acc[k][3] / Mf + r * tv[k].w;
     }
-    compress_tile<FULL>(p, L, tile, n_valid, A.signs, A.scales, te, X.part + (int64_t)set * 2 * L.ntiles,
-                        X.cnt + (int64_t)set * L.B, S);
+    const SetCtx C = make_ctx(X, L, set, A.scales);
+    compress_tile<FULL>(p, L, tile, n_valid, A.signs, te, C, S);
 }
 
-__global__ __launch_bounds__(THREADS) void k_server_pass1(Layout L, Scratch X, ServerArgs A, int set)
+__global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerArgs A, int set)
 {
     __shared__ TileShared S;
     const int32_t tile = blockIdx.x;
@@ -487,59 +595,78 @@ __global__ __launch_bounds__(THREADS) void k_server_pass1(Layout L, Scratch X, S
     else server_tile<false>(L, X, A, tile, set, (int)left, S);
 }
 
-// Second pass of worker and server: e <- p - Delta on the open segments of each
-// tile (e_{t+1} = p_t - Delta_t of Algorithm 4), now that every scale exists.
-// err holds p there; the sign is taken from p itself.
-template <bool FULL>
-__device__ __forceinline__ void residual_tile(const Layout &L, int32_t tile, int n_valid, float *err_tile,
-                                              const float *scales)
+// e <- p - Delta on one open segment of a tile whose p was parked in the
+// residual buffer (e_{t+1} = p_t - Delta_t of Algorithm 4), now that every scale
+// exists.  The sign is taken from p itself.  which: 0 = first (or only)
+// segment of the tile, 1 = last segment.
+__device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, int which, float *err_set,
+                                                 const float *scales)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
+    const int64_t left = L.d - tile_start;
+    const int n_valid = left >= TILE ? TILE : (int)left;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
-    int head_end = 0, tail_begin = TILE;
-    float sh = 0.f, st = 0.f;
-    if (fb == lb) {
-        const bool open = (L.offs[fb] < tile_start) || (L.offs[fb + 1] > tile_start + TILE);
-        if (open) { head_end = n_valid; sh = scales[fb]; }
+    float *err_tile = err_set + tile_start;
+    int lo, hi;
+    float s;
+    if (which == 0) {
+        lo = 0;
+        hi = (int)min(L.offs[fb + 1] - tile_start, (int64_t)n_valid);
+        s = scales[fb];
     } else {
-        if (L.offs[fb] < tile_start) {
-            head_end = (int)min(L.offs[fb + 1] - tile_start, (int64_t)n_valid);
-            sh = scales[fb];
-        }
-        if (L.offs[lb + 1] > tile_start + TILE) {
-            tail_begin = (int)(L.offs[lb] - tile_start);
-            st = scales[lb];
-        }
+        lo = (int)(L.offs[lb] - tile_start);
+        hi = n_valid;
+        s = scales[lb];
     }
-    if (head_end == 0 && tail_begin == TILE) return;
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         const int lb0 = local_base(k);
-        if (lb0 >= n_valid) continue;
-        if (lb0 >= head_end && lb0 + 3 < tail_begin) continue;
-        const float4 v = load4<FULL>(err_tile, lb0, n_valid);
-        float pv[4] = {v.x, v.y, v.z, v.w};
+        if (lb0 >= hi || lb0 + 4 <= lo) continue;
+        if (lb0 >= lo && lb0 + 4 <= hi) {
+            float4 v = *reinterpret_cast<const float4 *>(err_tile + lb0);
+            v.x = residual(v.x, s);
+            v.y = residual(v.y, s);
+            v.z = residual(v.z, s);
+            v.w = residual(v.w, s);
+            *reinterpret_cast<float4 *>(err_tile + lb0) = v;
+        } else {
+            // the other elements of this float4 belong to another segment, which
+            // another workgroup may be updating right now: touch only our own
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int j = lb0 + c;
-            if (j < head_end) pv[c] = pv[c] - signed_scale(sh, pv[c] >= 0.f);
-            else if (j >= tail_begin) pv[c] = pv[c] - signed_scale(st, pv[c] >= 0.f);
+            for (int c = 0; c < 4; ++c) {
+                const int j = lb0 + c;
+                if (j >= lo && j < hi) err_tile[j] = residual(err_tile[j], s);
+            }
         }
-        store4<FULL>(err_tile, lb0, n_valid, make_float4(pv[0], pv[1], pv[2], pv[3]));
     }
 }
 
-__global__ __launch_bounds__(THREADS) void k_residual_pass2(Layout L, float *err, int64_t err_stride,
-                                                            const float *scales)
+// Second pass over the open segments of blocks larger than fuse_limit: the
+// list (tile << 1 | slot) is fixed per layout and built with the plan.
+__global__ __launch_bounds__(THREADS) void k_residual_static(Layout L, const uint32_t *items, float *err,
+                                                             int64_t err_stride, const float *scales)
 {
-    const int32_t tile = blockIdx.x;
+    const uint32_t it = items[blockIdx.x];
     const int w = blockIdx.y;
-    const int64_t tile_start = (int64_t)tile * TILE;
-    const int64_t left = L.d - tile_start;
-    float *e = err + (int64_t)w * err_stride + tile_start;
-    const float *sc = scales + (int64_t)w * L.B;
-    if (left >= TILE) residual_tile<true>(L, tile, TILE, e, sc);
-    else residual_tile<false>(L, tile, (int)left, e, sc);
+    residual_segment(L, (int32_t)(it >> 1), (int)(it & 1u), err + (int64_t)w * err_stride, scales + (int64_t)w * L.B);
+}
+
+// Second pass over the segments whose wait ran out of its spin budget in the
+// first kernel of this call (normally none).  Also clears the counter the next
+// call will use.
+__global__ __launch_bounds__(THREADS) void k_residual_deferred(Layout L, const unsigned int *defer_cnt,
+                                                               unsigned int *next_defer_cnt,
+                                                               const unsigned long long *defer_list, int set_base,
+                                                               float *err, int64_t err_stride, const float *scales)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *next_defer_cnt = 0u;
+    const unsigned n = *defer_cnt;
+    for (unsigned i = blockIdx.x; i < n; i += gridDim.x) {
+        const unsigned long long it = defer_list[i];
+        const int w = (int)(it >> 33) - set_base;
+        const int32_t tile = (int32_t)((it >> 1) & 0xffffffffull);
+        residual_segment(L, tile, (int)(it & 1ull), err + (int64_t)w * err_stride, scales + (int64_t)w * L.B);
+    }
 }
 
 // Parameter update x <- x - eta * Delta~ (Algorithm 4).

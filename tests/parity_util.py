@@ -57,13 +57,22 @@ def check_vector(gpu, cpu, scales_cpu, same_scale, offs, what):
 class GpuState:
     """Device tensors of M workers + server + parameters for one layout."""
 
-    def __init__(self, offs, M, device="cuda", x0=None, pad=0):
+    def __init__(self, offs, M, device="cuda", x0=None, pad=0, route="one_pass"):
         self.offs = np.asarray(offs, dtype=np.int64)
         self.d = int(self.offs[-1])
         self.B = self.offs.size - 1
         self.M = M
         self.W = (self.d + 63) // 64
         self.plan = ef.ef_plan_create(self.offs, max(M, 1))
+        # which way e <- p - Delta is finished for blocks that span several tiles
+        if route == "two_pass":          # every such block through the second kernel
+            self.plan.tune(fuse_limit=0)
+        elif route == "deferred":        # every wait gives up at once -> deferral list
+            self.plan.tune(spin_limit=0)
+        elif route == "mixed":           # blocks of <= 2 tiles in one pass, larger ones in two
+            self.plan.tune(fuse_limit=2)
+        elif route != "one_pass":
+            raise ValueError(route)
         ds = ((self.d + 3) // 4) * 4 + 4 * pad           # row stride, multiple of 4
         self.stride = ds
         dev = torch.device(device)

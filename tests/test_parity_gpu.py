@@ -59,14 +59,21 @@ def _grads(rng, T, M, d, zeros=0.0, scale=1.0):
     return g
 
 
+ROUTES = ["one_pass", "two_pass", "deferred", "mixed"]
+
+
+@pytest.mark.parametrize("route", ROUTES)
 @pytest.mark.parametrize("name", list(LAYOUTS))
-def test_step_parity_small_layouts(name):
+def test_step_parity_small_layouts(name, route):
+    """Every layout through every route by which the residual of a block that
+    spans several tiles can be finished (in-kernel wait, second kernel for
+    large blocks, deferral after a wait that gave up): same bits each way."""
     offs = _offs(LAYOUTS[name])
     d = int(offs[-1])
     M, T = 3, 3
     rng = np.random.default_rng(zlib.crc32(name.encode()))
     g = _grads(rng, T, M, d, zeros=0.05)
-    st = GpuState(offs, M, x0=rng.standard_normal(d).astype(F))
+    st = GpuState(offs, M, x0=rng.standard_normal(d).astype(F), route=route)
     etas = [0.1, 0.1, 0.05]
     eta_prev = 0.0
     stats = {}
@@ -82,7 +89,7 @@ def test_server_worker_counts(M):
     offs = _offs(LAYOUTS["mixed_tiny_and_big"])
     d = int(offs[-1])
     rng = np.random.default_rng(M)
-    st = GpuState(offs, M)
+    st = GpuState(offs, M, route=ROUTES[M % 4])
     eta_prev = 0.0
     for t in range(2):
         st.set_grads(_grads(rng, 1, M, d)[0])
