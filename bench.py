@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--grad-sets", type=int, default=0, help="distinct gradient sets kept in HBM (0 = auto)")
     ap.add_argument("--cpu-blocks", type=int, default=0, help="blocks in the CPU oracle sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--fuse-limit", type=int, default=-1, help="override the plan's one-pass block limit")
+    ap.add_argument("--spin-limit", type=int, default=-1, help="override the plan's wait budget")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs M simulated workers and the server on ONE GPU; "
@@ -85,6 +87,8 @@ def main():
     d, B, M = w.d, w.B, w.M
     W = (d + 63) // 64
     plan = ef.ef_plan_create(w.offsets, M)
+    if args.fuse_limit >= 0 or args.spin_limit >= 0:
+        plan.tune(args.fuse_limit, args.spin_limit)
 
     # gradient sets resident in HBM, cycled over the steps
     n_sets = args.grad_sets or max(1, min(args.steps + args.warmup, int(64e9 // (4.0 * d * M)), 4))

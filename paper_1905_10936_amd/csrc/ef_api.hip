@@ -15,10 +15,12 @@ struct ef_plan {
     int max_workers;
     int device;
     int spin_limit;
-    unsigned int epoch;             // last epoch handed to a call
+    unsigned int calls;             // calls issued so far; its parity picks the list counters
+    std::vector<uint8_t> set_tag;   // tag the last call that used a set gave its partial words
     std::vector<int64_t> offs_host;
     std::vector<int32_t> fb_host, lb_host;
     uint32_t n_static;              // open segments of blocks larger than fuse_limit
+    uint32_t n_big;                 // those blocks
     // device allocations owned by the plan
     int64_t *d_offs;
     int32_t *d_tile_fb;
@@ -26,9 +28,11 @@ struct ef_plan {
     unsigned long long *d_part;
     unsigned int *d_cnt;
     unsigned long long *d_ready;
-    unsigned int *d_defer_cnt;      // [2], alternating between calls
+    unsigned int *d_list_cnt;       // [4]: defer_cnt[2], fin_cnt[2], alternating between calls
     unsigned long long *d_defer_list;
+    unsigned long long *d_fin_list;
     uint32_t *d_static;             // [2*ntiles] capacity
+    int32_t *d_big;                 // [min(B, 2*ntiles)] capacity
 };
 
 namespace {
@@ -75,9 +79,11 @@ void destroy_device(ef_plan *p)
     if (p->d_part) (void)hipFree(p->d_part);
     if (p->d_cnt) (void)hipFree(p->d_cnt);
     if (p->d_ready) (void)hipFree(p->d_ready);
-    if (p->d_defer_cnt) (void)hipFree(p->d_defer_cnt);
+    if (p->d_list_cnt) (void)hipFree(p->d_list_cnt);
     if (p->d_defer_list) (void)hipFree(p->d_defer_list);
+    if (p->d_fin_list) (void)hipFree(p->d_fin_list);
     if (p->d_static) (void)hipFree(p->d_static);
+    if (p->d_big) (void)hipFree(p->d_big);
 }
 
 int64_t tiles_of_block(const ef_plan *p, int64_t b)
@@ -86,12 +92,17 @@ int64_t tiles_of_block(const ef_plan *p, int64_t b)
     return (o[b + 1] - 1) / ef::TILE - o[b] / ef::TILE + 1;
 }
 
-// The open segments that the one-pass path leaves to the second kernel: those
-// of blocks spanning more than fuse_limit tiles.
+// What the one-pass path leaves to the later kernels: the blocks spanning more
+// than fuse_limit tiles and their (open) segments.
 int upload_static_list(ef_plan *p)
 {
     std::vector<uint32_t> items;
+    std::vector<int32_t> big;
     const int64_t *o = p->offs_host.data();
+    for (int64_t b = 0; b < p->L.B; ++b)
+        if (tiles_of_block(p, b) >= 2 && tiles_of_block(p, b) > p->L.fuse_limit) big.push_back((int32_t)b);
+    p->n_big = (uint32_t)big.size();
+    if (!big.empty()) EF_HIP(hipMemcpy(p->d_big, big.data(), sizeof(int32_t) * big.size(), hipMemcpyHostToDevice));
     for (int32_t t = 0; t < p->L.ntiles; ++t) {
         const int64_t start = (int64_t)t * ef::TILE, end = start + ef::TILE;
         const int32_t fb = p->fb_host[t], lb = p->lb_host[t];
@@ -134,18 +145,23 @@ int build_device(ef_plan *p)
     EF_HIP(hipMalloc(&p->d_tile_fb, sizeof(int32_t) * ntiles));
     EF_HIP(hipMalloc(&p->d_tile_lb, sizeof(int32_t) * ntiles));
     EF_HIP(hipMalloc(&p->d_part, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
-    EF_HIP(hipMalloc(&p->d_cnt, sizeof(unsigned int) * (size_t)B * nsets));
     EF_HIP(hipMemcpy(p->d_offs, p->offs_host.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice));
     EF_HIP(hipMemcpy(p->d_tile_fb, fb.data(), sizeof(int32_t) * ntiles, hipMemcpyHostToDevice));
     EF_HIP(hipMemcpy(p->d_tile_lb, lb.data(), sizeof(int32_t) * ntiles, hipMemcpyHostToDevice));
     EF_HIP(hipMemset(p->d_part, 0, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
-    EF_HIP(hipMemset(p->d_cnt, 0, sizeof(unsigned int) * (size_t)B * nsets));
+    // a block that crosses a tile boundary owns at least one of the 2*ntiles open segments
+    const size_t max_cross = (size_t)(2 * (int64_t)ntiles < B ? 2 * (int64_t)ntiles : B);
+    EF_HIP(hipMalloc(&p->d_cnt, sizeof(unsigned int) * (size_t)B * nsets));
     EF_HIP(hipMalloc(&p->d_ready, sizeof(unsigned long long) * (size_t)B * nsets));
-    EF_HIP(hipMalloc(&p->d_defer_cnt, sizeof(unsigned int) * 2));
-    EF_HIP(hipMalloc(&p->d_defer_list, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
-    EF_HIP(hipMalloc(&p->d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
+    EF_HIP(hipMemset(p->d_cnt, 0, sizeof(unsigned int) * (size_t)B * nsets));
     EF_HIP(hipMemset(p->d_ready, 0, sizeof(unsigned long long) * (size_t)B * nsets));
-    EF_HIP(hipMemset(p->d_defer_cnt, 0, sizeof(unsigned int) * 2));
+    EF_HIP(hipMalloc(&p->d_list_cnt, sizeof(unsigned int) * 4));
+    EF_HIP(hipMalloc(&p->d_defer_list, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
+    EF_HIP(hipMalloc(&p->d_fin_list, sizeof(unsigned long long) * max_cross * nsets));
+    EF_HIP(hipMalloc(&p->d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
+    EF_HIP(hipMalloc(&p->d_big, sizeof(int32_t) * max_cross));
+    EF_HIP(hipMemset(p->d_list_cnt, 0, sizeof(unsigned int) * 4));
+    p->set_tag.assign(nsets, 0);                 // the zeroed partial words carry tag 0
     p->L.offs = p->d_offs;
     p->L.tile_fb = p->d_tile_fb;
     p->L.tile_lb = p->d_tile_lb;
@@ -153,7 +169,7 @@ int build_device(ef_plan *p)
     p->X.cnt = p->d_cnt;
     p->X.ready = p->d_ready;
     p->X.defer_list = p->d_defer_list;
-    p->X.defer_cnt = p->d_defer_cnt;
+    p->X.fin_list = p->d_fin_list;
     // A block finishes in one pass if its tiles fit twice over into the
     // workgroups resident at once (see ef_device.h).
     {
@@ -165,28 +181,57 @@ int build_device(ef_plan *p)
         const int occ = occ_w < occ_s ? occ_w : occ_s;
         int64_t lim = (int64_t)prop.multiProcessorCount * occ / 2;
         if (lim < 1) lim = 1;
+        if (lim > ef::FUSE_LIMIT_MAX) lim = ef::FUSE_LIMIT_MAX;
         p->L.fuse_limit = (int32_t)lim;
     }
     p->spin_limit = 1 << 14;
-    p->epoch = 0;
+    p->calls = 0;
     int rc = upload_static_list(p);
     if (rc) return rc;
     EF_HIP(hipDeviceSynchronize());
     return EF_OK;
 }
 
-// Scratch view of one call: a fresh epoch and the deferral counter of its parity.
-ef::Scratch next_call(const ef_plan *plan_c, unsigned int **next_cnt)
+// Scratch view of one call over the sets [set_base, set_base + nsets): flips the
+// tag of every set it uses and picks the list counters of this call's parity.
+struct CallScratch {
+    ef::Scratch X;
+    unsigned int *next_defer_cnt, *next_fin_cnt;
+};
+
+CallScratch next_call(const ef_plan *plan_c, int set_base, int nsets)
 {
     ef_plan *plan = const_cast<ef_plan *>(plan_c);   // calls on one plan are ordered by contract
-    plan->epoch += 1;
-    if (plan->epoch == 0) plan->epoch = 2;           // keep the odd/even alternation across the wrap
-    ef::Scratch X = plan->X;
-    X.epoch = plan->epoch;
-    X.spin_limit = plan->spin_limit;
-    X.defer_cnt = plan->d_defer_cnt + (plan->epoch & 1u);
-    *next_cnt = plan->d_defer_cnt + ((plan->epoch + 1u) & 1u);
-    return X;
+    CallScratch c;
+    c.X = plan->X;
+    c.X.tags = 0;
+    for (int i = 0; i < nsets; ++i) {
+        plan->set_tag[set_base + i] ^= 1u;
+        c.X.tags |= (unsigned long long)plan->set_tag[set_base + i] << i;
+    }
+    c.X.set_base = set_base;
+    c.X.spin_limit = plan->spin_limit;
+    const unsigned cur = plan->calls & 1u, nxt = cur ^ 1u;
+    plan->calls += 1;
+    c.X.defer_cnt = plan->d_list_cnt + cur;
+    c.X.fin_cnt = plan->d_list_cnt + 2 + cur;
+    c.next_defer_cnt = plan->d_list_cnt + nxt;
+    c.next_fin_cnt = plan->d_list_cnt + 2 + nxt;
+    return c;
+}
+
+// The two short kernels after the main one: missing scales, then parked residuals.
+int launch_second_pass(const ef_plan *plan, const CallScratch &c, int nsets, float *err, int64_t err_stride,
+                       float *scales, hipStream_t s)
+{
+    hipLaunchKernelGGL(ef::k_finalize_scales, dim3(plan->n_big * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
+                       plan->L, c.X, (const int32_t *)plan->d_big, (int)plan->n_big, nsets, scales);
+    EF_HIP(hipGetLastError());
+    hipLaunchKernelGGL(ef::k_residual_parked, dim3(plan->n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
+                       plan->L, c.X, (const uint32_t *)plan->d_static, (int)plan->n_static, nsets, c.next_defer_cnt,
+                       c.next_fin_cnt, err, err_stride, (const float *)scales);
+    EF_HIP(hipGetLastError());
+    return EF_OK;
 }
 
 }  // namespace
@@ -216,10 +261,13 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_part = nullptr;
     p->d_cnt = nullptr;
     p->d_ready = nullptr;
-    p->d_defer_cnt = nullptr;
+    p->d_list_cnt = nullptr;
     p->d_defer_list = nullptr;
+    p->d_fin_list = nullptr;
     p->d_static = nullptr;
+    p->d_big = nullptr;
     p->n_static = 0;
+    p->n_big = 0;
     rc = build_device(p);
     if (rc) {
         destroy_device(p);
@@ -245,7 +293,7 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
     EF_HIP(hipDeviceSynchronize());
     if (spin_limit >= 0) plan->spin_limit = spin_limit;
     if (fuse_limit >= 0) {
-        plan->L.fuse_limit = fuse_limit;
+        plan->L.fuse_limit = fuse_limit > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : fuse_limit;
         int rc = upload_static_list(plan);
         if (rc) return rc;
     }
@@ -284,20 +332,10 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
     A.scales = scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)plan->L.ntiles, (unsigned)n_workers);
-    unsigned int *next_cnt;
-    const ef::Scratch X = next_call(plan, &next_cnt);
-    hipLaunchKernelGGL(ef::k_worker, grid, dim3(ef::THREADS), 0, s, plan->L, X, A);
+    const CallScratch c = next_call(plan, 0, n_workers);
+    hipLaunchKernelGGL(ef::k_worker, grid, dim3(ef::THREADS), 0, s, plan->L, c.X, A);
     EF_HIP(hipGetLastError());
-    if (plan->n_static) {
-        hipLaunchKernelGGL(ef::k_residual_static, dim3(plan->n_static, (unsigned)n_workers), dim3(ef::THREADS), 0, s,
-                           plan->L, (const uint32_t *)plan->d_static, err, state_stride, (const float *)scales);
-        EF_HIP(hipGetLastError());
-    }
-    hipLaunchKernelGGL(ef::k_residual_deferred, dim3(ef::DEFER_WGS), dim3(ef::THREADS), 0, s, plan->L,
-                       (const unsigned int *)X.defer_cnt, next_cnt, (const unsigned long long *)X.defer_list, 0, err,
-                       state_stride, (const float *)scales);
-    EF_HIP(hipGetLastError());
-    return EF_OK;
+    return launch_second_pass(plan, c, n_workers, err, state_stride, scales, s);
 }
 
 int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, const float *scales,
@@ -322,20 +360,10 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
     A.scales = out_scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)plan->L.ntiles, 1u);
-    unsigned int *next_cnt;
-    const ef::Scratch X = next_call(plan, &next_cnt);
-    hipLaunchKernelGGL(ef::k_server, grid, dim3(ef::THREADS), 0, s, plan->L, X, A, plan->max_workers);
+    const CallScratch c = next_call(plan, plan->max_workers, 1);
+    hipLaunchKernelGGL(ef::k_server, grid, dim3(ef::THREADS), 0, s, plan->L, c.X, A, plan->max_workers);
     EF_HIP(hipGetLastError());
-    if (plan->n_static) {
-        hipLaunchKernelGGL(ef::k_residual_static, dim3(plan->n_static, 1u), dim3(ef::THREADS), 0, s, plan->L,
-                           (const uint32_t *)plan->d_static, server_err, (int64_t)0, (const float *)out_scales);
-        EF_HIP(hipGetLastError());
-    }
-    hipLaunchKernelGGL(ef::k_residual_deferred, dim3(ef::DEFER_WGS), dim3(ef::THREADS), 0, s, plan->L,
-                       (const unsigned int *)X.defer_cnt, next_cnt, (const unsigned long long *)X.defer_list,
-                       plan->max_workers, server_err, (int64_t)0, (const float *)out_scales);
-    EF_HIP(hipGetLastError());
-    return EF_OK;
+    return launch_second_pass(plan, c, 1, server_err, (int64_t)0, out_scales, s);
 }
 
 int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, const float *scales, float eta,

@@ -17,22 +17,29 @@
 // segment whose block lies entirely inside the tile is "closed": its L1 norm,
 // scale and residual are finished by the tile alone.  At most two segments of
 // a tile are "open" (the block continues into a neighbouring tile).  Their fp64
-// partial sums go to a per-(tile, slot) scratch word, an arrival counter per
-// block is bumped, and the workgroup that arrives last adds the partials in
-// ascending tile order (so the scale does not depend on which workgroup that
-// was), writes the block's scale and posts it in a per-block "ready" word.
+// partial sums go to a per-(tile, slot) scratch word.  Whoever needs the
+// block's scale adds the block's partials in one fixed order (thread t takes
+// tiles t, t+256, ... in ascending order, then a fixed tree), so the scale has
+// the same bits wherever and whenever it is computed.
 //
 // One pass over the state
 // -----------------------
 // e <- p - Delta needs the block's scale, i.e. every tile of the block.  For a
-// block of at most `fuse_limit` tiles the workgroups keep p in registers, wait
-// (bounded) for the ready word and write the finished residual, so every fp32
-// tensor is read once and written once.  The wait cannot starve: all partials
-// of a tile are published before its first wait, workgroups are dispatched in
-// grid order, and fuse_limit keeps a block's tiles well inside what is resident
-// at once.  Should a wait still run out of its spin budget, or for blocks
-// larger than fuse_limit, the workgroup parks p in the residual buffer instead
-// and a second, short kernel subtracts the decoded value there.
+// block of at most `fuse_limit` tiles the workgroups keep p in registers, post
+// their partial and poll (bounded) the partial words of the block's other tiles
+// until all carry this call's tag, then write the finished residual, so every
+// fp32 tensor is read once and written once.  A partial is never negative, so
+// its sign bit is free to carry the tag, which flips on every call that uses
+// the scratch set: a word is "of this call" exactly when its tag matches, and
+// one relaxed agent-scope 64-bit store publishes value and tag together -- no
+// counters, no fences (an agent-scope release fence would write back the whole
+// L2 of streaming stores on every tile).  The wait cannot starve: all partials
+// of a tile are posted before its first wait, workgroups are dispatched in grid
+// order, and fuse_limit keeps a block's tiles well inside what is resident at
+// once.  Should a wait still run out of its spin budget, or for blocks larger
+// than fuse_limit, the workgroup parks p in the residual buffer instead; a small
+// kernel then computes the scales still missing and another subtracts the
+// decoded value where p was parked.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -60,12 +67,15 @@ struct Layout {
 
 // Scratch of one call.  A "set" is one worker, or the server.
 struct Scratch {
-    unsigned long long *part;   // [nsets][2*ntiles] fp64 partial sums of open segments (bit patterns)
-    unsigned int *cnt;          // [nsets][B] arrivals per block, 0 between calls
-    unsigned long long *ready;  // [nsets][B] (epoch << 32) | scale bits, posted by the last arriver
+    unsigned long long *part;   // [nsets][2*ntiles] tagged fp64 partial sums of open segments
+    unsigned int *cnt;          // [nsets][B] arrivals per one-pass block, 0 between calls
+    unsigned long long *ready;  // [nsets][B] (tag << 32) | scale bits, posted by the last arriver
     unsigned int *defer_cnt;    // entries in defer_list for this call
-    unsigned long long *defer_list;  // (set << 33) | (tile << 1) | slot
-    unsigned int epoch;         // differs from every earlier call on this plan
+    unsigned long long *defer_list;  // parked segments: (set << 33) | (tile << 1) | slot
+    unsigned int *fin_cnt;      // entries in fin_list for this call
+    unsigned long long *fin_list;    // blocks whose scale is still to be written: (set << 32) | block
+    unsigned long long tags;    // bit i = this call's tag of set (set_base + i)
+    int set_base;               // first set this call uses (0 for workers, max_workers for the server)
     int spin_limit;             // polls before a waiting workgroup gives up and parks p
 };
 
@@ -92,10 +102,27 @@ __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 // first local element of this thread's float4 in sub-row k
 __device__ __forceinline__ int local_base(int k) { return wave_id() * 1024 + k * 256 + lane_id() * 4; }
 
+// The fp32 state is streamed: each element is read once and written once per
+// call, so loads and stores carry the non-temporal hint and do not displace
+// the little that is reused (offsets, scales, partial sums) from the caches.
+typedef float vf4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 stream_load4(const float *p)
+{
+    const vf4 v = __builtin_nontemporal_load(reinterpret_cast<const vf4 *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ void stream_store4(float *p, float4 a)
+{
+    const vf4 v = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<vf4 *>(p));
+}
+
 template <bool FULL>
 __device__ __forceinline__ float4 load4(const float *base, int local, int n_valid)
 {
-    if (FULL || local + 4 <= n_valid) return *reinterpret_cast<const float4 *>(base + local);
+    if (FULL || local + 4 <= n_valid) return stream_load4(base + local);
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (local + 0 < n_valid) v.x = base[local + 0];
     if (local + 1 < n_valid) v.y = base[local + 1];
@@ -106,7 +133,7 @@ __device__ __forceinline__ float4 load4(const float *base, int local, int n_vali
 template <bool FULL>
 __device__ __forceinline__ void store4(float *base, int local, int n_valid, float4 v)
 {
-    if (FULL || local + 4 <= n_valid) { *reinterpret_cast<float4 *>(base + local) = v; return; }
+    if (FULL || local + 4 <= n_valid) { stream_store4(base + local, v); return; }
     if (local + 0 < n_valid) base[local + 0] = v.x;
     if (local + 1 < n_valid) base[local + 1] = v.y;
     if (local + 2 < n_valid) base[local + 2] = v.z;
@@ -170,6 +197,7 @@ struct TileShared {
     double open_sum[2];
     int long_list[MAX_LONG];
     int n_long;
+    int last[2];                // this workgroup arrived last at its first / last segment's block
     int flag[2];
 };
 
@@ -180,7 +208,9 @@ struct SetCtx {
     unsigned long long *ready;  // [B]
     unsigned int *defer_cnt;
     unsigned long long *defer_list;
-    unsigned int epoch;
+    unsigned int *fin_cnt;
+    unsigned long long *fin_list;
+    unsigned long long tag;     // 0 or 1
     int spin_limit;
     int set;
     float *scales_out;          // [B]
@@ -194,7 +224,9 @@ __device__ __forceinline__ SetCtx make_ctx(const Scratch &X, const Layout &L, in
     c.ready = X.ready + (int64_t)set * L.B;
     c.defer_cnt = X.defer_cnt;
     c.defer_list = X.defer_list;
-    c.epoch = X.epoch;
+    c.fin_cnt = X.fin_cnt;
+    c.fin_list = X.fin_list;
+    c.tag = (X.tags >> (set - X.set_base)) & 1ull;
     c.spin_limit = X.spin_limit;
     c.set = set;
     c.scales_out = scales_out;
@@ -203,68 +235,133 @@ __device__ __forceinline__ SetCtx make_ctx(const Scratch &X, const Layout &L, in
 
 // ------------------------------------------ cross-tile block reductions ---
 
+constexpr unsigned long long TAG_BIT = 1ull << 63;
+constexpr int MAX_PER_THREAD = 4;                       // partial words a thread polls
+constexpr int FUSE_LIMIT_MAX = MAX_PER_THREAD * THREADS; // tiles of the largest one-pass block
+
 __device__ __forceinline__ int block_tiles(const Layout &L, int64_t b)
 {
     return (int)((L.offs[b + 1] - 1) / TILE - L.offs[b] / TILE + 1);
 }
 
-// Called by every thread of the workgroup with the same arguments.  Publishes
-// the partial sum of an open segment of block b and, in the workgroup that
-// arrives last, adds all partials of b in ascending tile order, writes the
-// scale and posts it.  slot: 0 = the tile's first (or only) segment, 1 = its
-// last segment.  Never waits for another workgroup.
-__device__ __forceinline__ void publish_open_segment(double partial, int which, int32_t tile, int64_t b,
-                                                     const Layout &L, const SetCtx &C, TileShared &S)
+// Scratch word of block b's segment in tile t (t0 = b's first tile): slot 1 of
+// tile t0 if b starts inside that tile (it is then the tile's last segment),
+// slot 0 everywhere else (first or only segment).
+__device__ __forceinline__ int64_t part_index(int64_t t, int64_t t0, int64_t bs)
 {
-    const int64_t bs = L.offs[b], be = L.offs[b + 1];
-    const int64_t t0 = bs / TILE, t1 = (be - 1) / TILE;
+    return 2 * t + ((t == t0 && (bs % TILE) != 0) ? 1 : 0);
+}
+
+// Post the partial sum of an open segment of block b and, for a one-pass
+// block, count the arrival.  which: 0 = the tile's first (or only) segment,
+// 1 = its last segment.  Never waits; S.last[which] is valid after the next
+// __syncthreads().
+__device__ __forceinline__ void post_partial(double partial, int which, int32_t tile, int64_t b, const Layout &L,
+                                             const SetCtx &C, TileShared &S)
+{
     if (threadIdx.x == 0) {
-        // All traffic of this hand-off is relaxed agent-scope atomics, which the
-        // hardware performs at the point where the 8 XCDs' L2 caches meet.  The
-        // exchange returns only once the partial is there, and the counter bump
-        // is made to depend on its return value, so a workgroup that sees the
-        // final count also sees every partial.  (An agent-scope release fence
-        // would order them too, but it writes back the whole L2 of streaming
-        // stores on every tile.)
-        unsigned long long old =
-            __hip_atomic_exchange(C.part + 2 * (int64_t)tile + which, (unsigned long long)__double_as_longlong(partial),
-                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned inc = 1u;
-        asm volatile("" : "+v"(inc) : "v"((unsigned)old), "v"((unsigned)(old >> 32)) : "memory");
-        unsigned prev = __hip_atomic_fetch_add(C.cnt + b, inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        S.flag[0] = (prev + 1u == (unsigned)(t1 - t0 + 1)) ? 1 : 0;
-    }
-    __syncthreads();
-    const int last = S.flag[0];
-    __syncthreads();
-    if (!last) return;
-    const int first_slot = (bs % TILE != 0) ? 1 : 0;   // b is the last segment of tile t0 unless it starts there
-    double acc = 0.0;
-    for (int64_t t = t0 + threadIdx.x; t <= t1; t += THREADS) {
-        const int sl = (t == t0) ? first_slot : 0;
-        unsigned long long bits = __hip_atomic_load(C.part + 2 * t + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        acc += __longlong_as_double((long long)bits);
-    }
-    const double total = block_sum(acc, S.red);
-    if (threadIdx.x == 0) {
-        const float s = (float)(total / (double)(be - bs));
-        C.scales_out[b] = s;
-        __hip_atomic_store(C.cnt + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(C.ready + b, ((unsigned long long)C.epoch << 32) | (unsigned long long)__float_as_uint(s),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long w = (unsigned long long)__double_as_longlong(partial) | (C.tag ? TAG_BIT : 0ull);
+        __hip_atomic_store(C.part + 2 * (int64_t)tile + which, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int last = 0;
+        const int n = block_tiles(L, b);
+        if (n <= L.fuse_limit) {
+            // The store above need not have landed when the count does: whoever
+            // reads the partials checks their tags.
+            const unsigned prev = __hip_atomic_fetch_add(C.cnt + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            last = (prev + 1u == (unsigned)n) ? 1 : 0;
+        }
+        S.last[which] = last;
     }
 }
 
-// Wait (bounded) until block b's scale of this call has been posted.  Called by
-// every thread of the workgroup; returns the same answer to all of them.
-__device__ __forceinline__ bool wait_scale(int64_t b, const SetCtx &C, TileShared &S, float *s)
+// Sum of block b's partials once the kernel that posted them has finished.
+// Same order as gather_scale.  Called by every thread of the workgroup.
+__device__ __forceinline__ double sum_block_partials(const Layout &L, int64_t b, const unsigned long long *part,
+                                                     double *red)
+{
+    const int64_t bs = L.offs[b], be = L.offs[b + 1];
+    const int64_t t0 = bs / TILE, t1 = (be - 1) / TILE;
+    double acc = 0.0;
+    for (int64_t t = t0 + threadIdx.x; t <= t1; t += THREADS)
+        acc += __longlong_as_double((long long)(part[part_index(t, t0, bs)] & ~TAG_BIT));
+    return block_sum(acc, red);
+}
+
+// Wait (bounded) until every tile of block b has posted this call's partial,
+// then form the block's scale.  Called by every thread of the workgroup with
+// the same arguments; returns the same answer to all of them.
+__device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const SetCtx &C, TileShared &S, float *s)
+{
+    const int64_t bs = L.offs[b], be = L.offs[b + 1];
+    const int64_t t0 = bs / TILE, t1 = (be - 1) / TILE;
+    const int n = (int)(t1 - t0 + 1);                   // <= fuse_limit <= FUSE_LIMIT_MAX
+    double v[MAX_PER_THREAD];
+    unsigned have = 0;
+#pragma unroll
+    for (int q = 0; q < MAX_PER_THREAD; ++q) v[q] = 0.0;
+    bool ok = false;
+    for (int it = 0; it < C.spin_limit; ++it) {
+        int all = 1;
+#pragma unroll
+        for (int q = 0; q < MAX_PER_THREAD; ++q) {
+            const int i = (int)threadIdx.x + q * THREADS;
+            if (i < n && !((have >> q) & 1u)) {
+                const unsigned long long w = __hip_atomic_load(C.part + part_index(t0 + i, t0, bs), __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                if ((w >> 63) == C.tag) {
+                    v[q] = __longlong_as_double((long long)(w & ~TAG_BIT));
+                    have |= 1u << q;
+                } else {
+                    all = 0;
+                }
+            }
+        }
+        if (__syncthreads_and(all)) {
+            ok = true;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(8);
+    }
+    if (!ok) return false;
+    double acc = 0.0;
+#pragma unroll
+    for (int q = 0; q < MAX_PER_THREAD; ++q) acc += v[q];   // absent words were left at +0
+    const double total = block_sum(acc, S.red);
+    *s = (float)(total / (double)(be - bs));
+    return true;
+}
+
+// The workgroup that arrived last at one-pass block b forms the scale from the
+// partials (waiting, bounded, for those still in flight), writes it out and
+// posts it for the block's other tiles.  Called by every thread of that
+// workgroup.  Does not depend on the progress of any other workgroup.
+__device__ __forceinline__ bool finish_block(int64_t b, const Layout &L, const SetCtx &C, TileShared &S, float *s)
+{
+    const bool ok = gather_scale(b, L, C, S, s);
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(C.cnt + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ok) {
+            C.scales_out[b] = *s;
+            __hip_atomic_store(C.ready + b, (C.tag << 32) | (unsigned long long)__float_as_uint(*s), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            const unsigned k = atomicAdd(C.fin_cnt, 1u);
+            C.fin_list[k] = ((unsigned long long)C.set << 32) | (unsigned long long)b;
+        }
+    }
+    return ok;
+}
+
+// Wait (bounded) until the last arriver has posted block b's scale of this call.
+// Called by every thread of the workgroup; same answer to all of them.
+__device__ __forceinline__ bool wait_ready(int64_t b, const SetCtx &C, TileShared &S, float *s)
 {
     if (threadIdx.x == 0) {
         int found = 0;
         unsigned bits = 0;
         for (int it = 0; it < C.spin_limit; ++it) {
-            unsigned long long w = __hip_atomic_load(C.ready + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((unsigned)(w >> 32) == C.epoch) {
+            const unsigned long long w = __hip_atomic_load(C.ready + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((w >> 32) == C.tag) {
                 found = 1;
                 bits = (unsigned)w;
                 break;
@@ -281,12 +378,12 @@ __device__ __forceinline__ bool wait_scale(int64_t b, const SetCtx &C, TileShare
     return ok;
 }
 
-// Leave an open segment whose p was parked in the residual buffer to the
-// kernel that runs after this one.
+// Leave an open segment whose p gets parked in the residual buffer to the
+// kernels that run after this one.
 __device__ __forceinline__ void defer_segment(int32_t tile, int which, const SetCtx &C)
 {
     if (threadIdx.x == 0) {
-        unsigned i = atomicAdd(C.defer_cnt, 1u);
+        const unsigned i = atomicAdd(C.defer_cnt, 1u);
         C.defer_list[i] = ((unsigned long long)C.set << 33) | ((unsigned long long)tile << 1) | (unsigned)which;
     }
 }
@@ -336,9 +433,10 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
             s = (float)(total / (double)(be - bs));
             if (threadIdx.x == 0) C.scales_out[fb] = s;
         } else {
-            publish_open_segment(total, 0, tile, fb, L, C, S);
+            post_partial(total, 0, tile, fb, L, C, S);
             if (block_tiles(L, fb) <= L.fuse_limit) {
-                have_scale = wait_scale(fb, C, S, &s);
+                __syncthreads();
+                have_scale = S.last[0] ? finish_block(fb, L, C, S, &s) : wait_ready(fb, C, S, &s);
                 if (!have_scale) defer_segment(tile, 0, C);
             }
         }
@@ -410,20 +508,23 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
     __syncthreads();
     const int head_end = head_open ? (int)min(L.offs[fb + 1] - tile_start, (int64_t)n_valid) : 0;
     const int tail_begin = tail_open ? (int)(L.offs[lb] - tile_start) : TILE;
-    // publish everything this tile owes to others before waiting for anything
-    const double head_sum = S.open_sum[0], tail_sum = S.open_sum[1];
-    if (head_open) publish_open_segment(head_sum, 0, tile, fb, L, C, S);
-    if (tail_open) publish_open_segment(tail_sum, 1, tile, lb, L, C, S);
+    // post everything this tile owes to others before waiting for anything
+    if (threadIdx.x == 0) S.last[0] = S.last[1] = 0;
+    if (head_open) post_partial(S.open_sum[0], 0, tile, fb, L, C, S);
+    if (tail_open) post_partial(S.open_sum[1], 1, tile, lb, L, C, S);
+    __syncthreads();
+    const bool head_fused = head_open && block_tiles(L, fb) <= L.fuse_limit;
+    const bool tail_fused = tail_open && block_tiles(L, lb) <= L.fuse_limit;
+    const bool head_last = head_fused && S.last[0], tail_last = tail_fused && S.last[1];
     float s_head = 0.f, s_tail = 0.f;
     bool have_head = false, have_tail = false;
-    if (head_open && block_tiles(L, fb) <= L.fuse_limit) {
-        have_head = wait_scale(fb, C, S, &s_head);
-        if (!have_head) defer_segment(tile, 0, C);
-    }
-    if (tail_open && block_tiles(L, lb) <= L.fuse_limit) {
-        have_tail = wait_scale(lb, C, S, &s_tail);
-        if (!have_tail) defer_segment(tile, 1, C);
-    }
+    // first what others wait for from this workgroup, then what it waits for itself
+    if (head_last) have_head = finish_block(fb, L, C, S, &s_head);
+    if (tail_last) have_tail = finish_block(lb, L, C, S, &s_tail);
+    if (head_fused && !head_last) have_head = wait_ready(fb, C, S, &s_head);
+    if (tail_fused && !tail_last) have_tail = wait_ready(lb, C, S, &s_tail);
+    if (head_fused && !have_head) defer_segment(tile, 0, C);
+    if (tail_fused && !have_tail) defer_segment(tile, 1, C);
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         const int lb0 = local_base(k);
@@ -509,7 +610,7 @@ __device__ __forceinline__ void worker_tile(const Layout &L, const Scratch &X, c
     compress_tile<FULL>(p, L, tile, n_valid, A.signs + (int64_t)worker * L.W, e, C, S);
 }
 
-__global__ __launch_bounds__(THREADS) void k_worker(Layout L, Scratch X, WorkerArgs A)
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_worker(Layout L, Scratch X, WorkerArgs A)
 {
     __shared__ TileShared S;
     const int32_t tile = blockIdx.x;
@@ -641,29 +742,59 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
     }
 }
 
-// Second pass over the open segments of blocks larger than fuse_limit: the
-// list (tile << 1 | slot) is fixed per layout and built with the plan.
-__global__ __launch_bounds__(THREADS) void k_residual_static(Layout L, const uint32_t *items, float *err,
-                                                             int64_t err_stride, const float *scales)
+// Scales the first kernel of a call did not write: those of blocks larger than
+// fuse_limit (list fixed per layout: workgroups 0 .. n_big*nsets-1) and those
+// whose first tile gave up waiting (list filled by the first kernel: the last
+// DEFER_WGS workgroups).
+__global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X, const int32_t *big_blocks,
+                                                             int n_big, int nsets, float *scales)
 {
-    const uint32_t it = items[blockIdx.x];
-    const int w = blockIdx.y;
-    residual_segment(L, (int32_t)(it >> 1), (int)(it & 1u), err + (int64_t)w * err_stride, scales + (int64_t)w * L.B);
+    __shared__ double red[NWAVES];
+    const int n_static = n_big * nsets;
+    if ((int)blockIdx.x < n_static) {
+        const int64_t b = big_blocks[blockIdx.x % n_big];
+        const int w = blockIdx.x / n_big;
+        const double total =
+            sum_block_partials(L, b, X.part + (int64_t)(X.set_base + w) * 2 * L.ntiles, red);
+        if (threadIdx.x == 0) scales[(int64_t)w * L.B + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+        return;
+    }
+    const unsigned n = *X.fin_cnt;
+    for (unsigned i = blockIdx.x - n_static; i < n; i += DEFER_WGS) {
+        const unsigned long long it = X.fin_list[i];
+        const int set = (int)(it >> 32);
+        const int64_t b = (int64_t)(it & 0xffffffffull);
+        const double total = sum_block_partials(L, b, X.part + (int64_t)set * 2 * L.ntiles, red);
+        if (threadIdx.x == 0)
+            scales[(int64_t)(set - X.set_base) * L.B + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+    }
 }
 
-// Second pass over the segments whose wait ran out of its spin budget in the
-// first kernel of this call (normally none).  Also clears the counter the next
-// call will use.
-__global__ __launch_bounds__(THREADS) void k_residual_deferred(Layout L, const unsigned int *defer_cnt,
-                                                               unsigned int *next_defer_cnt,
-                                                               const unsigned long long *defer_list, int set_base,
-                                                               float *err, int64_t err_stride, const float *scales)
+// e <- p - Delta wherever the first kernel parked p: the open segments of blocks
+// larger than fuse_limit (list fixed per layout: workgroups 0 .. n_items*nsets-1)
+// and the segments whose wait ran out (list filled by the first kernel: the last
+// DEFER_WGS workgroups).  Also clears the list counters the next call will use.
+__global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X, const uint32_t *items,
+                                                             int n_items, int nsets, unsigned int *next_defer_cnt,
+                                                             unsigned int *next_fin_cnt, float *err,
+                                                             int64_t err_stride, const float *scales)
 {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *next_defer_cnt = 0u;
-    const unsigned n = *defer_cnt;
-    for (unsigned i = blockIdx.x; i < n; i += gridDim.x) {
-        const unsigned long long it = defer_list[i];
-        const int w = (int)(it >> 33) - set_base;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *next_defer_cnt = 0u;
+        *next_fin_cnt = 0u;
+    }
+    const int n_static = n_items * nsets;
+    if ((int)blockIdx.x < n_static) {
+        const uint32_t it = items[blockIdx.x % n_items];
+        const int w = blockIdx.x / n_items;
+        residual_segment(L, (int32_t)(it >> 1), (int)(it & 1u), err + (int64_t)w * err_stride,
+                         scales + (int64_t)w * L.B);
+        return;
+    }
+    const unsigned n = *X.defer_cnt;
+    for (unsigned i = blockIdx.x - n_static; i < n; i += DEFER_WGS) {
+        const unsigned long long it = X.defer_list[i];
+        const int w = (int)(it >> 33) - X.set_base;
         const int32_t tile = (int32_t)((it >> 1) & 0xffffffffull);
         residual_segment(L, tile, (int)(it & 1ull), err + (int64_t)w * err_stride, scales + (int64_t)w * L.B);
     }
