@@ -72,6 +72,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--fuse-limit", type=int, default=-1, help="override the plan's one-pass block limit")
     ap.add_argument("--spin-limit", type=int, default=-1, help="override the plan's wait budget")
+    ap.add_argument("--persistent", type=int, default=-1, help="1/0: force the persistent worker kernel on/off")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs M simulated workers and the server on ONE GPU; "
@@ -89,6 +90,8 @@ def main():
     plan = ef.ef_plan_create(w.offsets, M)
     if args.fuse_limit >= 0 or args.spin_limit >= 0:
         plan.tune(args.fuse_limit, args.spin_limit)
+    if args.persistent >= 0:
+        plan.set_persistent(args.persistent)
 
     # gradient sets resident in HBM, cycled over the steps
     n_sets = args.grad_sets or max(1, min(args.steps + args.warmup, int(64e9 // (4.0 * d * M)), 4))

@@ -94,6 +94,15 @@ int ef_plan_destroy(ef_plan *plan);
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
 int ef_plan_fuse_limit(const ef_plan *plan);
 
+/*
+ * Which kernel ef_worker_step runs over the tiles that lie inside one block:
+ * on = 0 (default) one workgroup per tile that waits in place for its block's
+ * scale; on = 1 a persistent kernel whose workgroups take tiles from a ticket
+ * counter and keep several tiles in registers while their scales form.  Same
+ * results either way.  Synchronises the device.
+ */
+int ef_plan_set_persistent(ef_plan *plan, int on);
+
 int64_t ef_plan_d(const ef_plan *plan);          /* d = block_offsets[B] */
 int64_t ef_plan_blocks(const ef_plan *plan);     /* B */
 int64_t ef_plan_sign_words(const ef_plan *plan); /* W = ceil(d/64) */

@@ -23,7 +23,7 @@ EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1
 EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
-    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
     "ef_sign_words", "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
 )
 
@@ -55,6 +55,8 @@ def lib():
         getattr(L, name).argtypes = [vp]
     L.ef_plan_tune.restype = c_int
     L.ef_plan_tune.argtypes = [vp, c_int, c_int]
+    L.ef_plan_set_persistent.restype = c_int
+    L.ef_plan_set_persistent.argtypes = [vp, c_int]
     L.ef_plan_fuse_limit.restype = c_int
     L.ef_plan_fuse_limit.argtypes = [vp]
     L.ef_sign_words.restype = i64
@@ -129,6 +131,9 @@ class Plan:
     def tune(self, fuse_limit=-1, spin_limit=-1):
         _check(lib().ef_plan_tune(self._h, int(fuse_limit), int(spin_limit)))
 
+    def set_persistent(self, on):
+        _check(lib().ef_plan_set_persistent(self._h, int(bool(on))))
+
     @property
     def fuse_limit(self):
         return int(lib().ef_plan_fuse_limit(self._h))
@@ -151,6 +156,10 @@ def ef_plan_create(block_offsets, max_workers, stream=None):
 
 def ef_plan_tune(plan, fuse_limit=-1, spin_limit=-1):
     plan.tune(fuse_limit, spin_limit)
+
+
+def ef_plan_set_persistent(plan, on):
+    plan.set_persistent(on)
 
 
 def ef_plan_fuse_limit(plan):

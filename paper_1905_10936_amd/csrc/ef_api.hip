@@ -19,8 +19,8 @@ struct ef_plan {
     std::vector<uint8_t> set_tag;   // tag the last call that used a set gave its partial words
     std::vector<int64_t> offs_host;
     std::vector<int32_t> fb_host, lb_host;
-    uint32_t n_static;              // open segments of blocks larger than fuse_limit
-    uint32_t n_big;                 // those blocks
+    uint32_t n_static;              // segments whose p the first kernels always park
+    uint32_t n_late;                // blocks whose scale the first kernels never write
     // device allocations owned by the plan
     int64_t *d_offs;
     int32_t *d_tile_fb;
@@ -28,11 +28,14 @@ struct ef_plan {
     unsigned long long *d_part;
     unsigned int *d_cnt;
     unsigned long long *d_ready;
-    unsigned int *d_list_cnt;       // [4]: defer_cnt[2], fin_cnt[2], alternating between calls
+    unsigned int *d_list_cnt;       // [6]: defer_cnt[2], fin_cnt[2], ticket[2], alternating between calls
+    int worker_grid;                // workgroups of the persistent worker kernel
+    int persistent;                 // 1: pipelined persistent worker kernel, 0: one workgroup per tile
     unsigned long long *d_defer_list;
     unsigned long long *d_fin_list;
     uint32_t *d_static;             // [2*ntiles] capacity
-    int32_t *d_big;                 // [min(B, 2*ntiles)] capacity
+    int32_t *d_late;                // [min(B, 2*ntiles)] capacity
+    int32_t *d_mixed, *d_uniform;   // tile lists
 };
 
 namespace {
@@ -83,7 +86,9 @@ void destroy_device(ef_plan *p)
     if (p->d_defer_list) (void)hipFree(p->d_defer_list);
     if (p->d_fin_list) (void)hipFree(p->d_fin_list);
     if (p->d_static) (void)hipFree(p->d_static);
-    if (p->d_big) (void)hipFree(p->d_big);
+    if (p->d_late) (void)hipFree(p->d_late);
+    if (p->d_mixed) (void)hipFree(p->d_mixed);
+    if (p->d_uniform) (void)hipFree(p->d_uniform);
 }
 
 int64_t tiles_of_block(const ef_plan *p, int64_t b)
@@ -92,26 +97,41 @@ int64_t tiles_of_block(const ef_plan *p, int64_t b)
     return (o[b + 1] - 1) / ef::TILE - o[b] / ef::TILE + 1;
 }
 
-// What the one-pass path leaves to the later kernels: the blocks spanning more
-// than fuse_limit tiles and their (open) segments.
+bool has_uniform_tile(const ef_plan *p, int64_t b)
+{
+    const int64_t *o = p->offs_host.data();
+    return tiles_of_block(p, b) - (o[b] % ef::TILE != 0 ? 1 : 0) - (o[b + 1] % ef::TILE != 0 ? 1 : 0) >= 1;
+}
+
+// What the first kernels of a call always leave to the two short kernels after
+// them: the scales of crossing blocks that have no uniform tile or span more
+// than fuse_limit tiles, and the residual of every open segment of a mixed tile
+// and of every tile of a block larger than fuse_limit.
 int upload_static_list(ef_plan *p)
 {
     std::vector<uint32_t> items;
-    std::vector<int32_t> big;
+    std::vector<int32_t> late;
     const int64_t *o = p->offs_host.data();
-    for (int64_t b = 0; b < p->L.B; ++b)
-        if (tiles_of_block(p, b) >= 2 && tiles_of_block(p, b) > p->L.fuse_limit) big.push_back((int32_t)b);
-    p->n_big = (uint32_t)big.size();
-    if (!big.empty()) EF_HIP(hipMemcpy(p->d_big, big.data(), sizeof(int32_t) * big.size(), hipMemcpyHostToDevice));
+    for (int64_t b = 0; b < p->L.B; ++b) {
+        const int64_t n = tiles_of_block(p, b);
+        if (n >= 2 && (n > p->L.fuse_limit || !has_uniform_tile(p, b))) late.push_back((int32_t)b);
+    }
     for (int32_t t = 0; t < p->L.ntiles; ++t) {
         const int64_t start = (int64_t)t * ef::TILE, end = start + ef::TILE;
         const int32_t fb = p->fb_host[t], lb = p->lb_host[t];
-        const bool first_open = (o[fb] < start) || (o[fb + 1] > end);
-        if (first_open && tiles_of_block(p, fb) > p->L.fuse_limit) items.push_back(((uint32_t)t << 1) | 0u);
-        if (lb != fb && o[lb + 1] > end && tiles_of_block(p, lb) > p->L.fuse_limit)
-            items.push_back(((uint32_t)t << 1) | 1u);
+        const bool full = end <= p->L.d;
+        if (fb == lb) {
+            // a full tile parks p only for blocks beyond fuse_limit, the ragged last tile always
+            const bool open = (o[fb] < start) || (o[fb + 1] > end);
+            if (open && (!full || tiles_of_block(p, fb) > p->L.fuse_limit)) items.push_back(((uint32_t)t << 1) | 0u);
+        } else {
+            if (o[fb] < start) items.push_back(((uint32_t)t << 1) | 0u);
+            if (o[lb + 1] > end) items.push_back(((uint32_t)t << 1) | 1u);
+        }
     }
+    p->n_late = (uint32_t)late.size();
     p->n_static = (uint32_t)items.size();
+    if (!late.empty()) EF_HIP(hipMemcpy(p->d_late, late.data(), sizeof(int32_t) * late.size(), hipMemcpyHostToDevice));
     if (!items.empty())
         EF_HIP(hipMemcpy(p->d_static, items.data(), sizeof(uint32_t) * items.size(), hipMemcpyHostToDevice));
     return EF_OK;
@@ -155,12 +175,29 @@ int build_device(ef_plan *p)
     EF_HIP(hipMalloc(&p->d_ready, sizeof(unsigned long long) * (size_t)B * nsets));
     EF_HIP(hipMemset(p->d_cnt, 0, sizeof(unsigned int) * (size_t)B * nsets));
     EF_HIP(hipMemset(p->d_ready, 0, sizeof(unsigned long long) * (size_t)B * nsets));
-    EF_HIP(hipMalloc(&p->d_list_cnt, sizeof(unsigned int) * 4));
+    EF_HIP(hipMalloc(&p->d_list_cnt, sizeof(unsigned int) * 6));
     EF_HIP(hipMalloc(&p->d_defer_list, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
     EF_HIP(hipMalloc(&p->d_fin_list, sizeof(unsigned long long) * max_cross * nsets));
     EF_HIP(hipMalloc(&p->d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
-    EF_HIP(hipMalloc(&p->d_big, sizeof(int32_t) * max_cross));
-    EF_HIP(hipMemset(p->d_list_cnt, 0, sizeof(unsigned int) * 4));
+    EF_HIP(hipMalloc(&p->d_late, sizeof(int32_t) * max_cross));
+    {
+        std::vector<int32_t> mixed, uniform;
+        for (int32_t t = 0; t < ntiles; ++t) {
+            const bool full = ((int64_t)t + 1) * ef::TILE <= d;
+            (fb[t] == lb[t] && full ? uniform : mixed).push_back(t);
+        }
+        p->L.n_mixed = (int32_t)mixed.size();
+        p->L.n_uniform = (int32_t)uniform.size();
+        EF_HIP(hipMalloc(&p->d_mixed, sizeof(int32_t) * (mixed.size() + 1)));
+        EF_HIP(hipMalloc(&p->d_uniform, sizeof(int32_t) * (uniform.size() + 1)));
+        if (!mixed.empty())
+            EF_HIP(hipMemcpy(p->d_mixed, mixed.data(), sizeof(int32_t) * mixed.size(), hipMemcpyHostToDevice));
+        if (!uniform.empty())
+            EF_HIP(hipMemcpy(p->d_uniform, uniform.data(), sizeof(int32_t) * uniform.size(), hipMemcpyHostToDevice));
+        p->L.mixed_tiles = p->d_mixed;
+        p->L.uniform_tiles = p->d_uniform;
+    }
+    EF_HIP(hipMemset(p->d_list_cnt, 0, sizeof(unsigned int) * 6));
     p->set_tag.assign(nsets, 0);                 // the zeroed partial words carry tag 0
     p->L.offs = p->d_offs;
     p->L.tile_fb = p->d_tile_fb;
@@ -176,15 +213,25 @@ int build_device(ef_plan *p)
         hipDeviceProp_t prop;
         EF_HIP(hipGetDeviceProperties(&prop, p->device));
         int occ_w = 0, occ_s = 0;
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_w, ef::k_worker, ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_w, ef::k_worker_uniform, ef::THREADS, 0));
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server, ef::THREADS, 0));
-        const int occ = occ_w < occ_s ? occ_w : occ_s;
-        int64_t lim = (int64_t)prop.multiProcessorCount * occ / 2;
+        if (occ_w < 1) occ_w = 1;
+        p->worker_grid = prop.multiProcessorCount * occ_w;
+        // one-pass blocks must fit, with a factor 2 to spare, both into the tiles the
+        // persistent worker grid holds at once and into the server kernel's resident tiles
+        int occ_d = 0;
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, ef::k_worker_uniform_direct, ef::THREADS, 0));
+        int64_t lim_w = (int64_t)p->worker_grid * ef::PIPE_DEPTH / 2;
+        const int64_t lim_d = (int64_t)prop.multiProcessorCount * occ_d / 2;
+        if (lim_d < lim_w) lim_w = lim_d;
+        const int64_t lim_s = (int64_t)prop.multiProcessorCount * occ_s / 2;
+        int64_t lim = lim_w < lim_s ? lim_w : lim_s;
         if (lim < 1) lim = 1;
         if (lim > ef::FUSE_LIMIT_MAX) lim = ef::FUSE_LIMIT_MAX;
         p->L.fuse_limit = (int32_t)lim;
     }
     p->spin_limit = 1 << 14;
+    p->persistent = 0;
     p->calls = 0;
     int rc = upload_static_list(p);
     if (rc) return rc;
@@ -196,7 +243,7 @@ int build_device(ef_plan *p)
 // tag of every set it uses and picks the list counters of this call's parity.
 struct CallScratch {
     ef::Scratch X;
-    unsigned int *next_defer_cnt, *next_fin_cnt;
+    unsigned int *next_defer_cnt, *next_fin_cnt, *next_ticket;
 };
 
 CallScratch next_call(const ef_plan *plan_c, int set_base, int nsets)
@@ -215,8 +262,10 @@ CallScratch next_call(const ef_plan *plan_c, int set_base, int nsets)
     plan->calls += 1;
     c.X.defer_cnt = plan->d_list_cnt + cur;
     c.X.fin_cnt = plan->d_list_cnt + 2 + cur;
+    c.X.ticket = plan->d_list_cnt + 4 + cur;
     c.next_defer_cnt = plan->d_list_cnt + nxt;
     c.next_fin_cnt = plan->d_list_cnt + 2 + nxt;
+    c.next_ticket = plan->d_list_cnt + 4 + nxt;
     return c;
 }
 
@@ -224,12 +273,12 @@ CallScratch next_call(const ef_plan *plan_c, int set_base, int nsets)
 int launch_second_pass(const ef_plan *plan, const CallScratch &c, int nsets, float *err, int64_t err_stride,
                        float *scales, hipStream_t s)
 {
-    hipLaunchKernelGGL(ef::k_finalize_scales, dim3(plan->n_big * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
-                       plan->L, c.X, (const int32_t *)plan->d_big, (int)plan->n_big, nsets, scales);
+    hipLaunchKernelGGL(ef::k_finalize_scales, dim3(plan->n_late * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
+                       plan->L, c.X, (const int32_t *)plan->d_late, (int)plan->n_late, nsets, scales);
     EF_HIP(hipGetLastError());
     hipLaunchKernelGGL(ef::k_residual_parked, dim3(plan->n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
                        plan->L, c.X, (const uint32_t *)plan->d_static, (int)plan->n_static, nsets, c.next_defer_cnt,
-                       c.next_fin_cnt, err, err_stride, (const float *)scales);
+                       c.next_fin_cnt, c.next_ticket, err, err_stride, (const float *)scales);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
@@ -265,9 +314,10 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_defer_list = nullptr;
     p->d_fin_list = nullptr;
     p->d_static = nullptr;
-    p->d_big = nullptr;
+    p->d_late = nullptr;
+    p->d_mixed = p->d_uniform = nullptr;
     p->n_static = 0;
-    p->n_big = 0;
+    p->n_late = 0;
     rc = build_device(p);
     if (rc) {
         destroy_device(p);
@@ -302,6 +352,14 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
 
 int ef_plan_fuse_limit(const ef_plan *plan) { return plan ? plan->L.fuse_limit : 0; }
 
+int ef_plan_set_persistent(ef_plan *plan, int on)
+{
+    if (!plan) return EF_ERR_NULL;
+    EF_HIP(hipDeviceSynchronize());
+    plan->persistent = on ? 1 : 0;
+    return EF_OK;
+}
+
 int64_t ef_plan_d(const ef_plan *plan) { return plan ? plan->L.d : 0; }
 int64_t ef_plan_blocks(const ef_plan *plan) { return plan ? plan->L.B : 0; }
 int64_t ef_plan_sign_words(const ef_plan *plan) { return plan ? plan->L.W : 0; }
@@ -331,10 +389,23 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
     A.signs = packed_signs;
     A.scales = scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    dim3 grid((unsigned)plan->L.ntiles, (unsigned)n_workers);
     const CallScratch c = next_call(plan, 0, n_workers);
-    hipLaunchKernelGGL(ef::k_worker, grid, dim3(ef::THREADS), 0, s, plan->L, c.X, A);
-    EF_HIP(hipGetLastError());
+    if (plan->L.n_mixed) {
+        hipLaunchKernelGGL(ef::k_worker_mixed, dim3((unsigned)plan->L.n_mixed, (unsigned)n_workers),
+                           dim3(ef::THREADS), 0, s, plan->L, c.X, A);
+        EF_HIP(hipGetLastError());
+    }
+    if (plan->L.n_uniform && plan->persistent) {
+        int64_t wgs = (int64_t)plan->L.n_uniform * n_workers;
+        if (wgs > plan->worker_grid) wgs = plan->worker_grid;
+        hipLaunchKernelGGL(ef::k_worker_uniform, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, plan->L, c.X, A,
+                           n_workers);
+        EF_HIP(hipGetLastError());
+    } else if (plan->L.n_uniform) {
+        hipLaunchKernelGGL(ef::k_worker_uniform_direct, dim3((unsigned)plan->L.n_uniform, (unsigned)n_workers),
+                           dim3(ef::THREADS), 0, s, plan->L, c.X, A);
+        EF_HIP(hipGetLastError());
+    }
     return launch_second_pass(plan, c, n_workers, err, state_stride, scales, s);
 }
 

@@ -4,55 +4,62 @@
 //
 // Work decomposition
 // ------------------
-// The flat d-vector is cut into tiles of TILE = 4096 consecutive elements, one
-// 256-thread workgroup per (tile, worker).  Tiles, not blocks, are the unit of
-// work, so a block of 8M elements and a block of 1 element cost the same per
-// element.  A tile is a whole number of 64-element sign words and starts on a
-// 16 KiB boundary, so every fp32 access is a coalesced 128-bit access whatever
-// the block boundaries are.  Inside a tile, wavefront w owns the 1024
-// consecutive elements [1024w, 1024w+1024) as 4 sub-rows of 256; lane l of
-// sub-row k holds the 4 consecutive elements 1024w + 256k + 4l .. +3.
+// The flat d-vector is cut into tiles of TILE = 4096 consecutive elements, the
+// unit of work of a 256-thread workgroup.  Tiles, not blocks, are the unit, so
+// a block of 8M elements and a block of 1 element cost the same per element.
+// A tile is a whole number of 64-element sign words and starts on a 16 KiB
+// boundary, so every fp32 access is a coalesced 128-bit access whatever the
+// block boundaries are.  Inside a tile, wavefront w owns the 1024 consecutive
+// elements [1024w, 1024w+1024) as 4 sub-rows of 256; lane l of sub-row k holds
+// the 4 consecutive elements 1024w + 256k + 4l .. +3.
 //
-// The blocks of the partition (Section 3.2) cut a tile into segments.  A
-// segment whose block lies entirely inside the tile is "closed": its L1 norm,
-// scale and residual are finished by the tile alone.  At most two segments of
-// a tile are "open" (the block continues into a neighbouring tile).  Their fp64
-// partial sums go to a per-(tile, slot) scratch word.  Whoever needs the
-// block's scale adds the block's partials in one fixed order (thread t takes
-// tiles t, t+256, ... in ascending order, then a fixed tree), so the scale has
-// the same bits wherever and whenever it is computed.
+// The blocks of the partition (Section 3.2) cut a tile into segments.  A full
+// tile that lies inside one block is "uniform"; a tile where several blocks
+// meet, and the ragged last tile of the vector, is "mixed".  A segment whose block lies entirely inside the tile is "closed":
+// its L1 norm, scale and residual are finished by the tile alone (in fp64, in
+// ascending order for short segments).  The other segments are "open": their
+// fp64 partial sums go to a per-(tile, slot) scratch word, and whoever needs
+// the block's scale adds the block's partials in one fixed order (thread t
+// takes tiles t, t+256, ... ascending, then a fixed tree), so the scale has the
+// same bits wherever and whenever it is computed.
 //
 // One pass over the state
 // -----------------------
 // e <- p - Delta needs the block's scale, i.e. every tile of the block.  For a
-// block of at most `fuse_limit` tiles the workgroups keep p in registers, post
-// their partial and poll (bounded) the partial words of the block's other tiles
-// until all carry this call's tag, then write the finished residual, so every
-// fp32 tensor is read once and written once.  A partial is never negative, so
-// its sign bit is free to carry the tag, which flips on every call that uses
-// the scratch set: a word is "of this call" exactly when its tag matches, and
-// one relaxed agent-scope 64-bit store publishes value and tag together -- no
-// counters, no fences (an agent-scope release fence would write back the whole
-// L2 of streaming stores on every tile).  The wait cannot starve: all partials
-// of a tile are posted before its first wait, workgroups are dispatched in grid
-// order, and fuse_limit keeps a block's tiles well inside what is resident at
-// once.  Should a wait still run out of its spin budget, or for blocks larger
-// than fuse_limit, the workgroup parks p in the residual buffer instead; a small
-// kernel then computes the scales still missing and another subtracts the
-// decoded value where p was parked.
+// block of at most `fuse_limit` tiles the workgroups of its uniform tiles keep
+// p in registers until the scale exists and then write the finished residual,
+// so every fp32 tensor is read once and written once.  The hand-off between
+// workgroups uses relaxed agent-scope atomics only (an agent-scope release
+// fence would write back the whole L2 of streaming stores on every tile):
+//   * a partial is never negative, so its sign bit carries a tag that flips on
+//     every call that uses the scratch set; one 64-bit store publishes value
+//     and tag together;
+//   * an arrival counter per block tells the workgroup that arrives last;
+//     it gathers the partials (re-reading those whose tag is still old),
+//     writes the scale and posts (tag, scale) in the block's "ready" word;
+//   * the others look at the ready word when they come to write the tile.
+// Mixed tiles never wait: their open segments, like all tiles of blocks larger
+// than fuse_limit and any tile whose (bounded) wait ran out, get p parked in
+// the residual buffer; a small kernel then computes the scales still missing
+// and another subtracts the decoded value where p was parked.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace ef {
 
-constexpr int TILE = 4096;      // elements per workgroup
+constexpr int TILE = 4096;      // elements per workgroup and step
 constexpr int THREADS = 256;    // 4 wavefronts
 constexpr int NWAVES = THREADS / 64;
 constexpr int SUBROWS = 4;      // float4 per thread
 constexpr int SMALL_SEG = 64;   // segments up to this length are summed by one thread
 constexpr int MAX_LONG = TILE / SMALL_SEG;
-constexpr int DEFER_WGS = 64;   // workgroups of the kernel that finishes deferred segments
+constexpr int DEFER_WGS = 64;   // workgroups that serve the run-time lists of the second-pass kernels
+constexpr int PIPE_DEPTH = 3;   // tiles a persistent workgroup keeps in registers while their scales form
+constexpr int TICKET_TILES = 2; // consecutive tiles handed out per ticket
+constexpr unsigned long long TAG_BIT = 1ull << 63;
+constexpr int MAX_PER_THREAD = 6;                        // partial words a thread gathers
+constexpr int FUSE_LIMIT_MAX = MAX_PER_THREAD * THREADS; // tiles of the largest one-pass block
 
 struct Layout {
     int64_t d;                  // elements
@@ -60,9 +67,12 @@ struct Layout {
     int64_t W;                  // sign words
     int32_t ntiles;
     int32_t fuse_limit;         // blocks of up to this many tiles finish in one pass
+    int32_t n_mixed, n_uniform;
     const int64_t *offs;        // [B+1] device copy of block_offsets
     const int32_t *tile_fb;     // [ntiles] block holding the tile's first element
     const int32_t *tile_lb;     // [ntiles] block holding the tile's last valid element
+    const int32_t *mixed_tiles;   // [n_mixed] ascending
+    const int32_t *uniform_tiles; // [n_uniform] ascending
 };
 
 // Scratch of one call.  A "set" is one worker, or the server.
@@ -74,6 +84,7 @@ struct Scratch {
     unsigned long long *defer_list;  // parked segments: (set << 33) | (tile << 1) | slot
     unsigned int *fin_cnt;      // entries in fin_list for this call
     unsigned long long *fin_list;    // blocks whose scale is still to be written: (set << 32) | block
+    unsigned int *ticket;       // next chunk of tiles to hand out (persistent kernels), 0 at call start
     unsigned long long tags;    // bit i = this call's tag of set (set_base + i)
     int set_base;               // first set this call uses (0 for workers, max_workers for the server)
     int spin_limit;             // polls before a waiting workgroup gives up and parks p
@@ -119,10 +130,9 @@ __device__ __forceinline__ void stream_store4(float *p, float4 a)
     __builtin_nontemporal_store(v, reinterpret_cast<vf4 *>(p));
 }
 
-template <bool FULL>
-__device__ __forceinline__ float4 load4(const float *base, int local, int n_valid)
+__device__ __forceinline__ float4 guarded_load4(const float *base, int local, int n_valid)
 {
-    if (FULL || local + 4 <= n_valid) return stream_load4(base + local);
+    if (local + 4 <= n_valid) return stream_load4(base + local);
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (local + 0 < n_valid) v.x = base[local + 0];
     if (local + 1 < n_valid) v.y = base[local + 1];
@@ -130,13 +140,43 @@ __device__ __forceinline__ float4 load4(const float *base, int local, int n_vali
     return v;                   // local + 3 < n_valid would have taken the vector path
 }
 
-template <bool FULL>
-__device__ __forceinline__ void store4(float *base, int local, int n_valid, float4 v)
+__device__ __forceinline__ void guarded_store4(float *base, int local, int n_valid, float4 v)
 {
-    if (FULL || local + 4 <= n_valid) { stream_store4(base + local, v); return; }
+    if (local + 4 <= n_valid) { stream_store4(base + local, v); return; }
     if (local + 0 < n_valid) base[local + 0] = v.x;
     if (local + 1 < n_valid) base[local + 1] = v.y;
     if (local + 2 < n_valid) base[local + 2] = v.z;
+}
+
+// A thread's four float4 of one tile.  Only the last tile of a vector can be
+// ragged; the test is uniform over the workgroup, so full tiles run straight
+// through 128-bit accesses with no per-access branch.
+__device__ __forceinline__ void load_tile(const float *base, float4 (&v)[SUBROWS], int n_valid)
+{
+    if (n_valid == TILE) {
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) v[k] = stream_load4(base + local_base(k));
+    } else {
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) v[k] = guarded_load4(base, local_base(k), n_valid);
+    }
+}
+
+__device__ __forceinline__ void store_tile(float *base, const float4 (&v)[SUBROWS], int n_valid)
+{
+    if (n_valid == TILE) {
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) stream_store4(base + local_base(k), v[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) guarded_store4(base, local_base(k), n_valid, v[k]);
+    }
+}
+
+__device__ __forceinline__ int tile_valid(const Layout &L, int32_t tile)
+{
+    const int64_t left = L.d - (int64_t)tile * TILE;
+    return left >= TILE ? TILE : (int)left;
 }
 
 // Butterfly sum over the 64 lanes: every lane ends with the same bits.
@@ -163,11 +203,19 @@ __device__ __forceinline__ float signed_scale(float s, bool plus) { return plus 
 // e' = p - Delta for one element whose block has scale s
 __device__ __forceinline__ float residual(float p, float s) { return p - signed_scale(s, p >= 0.f); }
 
-// Pack the signs of this thread's 16 values into the wavefront's 16 sign words
-// and store them.  nib[k] holds the 4 sign bits of sub-row k (bit c = element c).
-// Within a sub-row, 16 consecutive lanes make one 64-bit word.
-__device__ __forceinline__ void pack_and_store_signs(const unsigned nib[SUBROWS], uint64_t *signs,
-                                                     int64_t tile_start, int64_t W)
+__device__ __forceinline__ void residual4(float4 &v, float s)
+{
+    v.x = residual(v.x, s);
+    v.y = residual(v.y, s);
+    v.z = residual(v.z, s);
+    v.w = residual(v.w, s);
+}
+
+// Sign words of the tile whose values are in p (bit = p >= 0, Appendix A with
+// sign(0) read as +1; elements past n_valid give 0 bits).  Within a sub-row, 16
+// consecutive lanes make one 64-bit word; each wavefront stores its 16 words.
+__device__ __forceinline__ void store_signs(const float4 (&p)[SUBROWS], int n_valid, uint64_t *signs,
+                                            int64_t tile_start, int64_t W)
 {
     const int lane = lane_id();
     const int l16 = lane & 15;
@@ -175,8 +223,17 @@ __device__ __forceinline__ void pack_and_store_signs(const unsigned nib[SUBROWS]
     unsigned mylo = 0, myhi = 0;
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
-        unsigned lo = (l16 < 8) ? (nib[k] << sh) : 0u;
-        unsigned hi = (l16 >= 8) ? (nib[k] << sh) : 0u;
+        const int lb0 = local_base(k);
+        unsigned nib = (p[k].x >= 0.f ? 1u : 0u) | (p[k].y >= 0.f ? 2u : 0u) | (p[k].z >= 0.f ? 4u : 0u) |
+                       (p[k].w >= 0.f ? 8u : 0u);
+        if (n_valid != TILE) {
+            unsigned vm = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) vm |= (lb0 + c < n_valid) ? (1u << c) : 0u;
+            nib &= vm;
+        }
+        unsigned lo = (l16 < 8) ? (nib << sh) : 0u;
+        unsigned hi = (l16 >= 8) ? (nib << sh) : 0u;
 #pragma unroll
         for (int off = 1; off <= 8; off <<= 1) {
             lo |= (unsigned)__shfl_xor((int)lo, off);
@@ -191,86 +248,126 @@ __device__ __forceinline__ void pack_and_store_signs(const unsigned nib[SUBROWS]
     }
 }
 
+// fp64 sum of |p| over the thread's valid elements
+__device__ __forceinline__ double abs_sum(const float4 (&p)[SUBROWS], int n_valid)
+{
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k) {
+        const int lb0 = local_base(k);
+        const float a[4] = {fabsf(p[k].x), fabsf(p[k].y), fabsf(p[k].z), fabsf(p[k].w)};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc += (n_valid == TILE || lb0 + c < n_valid) ? (double)a[c] : 0.0;
+    }
+    return acc;
+}
+
 struct TileShared {
     float val[TILE];            // |p| per element, then the element's scale (closed segments)
     double red[NWAVES];
     double open_sum[2];
     int long_list[MAX_LONG];
     int n_long;
-    int last[2];                // this workgroup arrived last at its first / last segment's block
     int flag[2];
+    unsigned ticket;
 };
 
-// Per-call view of one set's scratch and outputs.
-struct SetCtx {
-    unsigned long long *part;   // [2*ntiles]
-    unsigned int *cnt;          // [B]
-    unsigned long long *ready;  // [B]
-    unsigned int *defer_cnt;
-    unsigned long long *defer_list;
-    unsigned int *fin_cnt;
-    unsigned long long *fin_list;
-    unsigned long long tag;     // 0 or 1
-    int spin_limit;
-    int set;
-    float *scales_out;          // [B]
-};
+// ------------------------------------------------- per-set scratch views ---
 
-__device__ __forceinline__ SetCtx make_ctx(const Scratch &X, const Layout &L, int set, float *scales_out)
+__device__ __forceinline__ unsigned long long *set_part(const Scratch &X, const Layout &L, int set)
 {
-    SetCtx c;
-    c.part = X.part + (int64_t)set * 2 * L.ntiles;
-    c.cnt = X.cnt + (int64_t)set * L.B;
-    c.ready = X.ready + (int64_t)set * L.B;
-    c.defer_cnt = X.defer_cnt;
-    c.defer_list = X.defer_list;
-    c.fin_cnt = X.fin_cnt;
-    c.fin_list = X.fin_list;
-    c.tag = (X.tags >> (set - X.set_base)) & 1ull;
-    c.spin_limit = X.spin_limit;
-    c.set = set;
-    c.scales_out = scales_out;
-    return c;
+    return X.part + (int64_t)set * 2 * L.ntiles;
+}
+__device__ __forceinline__ unsigned int *set_cnt(const Scratch &X, const Layout &L, int set)
+{
+    return X.cnt + (int64_t)set * L.B;
+}
+__device__ __forceinline__ unsigned long long *set_ready(const Scratch &X, const Layout &L, int set)
+{
+    return X.ready + (int64_t)set * L.B;
+}
+__device__ __forceinline__ unsigned long long set_tag(const Scratch &X, int set)
+{
+    return (X.tags >> (set - X.set_base)) & 1ull;
 }
 
 // ------------------------------------------ cross-tile block reductions ---
 
-constexpr unsigned long long TAG_BIT = 1ull << 63;
-constexpr int MAX_PER_THREAD = 4;                       // partial words a thread polls
-constexpr int FUSE_LIMIT_MAX = MAX_PER_THREAD * THREADS; // tiles of the largest one-pass block
+struct BlockSpan {
+    int64_t bs, be;             // element range
+    int64_t t0;                 // first tile
+    int n;                      // tiles
+};
 
-__device__ __forceinline__ int block_tiles(const Layout &L, int64_t b)
+__device__ __forceinline__ BlockSpan block_span(const Layout &L, int64_t b)
 {
-    return (int)((L.offs[b + 1] - 1) / TILE - L.offs[b] / TILE + 1);
+    BlockSpan s;
+    s.bs = L.offs[b];
+    s.be = L.offs[b + 1];
+    s.t0 = s.bs / TILE;
+    s.n = (int)((s.be - 1) / TILE - s.t0 + 1);
+    return s;
 }
 
-// Scratch word of block b's segment in tile t (t0 = b's first tile): slot 1 of
-// tile t0 if b starts inside that tile (it is then the tile's last segment),
-// slot 0 everywhere else (first or only segment).
-__device__ __forceinline__ int64_t part_index(int64_t t, int64_t t0, int64_t bs)
+// Does the block own a whole tile?  Its first tile is shared (or ragged) if it
+// starts inside it, its last tile if it ends inside it; the tiles between are
+// its own.
+__device__ __forceinline__ bool has_uniform_tile(const BlockSpan &s)
 {
-    return 2 * t + ((t == t0 && (bs % TILE) != 0) ? 1 : 0);
+    return s.n - ((s.bs % TILE) != 0 ? 1 : 0) - ((s.be % TILE) != 0 ? 1 : 0) >= 1;
 }
 
-// Post the partial sum of an open segment of block b and, for a one-pass
-// block, count the arrival.  which: 0 = the tile's first (or only) segment,
-// 1 = its last segment.  Never waits; S.last[which] is valid after the next
-// __syncthreads().
+// One-pass blocks: their arrivals are counted and their scale is posted.
+__device__ __forceinline__ bool is_counted(const Layout &L, const BlockSpan &s)
+{
+    return s.n >= 2 && s.n <= L.fuse_limit && has_uniform_tile(s);
+}
+
+// Scratch word of block b's segment in tile t: slot 1 of the block's first tile
+// if b starts inside that tile (it is then the tile's last segment), slot 0
+// everywhere else (first or only segment).
+__device__ __forceinline__ int64_t part_index(int64_t t, const BlockSpan &s)
+{
+    return 2 * t + ((t == s.t0 && (s.bs % TILE) != 0) ? 1 : 0);
+}
+
+// What a tile has posted and may have to follow up on: for each of its (at most
+// two) open segments of counted blocks, the block, its tile count and -- in
+// thread 0 only -- the arrival count the block had before this tile.
+struct Posted {
+    int b[2];
+    int n[2];
+    unsigned prev[2];
+};
+
+__device__ __forceinline__ void clear_posted(Posted &P)
+{
+    P.b[0] = P.b[1] = -1;
+    P.n[0] = P.n[1] = 0;
+    P.prev[0] = P.prev[1] = 0;
+}
+
+// Post the partial sum of an open segment of block b and, for a counted block,
+// count the arrival.  which: 0 = the tile's first (or only) segment, 1 = its
+// last segment.  Never waits, not even for the counter's answer: that is looked
+// at in resolve_posted, after other work has been issued.
 __device__ __forceinline__ void post_partial(double partial, int which, int32_t tile, int64_t b, const Layout &L,
-                                             const SetCtx &C, TileShared &S)
+                                             const Scratch &X, int set, Posted &P)
 {
+    const BlockSpan sp = block_span(L, b);
+    const bool counted = is_counted(L, sp);
+    P.b[which] = counted ? (int)b : -1;
+    P.n[which] = sp.n;
     if (threadIdx.x == 0) {
-        const unsigned long long w = (unsigned long long)__double_as_longlong(partial) | (C.tag ? TAG_BIT : 0ull);
-        __hip_atomic_store(C.part + 2 * (int64_t)tile + which, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int last = 0;
-        const int n = block_tiles(L, b);
-        if (n <= L.fuse_limit) {
-            // The store above need not have landed when the count does: whoever
-            // reads the partials checks their tags.
-            const unsigned prev = __hip_atomic_fetch_add(C.cnt + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            last = (prev + 1u == (unsigned)n) ? 1 : 0;
-        }
-        S.last[which] = last;
+        const unsigned long long w =
+            (unsigned long long)__double_as_longlong(partial) | (set_tag(X, set) ? TAG_BIT : 0ull);
+        __hip_atomic_store(set_part(X, L, set) + 2 * (int64_t)tile + which, w, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        // The store above need not have landed when the count does: whoever
+        // reads the partials checks their tags.
+        if (counted)
+            P.prev[which] =
+                __hip_atomic_fetch_add(set_cnt(X, L, set) + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -279,36 +376,36 @@ __device__ __forceinline__ void post_partial(double partial, int which, int32_t 
 __device__ __forceinline__ double sum_block_partials(const Layout &L, int64_t b, const unsigned long long *part,
                                                      double *red)
 {
-    const int64_t bs = L.offs[b], be = L.offs[b + 1];
-    const int64_t t0 = bs / TILE, t1 = (be - 1) / TILE;
+    const BlockSpan sp = block_span(L, b);
     double acc = 0.0;
-    for (int64_t t = t0 + threadIdx.x; t <= t1; t += THREADS)
-        acc += __longlong_as_double((long long)(part[part_index(t, t0, bs)] & ~TAG_BIT));
+    for (int64_t i = threadIdx.x; i < sp.n; i += THREADS)
+        acc += __longlong_as_double((long long)(part[part_index(sp.t0 + i, sp)] & ~TAG_BIT));
     return block_sum(acc, red);
 }
 
 // Wait (bounded) until every tile of block b has posted this call's partial,
 // then form the block's scale.  Called by every thread of the workgroup with
 // the same arguments; returns the same answer to all of them.
-__device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const SetCtx &C, TileShared &S, float *s)
+__device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const Scratch &X, int set, TileShared &S,
+                                             float *s)
 {
-    const int64_t bs = L.offs[b], be = L.offs[b + 1];
-    const int64_t t0 = bs / TILE, t1 = (be - 1) / TILE;
-    const int n = (int)(t1 - t0 + 1);                   // <= fuse_limit <= FUSE_LIMIT_MAX
+    const BlockSpan sp = block_span(L, b);          // sp.n <= fuse_limit <= FUSE_LIMIT_MAX
+    const unsigned long long *part = set_part(X, L, set);
+    const unsigned long long tag = set_tag(X, set);
     double v[MAX_PER_THREAD];
     unsigned have = 0;
 #pragma unroll
     for (int q = 0; q < MAX_PER_THREAD; ++q) v[q] = 0.0;
     bool ok = false;
-    for (int it = 0; it < C.spin_limit; ++it) {
+    for (int it = 0; it < X.spin_limit; ++it) {
         int all = 1;
 #pragma unroll
         for (int q = 0; q < MAX_PER_THREAD; ++q) {
             const int i = (int)threadIdx.x + q * THREADS;
-            if (i < n && !((have >> q) & 1u)) {
-                const unsigned long long w = __hip_atomic_load(C.part + part_index(t0 + i, t0, bs), __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT);
-                if ((w >> 63) == C.tag) {
+            if (i < sp.n && !((have >> q) & 1u)) {
+                const unsigned long long w =
+                    __hip_atomic_load(part + part_index(sp.t0 + i, sp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((w >> 63) == tag) {
                     v[q] = __longlong_as_double((long long)(w & ~TAG_BIT));
                     have |= 1u << q;
                 } else {
@@ -327,49 +424,78 @@ __device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const S
 #pragma unroll
     for (int q = 0; q < MAX_PER_THREAD; ++q) acc += v[q];   // absent words were left at +0
     const double total = block_sum(acc, S.red);
-    *s = (float)(total / (double)(be - bs));
+    *s = (float)(total / (double)(sp.be - sp.bs));
     return true;
 }
 
-// The workgroup that arrived last at one-pass block b forms the scale from the
+// The workgroup that arrived last at counted block b forms the scale from the
 // partials (waiting, bounded, for those still in flight), writes it out and
 // posts it for the block's other tiles.  Called by every thread of that
 // workgroup.  Does not depend on the progress of any other workgroup.
-__device__ __forceinline__ bool finish_block(int64_t b, const Layout &L, const SetCtx &C, TileShared &S, float *s)
+__device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const Scratch &X, int set,
+                                             float *scales_out, TileShared &S)
 {
-    const bool ok = gather_scale(b, L, C, S, s);
+    float s;
+    const bool ok = gather_scale(b, L, X, set, S, &s);
     if (threadIdx.x == 0) {
-        __hip_atomic_store(C.cnt + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(set_cnt(X, L, set) + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (ok) {
-            C.scales_out[b] = *s;
-            __hip_atomic_store(C.ready + b, (C.tag << 32) | (unsigned long long)__float_as_uint(*s), __ATOMIC_RELAXED,
+            scales_out[b] = s;
+            __hip_atomic_store(set_ready(X, L, set) + b,
+                               (set_tag(X, set) << 32) | (unsigned long long)__float_as_uint(s), __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         } else {
-            const unsigned k = atomicAdd(C.fin_cnt, 1u);
-            C.fin_list[k] = ((unsigned long long)C.set << 32) | (unsigned long long)b;
+            const unsigned k = atomicAdd(X.fin_cnt, 1u);
+            X.fin_list[k] = ((unsigned long long)set << 32) | (unsigned long long)b;
         }
     }
-    return ok;
+}
+
+// Follow up on what a tile posted: where this workgroup was the last to arrive
+// at a block, finish that block.  Called by every thread of the workgroup.
+__device__ __forceinline__ void resolve_posted(const Posted &P, const Layout &L, const Scratch &X, int set,
+                                               float *scales_out, TileShared &S)
+{
+    if (P.b[0] < 0 && P.b[1] < 0) return;
+    if (threadIdx.x == 0) {
+        S.flag[0] = (P.b[0] >= 0 && P.prev[0] + 1u == (unsigned)P.n[0]) ? 1 : 0;
+        S.flag[1] = (P.b[1] >= 0 && P.prev[1] + 1u == (unsigned)P.n[1]) ? 1 : 0;
+    }
+    __syncthreads();
+    const bool last0 = S.flag[0] != 0, last1 = S.flag[1] != 0;
+    __syncthreads();
+    if (last0) finish_block(P.b[0], L, X, set, scales_out, S);
+    if (last1) finish_block(P.b[1], L, X, set, scales_out, S);
+}
+
+// Thread 0's early look at the ready word of block b (b < 0: none).
+__device__ __forceinline__ unsigned long long peek_ready(int b, const Layout &L, const Scratch &X, int set)
+{
+    unsigned long long w = ~0ull;          // its tag field can never match
+    if (threadIdx.x == 0 && b >= 0)
+        w = __hip_atomic_load(set_ready(X, L, set) + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return w;
 }
 
 // Wait (bounded) until the last arriver has posted block b's scale of this call.
-// Called by every thread of the workgroup; same answer to all of them.
-__device__ __forceinline__ bool wait_ready(int64_t b, const SetCtx &C, TileShared &S, float *s)
+// `peeked` is thread 0's earlier look at the word (see peek_ready).  Called by
+// every thread of the workgroup; same answer to all of them.
+__device__ __forceinline__ bool wait_ready(int64_t b, unsigned long long peeked, const Layout &L, const Scratch &X,
+                                           int set, TileShared &S, float *s)
 {
     if (threadIdx.x == 0) {
-        int found = 0;
-        unsigned bits = 0;
-        for (int it = 0; it < C.spin_limit; ++it) {
-            const unsigned long long w = __hip_atomic_load(C.ready + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((w >> 32) == C.tag) {
-                found = 1;
-                bits = (unsigned)w;
-                break;
-            }
-            __builtin_amdgcn_s_sleep(8);
+        const unsigned long long tag = set_tag(X, set);
+        const unsigned long long *word = set_ready(X, L, set) + b;
+        unsigned long long w = peeked;
+        int found = ((w >> 32) == tag) ? 1 : 0;
+        for (int it = 0; !found && it < X.spin_limit; ++it) {
+            w = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            found = ((w >> 32) == tag) ? 1 : 0;
+            if (!found) __builtin_amdgcn_s_sleep(8);
         }
+        if (X.spin_limit <= 0) found = 0;   // a zero budget means: never take the one-pass route
         S.flag[0] = found;
-        S.flag[1] = (int)bits;
+        S.flag[1] = (int)(unsigned)w;
     }
     __syncthreads();
     const bool ok = S.flag[0] != 0;
@@ -378,83 +504,32 @@ __device__ __forceinline__ bool wait_ready(int64_t b, const SetCtx &C, TileShare
     return ok;
 }
 
-// Leave an open segment whose p gets parked in the residual buffer to the
-// kernels that run after this one.
-__device__ __forceinline__ void defer_segment(int32_t tile, int which, const SetCtx &C)
+// Leave a segment whose p gets parked in the residual buffer to the kernels
+// that run after this one.
+__device__ __forceinline__ void defer_segment(int32_t tile, int which, const Scratch &X, int set)
 {
     if (threadIdx.x == 0) {
-        const unsigned i = atomicAdd(C.defer_cnt, 1u);
-        C.defer_list[i] = ((unsigned long long)C.set << 33) | ((unsigned long long)tile << 1) | (unsigned)which;
+        const unsigned i = atomicAdd(X.defer_cnt, 1u);
+        X.defer_list[i] = ((unsigned long long)set << 33) | ((unsigned long long)tile << 1) | (unsigned)which;
     }
 }
 
-// Compress the tile whose corrected values are in p[][] (Section 3.2): sign
-// words, block sums, scales, and the residual e' = p - Delta (Algorithm 4).
-template <bool FULL>
-__device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
-                                              uint64_t *signs, float *err_tile, const SetCtx &C, TileShared &S)
+// ------------------------------------------------------- tile compression ---
+
+// Mixed tile (several blocks meet): sign words; segmented fp64 sums through LDS;
+// scales and residuals e' = p - Delta of the closed segments; partial sums of
+// the (at most two) open segments posted, their elements stored as p for the
+// second-pass kernels.  Never waits for another workgroup.  (Section 3.2 and
+// e_{t+1} = p_t - Delta_t of Algorithm 4.)
+__device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
+                                               uint64_t *signs, float *scales_out, float *err_tile,
+                                               const Scratch &X, int set, TileShared &S, Posted &P)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
+    clear_posted(P);
+    store_signs(p, n_valid, signs, tile_start, L.W);
 
-    // --- signs
-    unsigned nib[SUBROWS];
-#pragma unroll
-    for (int k = 0; k < SUBROWS; ++k) {
-        const int lb0 = local_base(k);
-        unsigned n = (p[k].x >= 0.f ? 1u : 0u) | (p[k].y >= 0.f ? 2u : 0u) | (p[k].z >= 0.f ? 4u : 0u) |
-                     (p[k].w >= 0.f ? 8u : 0u);
-        if (!FULL) {
-            unsigned vm = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) vm |= (lb0 + c < n_valid) ? (1u << c) : 0u;
-            n &= vm;
-        }
-        nib[k] = n;
-    }
-    pack_and_store_signs(nib, signs, tile_start, L.W);
-
-    if (fb == lb) {
-        // --- one block covers the whole tile
-        double acc = 0.0;
-#pragma unroll
-        for (int k = 0; k < SUBROWS; ++k) {
-            const int lb0 = local_base(k);
-            const float a[4] = {fabsf(p[k].x), fabsf(p[k].y), fabsf(p[k].z), fabsf(p[k].w)};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc += (FULL || lb0 + c < n_valid) ? (double)a[c] : 0.0;
-        }
-        const double total = block_sum(acc, S.red);
-        const int64_t bs = L.offs[fb], be = L.offs[fb + 1];
-        const bool closed = (bs >= tile_start) && (be <= tile_start + TILE);
-        float s = 0.f;
-        bool have_scale = closed;
-        if (closed) {
-            s = (float)(total / (double)(be - bs));
-            if (threadIdx.x == 0) C.scales_out[fb] = s;
-        } else {
-            post_partial(total, 0, tile, fb, L, C, S);
-            if (block_tiles(L, fb) <= L.fuse_limit) {
-                __syncthreads();
-                have_scale = S.last[0] ? finish_block(fb, L, C, S, &s) : wait_ready(fb, C, S, &s);
-                if (!have_scale) defer_segment(tile, 0, C);
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < SUBROWS; ++k) {
-            float4 e = p[k];
-            if (have_scale) {
-                e.x = residual(p[k].x, s);
-                e.y = residual(p[k].y, s);
-                e.z = residual(p[k].z, s);
-                e.w = residual(p[k].w, s);
-            }
-            store4<FULL>(err_tile, local_base(k), n_valid, e);
-        }
-        return;
-    }
-
-    // --- several blocks meet in this tile: segmented sums through LDS
     const int nseg = lb - fb + 1;
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
@@ -481,7 +556,7 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
             S.open_sum[sg == 0 ? 0 : 1] = acc;
         } else {
             const float sc = (float)(acc / (double)(be - bs));
-            C.scales_out[b] = sc;
+            scales_out[b] = sc;
             for (int j = lo; j < hi; ++j) S.val[j] = sc;
         }
     }
@@ -501,30 +576,15 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
             if (lane_id() == 0) S.open_sum[sg == 0 ? 0 : 1] = acc;
         } else {
             const float sc = (float)(acc / (double)(be - bs));
-            if (lane_id() == 0) C.scales_out[b] = sc;
+            if (lane_id() == 0) scales_out[b] = sc;
             for (int j = lo + lane_id(); j < hi; j += 64) S.val[j] = sc;
         }
     }
     __syncthreads();
     const int head_end = head_open ? (int)min(L.offs[fb + 1] - tile_start, (int64_t)n_valid) : 0;
     const int tail_begin = tail_open ? (int)(L.offs[lb] - tile_start) : TILE;
-    // post everything this tile owes to others before waiting for anything
-    if (threadIdx.x == 0) S.last[0] = S.last[1] = 0;
-    if (head_open) post_partial(S.open_sum[0], 0, tile, fb, L, C, S);
-    if (tail_open) post_partial(S.open_sum[1], 1, tile, lb, L, C, S);
-    __syncthreads();
-    const bool head_fused = head_open && block_tiles(L, fb) <= L.fuse_limit;
-    const bool tail_fused = tail_open && block_tiles(L, lb) <= L.fuse_limit;
-    const bool head_last = head_fused && S.last[0], tail_last = tail_fused && S.last[1];
-    float s_head = 0.f, s_tail = 0.f;
-    bool have_head = false, have_tail = false;
-    // first what others wait for from this workgroup, then what it waits for itself
-    if (head_last) have_head = finish_block(fb, L, C, S, &s_head);
-    if (tail_last) have_tail = finish_block(lb, L, C, S, &s_tail);
-    if (head_fused && !head_last) have_head = wait_ready(fb, C, S, &s_head);
-    if (tail_fused && !tail_last) have_tail = wait_ready(lb, C, S, &s_tail);
-    if (head_fused && !have_head) defer_segment(tile, 0, C);
-    if (tail_fused && !have_tail) defer_segment(tile, 1, C);
+    if (head_open) post_partial(S.open_sum[0], 0, tile, fb, L, X, set, P);
+    if (tail_open) post_partial(S.open_sum[1], 1, tile, lb, L, X, set, P);
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         const int lb0 = local_base(k);
@@ -535,16 +595,69 @@ __device__ __forceinline__ void compress_tile(float4 (&p)[SUBROWS], const Layout
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int j = lb0 + c;
-            if (j < head_end) ev[c] = have_head ? residual(pv[c], s_head) : pv[c];
-            else if (j >= tail_begin) ev[c] = have_tail ? residual(pv[c], s_tail) : pv[c];
-            else ev[c] = residual(pv[c], sv[c]);
+            ev[c] = (j < head_end || j >= tail_begin) ? pv[c] : residual(pv[c], sv[c]);
         }
-        store4<FULL>(err_tile, lb0, n_valid, make_float4(ev[0], ev[1], ev[2], ev[3]));
+        p[k] = make_float4(ev[0], ev[1], ev[2], ev[3]);
     }
+    store_tile(err_tile, p, n_valid);
+    __syncthreads();            // S.val is free again
 }
 
-// Fill S.val (read as int) with the segment index of every element of a tile
-// that several blocks share, so that element j can look up scale[fb + seg].
+// Uniform tile (inside one block b): sign words and the tile's fp64 sum.
+// Returns what is left to do with it:
+//   UNI_DONE    the block is this tile alone: scale and residual written;
+//   UNI_PARKED  block larger than fuse_limit: partial posted, p parked for the
+//               second-pass kernels;
+//   UNI_PENDING partial posted and arrival counted (P): p stays with the caller
+//               until the block's scale is posted.
+enum { UNI_DONE = 0, UNI_PARKED = 1, UNI_PENDING = 2 };
+
+__device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
+                                                uint64_t *signs, float *scales_out, float *err_tile,
+                                                const Scratch &X, int set, TileShared &S, Posted &P)
+{
+    const int64_t tile_start = (int64_t)tile * TILE;
+    const int32_t b = L.tile_fb[tile];
+    clear_posted(P);
+    store_signs(p, n_valid, signs, tile_start, L.W);
+    const double total = block_sum(abs_sum(p, n_valid), S.red);
+    const int64_t bs = L.offs[b], be = L.offs[b + 1];
+    if (bs >= tile_start && be <= tile_start + TILE) {
+        const float s = (float)(total / (double)(be - bs));
+        if (threadIdx.x == 0) scales_out[b] = s;
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) residual4(p[k], s);
+        store_tile(err_tile, p, n_valid);
+        return UNI_DONE;
+    }
+    post_partial(total, 0, tile, b, L, X, set, P);
+    if (P.b[0] < 0) {
+        store_tile(err_tile, p, n_valid);
+        return UNI_PARKED;
+    }
+    return UNI_PENDING;
+}
+
+// Write the residual of a uniform tile of counted block b whose p was kept
+// (e_{t+1} = p_t - Delta_t, Algorithm 4), waiting (bounded) for the scale; if
+// the wait runs out, p is parked and the segment deferred.
+__device__ __forceinline__ void finish_uniform(float4 (&p)[SUBROWS], int32_t tile, int n_valid, int b,
+                                               unsigned long long peeked, float *err_tile, const Layout &L,
+                                               const Scratch &X, int set, TileShared &S)
+{
+    float s;
+    const bool ok = wait_ready(b, peeked, L, X, set, S, &s);
+    if (ok) {
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) residual4(p[k], s);
+    } else {
+        defer_segment(tile, 0, X, set);
+    }
+    store_tile(err_tile, p, n_valid);
+}
+
+// Fill S.val (read as int) with the segment index of every element of a mixed
+// tile, so that element j can look up scale[fb + seg].
 __device__ __forceinline__ void build_segment_index(const Layout &L, int32_t tile, int n_valid, int32_t fb,
                                                     int nseg, TileShared &S)
 {
@@ -572,66 +685,198 @@ __device__ __forceinline__ void build_segment_index(const Layout &L, int32_t til
     __syncthreads();
 }
 
-// ------------------------------------------------------------- kernels ---
+// --------------------------------------------------------- worker kernels ---
 
-// Worker (Algorithm 4, "on each worker i"): momentum, corrected value p, sign
-// words, block scales, residual.
-template <bool FULL>
-__device__ __forceinline__ void worker_tile(const Layout &L, const Scratch &X, const WorkerArgs &A, int32_t tile,
-                                            int worker, int n_valid, TileShared &S)
+// m <- mu*m + g and p = mu*m + g + r*e (Algorithm 4, "on each worker i"), one
+// rounding per operation, left to right.  m is overwritten with the new
+// momentum, e with p.
+__device__ __forceinline__ void worker_values(const float4 (&g)[SUBROWS], float4 (&m)[SUBROWS], float4 (&e)[SUBROWS],
+                                              float mu, float r)
 {
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k) {
+        m[k].x = mu * m[k].x + g[k].x;
+        m[k].y = mu * m[k].y + g[k].y;
+        m[k].z = mu * m[k].z + g[k].z;
+        m[k].w = mu * m[k].w + g[k].w;
+        e[k].x = (mu * m[k].x + g[k].x) + r * e[k].x;
+        e[k].y = (mu * m[k].y + g[k].y) + r * e[k].y;
+        e[k].z = (mu * m[k].z + g[k].z) + r * e[k].z;
+        e[k].w = (mu * m[k].w + g[k].w) + r * e[k].w;
+    }
+}
+
+// Mixed tiles of all workers, one workgroup per (tile, worker).  Runs before
+// the uniform-tile kernel of the same call.
+__global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, WorkerArgs A)
+{
+    __shared__ TileShared S;
+    const int32_t tile = L.mixed_tiles[blockIdx.x];
+    const int worker = blockIdx.y;
+    const int n_valid = tile_valid(L, tile);
     const int64_t tile_start = (int64_t)tile * TILE;
     const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
     float *m = A.mom + (int64_t)worker * A.state_stride + tile_start;
     float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
-    float4 p[SUBROWS];
-    float4 gv[SUBROWS], mv[SUBROWS], ev[SUBROWS];
-#pragma unroll
-    for (int k = 0; k < SUBROWS; ++k) {
-        gv[k] = load4<FULL>(g, local_base(k), n_valid);
-        mv[k] = load4<FULL>(m, local_base(k), n_valid);
-        ev[k] = load4<FULL>(e, local_base(k), n_valid);
-    }
-    const float mu = A.mu, r = A.r;
-#pragma unroll
-    for (int k = 0; k < SUBROWS; ++k) {
-        float4 mn;
-        mn.x = mu * mv[k].x + gv[k].x;
-        mn.y = mu * mv[k].y + gv[k].y;
-        mn.z = mu * mv[k].z + gv[k].z;
-        mn.w = mu * mv[k].w + gv[k].w;
-        store4<FULL>(m, local_base(k), n_valid, mn);
-        p[k].x = (mu * mn.x + gv[k].x) + r * ev[k].x;
-        p[k].y = (mu * mn.y + gv[k].y) + r * ev[k].y;
-        p[k].z = (mu * mn.z + gv[k].z) + r * ev[k].z;
-        p[k].w = (mu * mn.w + gv[k].w) + r * ev[k].w;
-    }
-    const SetCtx C = make_ctx(X, L, worker, A.scales + (int64_t)worker * L.B);
-    compress_tile<FULL>(p, L, tile, n_valid, A.signs + (int64_t)worker * L.W, e, C, S);
+    float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
+    load_tile(g, gv, n_valid);
+    load_tile(m, mv, n_valid);
+    load_tile(e, pv, n_valid);
+    worker_values(gv, mv, pv, A.mu, A.r);
+    store_tile(m, mv, n_valid);
+    Posted P;
+    float *scales_out = A.scales + (int64_t)worker * L.B;
+    compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W, scales_out, e, X, worker, S, P);
+    resolve_posted(P, L, X, worker, scales_out, S);
 }
 
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_worker(Layout L, Scratch X, WorkerArgs A)
+// Uniform tiles of all workers, as a persistent kernel.
+//
+// Every workgroup loops: take the next tile, issue its loads, and while they
+// are in flight write out the oldest of the PIPE_DEPTH tiles it holds in
+// registers (their blocks' scales have had PIPE_DEPTH tile-times to form, so
+// the wait is normally over before it starts); then compute the new tile, post
+// its partial sum and keep it in turn.  Tiles are handed out through one ticket
+// counter, TICKET_TILES at a time, so at any moment the resident workgroups
+// work on one compact, advancing window of the five fp32 streams (best DRAM
+// page locality, no dependence on dispatch order), and a workgroup never waits
+// while it holds a tile it has not posted: a wait can only starve if one block
+// had more than (resident workgroups x PIPE_DEPTH) uniform tiles, which
+// fuse_limit rules out, and is bounded by spin_limit in any case.
+struct HeldTile {
+    float4 p[SUBROWS];
+    int32_t tile;
+    int set;
+    int b;                      // < 0: slot empty
+};
+
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
+{
+    __shared__ TileShared S;
+    const unsigned nchunks = (unsigned)((L.n_uniform + TICKET_TILES - 1) / TICKET_TILES);
+    const unsigned total = nchunks * (unsigned)n_workers;
+
+    HeldTile held[PIPE_DEPTH];
+#pragma unroll
+    for (int q = 0; q < PIPE_DEPTH; ++q) held[q].b = -1;
+    Posted posted;
+    clear_posted(posted);
+    int posted_set = 0;
+
+    unsigned tk_next = 0;       // thread 0: the ticket taken ahead of need
+    if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);
+    int cur = 0, cur_end = 0, cur_set = 0;
+
+    for (;;) {
+        // ---- next tile
+        if (cur >= cur_end) {
+            if (threadIdx.x == 0) S.ticket = tk_next;
+            __syncthreads();
+            const unsigned t = (unsigned)__builtin_amdgcn_readfirstlane((int)S.ticket);
+            __syncthreads();
+            if (t >= total) break;
+            cur_set = (int)(t / nchunks);
+            cur = (int)(t % nchunks) * TICKET_TILES;
+            cur_end = min(cur + TICKET_TILES, L.n_uniform);
+            if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);   // answer is read at the next chunk
+        }
+        const int32_t tile = L.uniform_tiles[cur++];
+        const int worker = cur_set;
+        constexpr int n_valid = TILE;      // uniform tiles are full tiles
+        const int64_t tile_start = (int64_t)tile * TILE;
+        const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
+        float *m = A.mom + (int64_t)worker * A.state_stride + tile_start;
+        float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
+
+        // ---- this tile's loads go out first
+        float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
+        load_tile(g, gv, n_valid);
+        load_tile(m, mv, n_valid);
+        load_tile(e, pv, n_valid);
+
+        // ---- while they fly: follow up on the previous tile's post, write out the oldest tile held
+        HeldTile &old = held[0];
+        const unsigned long long peeked = peek_ready(old.b, L, X, old.b >= 0 ? old.set : 0);
+        resolve_posted(posted, L, X, posted_set, A.scales + (int64_t)posted_set * L.B, S);
+        if (old.b >= 0) {
+            float *e_old = A.err + (int64_t)old.set * A.state_stride + (int64_t)old.tile * TILE;
+            finish_uniform(old.p, old.tile, TILE, old.b, peeked, e_old, L, X, old.set, S);
+        }
+#pragma unroll
+        for (int q = 0; q + 1 < PIPE_DEPTH; ++q) held[q] = held[q + 1];
+
+        // ---- the new tile
+        worker_values(gv, mv, pv, A.mu, A.r);
+        store_tile(m, mv, n_valid);
+        HeldTile &slot = held[PIPE_DEPTH - 1];
+        const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W,
+                                          A.scales + (int64_t)worker * L.B, e, X, worker, S, posted);
+        posted_set = worker;
+        slot.b = -1;
+        if (kind == UNI_PENDING) {
+#pragma unroll
+            for (int k = 0; k < SUBROWS; ++k) slot.p[k] = pv[k];
+            slot.tile = tile;
+            slot.set = worker;
+            slot.b = posted.b[0];
+        }
+    }
+
+    // ---- drain
+    resolve_posted(posted, L, X, posted_set, A.scales + (int64_t)posted_set * L.B, S);
+#pragma unroll
+    for (int q = 0; q < PIPE_DEPTH; ++q) {
+        if (held[q].b >= 0) {
+            float *e_q = A.err + (int64_t)held[q].set * A.state_stride + (int64_t)held[q].tile * TILE;
+            finish_uniform(held[q].p, held[q].tile, TILE, held[q].b, ~0ull, e_q, L, X, held[q].set, S);
+        }
+    }
+}
+
+// Uniform tiles of all workers, one workgroup per (tile, worker): the same
+// steps without the pipeline; the workgroup waits in place for its block's
+// scale.  Relies on workgroups being dispatched in grid order (fuse_limit keeps
+// a block's tiles well inside what is resident at once) and on spin_limit.
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
+{
+    __shared__ TileShared S;
+    const int32_t tile = L.uniform_tiles[blockIdx.x];
+    const int worker = blockIdx.y;
+    constexpr int n_valid = TILE;
+    const int64_t tile_start = (int64_t)tile * TILE;
+    const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
+    float *m = A.mom + (int64_t)worker * A.state_stride + tile_start;
+    float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
+    float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
+    load_tile(g, gv, n_valid);
+    load_tile(m, mv, n_valid);
+    load_tile(e, pv, n_valid);
+    worker_values(gv, mv, pv, A.mu, A.r);
+    store_tile(m, mv, n_valid);
+    Posted P;
+    float *scales_out = A.scales + (int64_t)worker * L.B;
+    const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W, scales_out, e, X, worker,
+                                      S, P);
+    resolve_posted(P, L, X, worker, scales_out, S);
+    if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, P.b[0], ~0ull, e, L, X, worker, S);
+}
+
+// --------------------------------------------------------- server kernel ---
+
+// Server (Algorithm 4, "on server"): decode and add the M payloads in worker
+// order, divide by M, add the rescaled server residual, compress.  One
+// workgroup per tile; a uniform tile of a counted block waits in the kernel.
+__global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerArgs A, int set)
 {
     __shared__ TileShared S;
     const int32_t tile = blockIdx.x;
-    const int worker = blockIdx.y;
-    const int64_t left = L.d - (int64_t)tile * TILE;
-    if (left >= TILE) worker_tile<true>(L, X, A, tile, worker, TILE, S);
-    else worker_tile<false>(L, X, A, tile, worker, (int)left, S);
-}
-
-// Server (Algorithm 4, "on server"): decode and add the M payloads in worker
-// order, divide by M, add the rescaled server residual, compress.
-template <bool FULL>
-__device__ __forceinline__ void server_tile(const Layout &L, const Scratch &X, const ServerArgs &A, int32_t tile,
-                                            int set, int n_valid, TileShared &S)
-{
+    const int n_valid = tile_valid(L, tile);
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     float *te = A.err + tile_start;
     float4 tv[SUBROWS];
-#pragma unroll
-    for (int k = 0; k < SUBROWS; ++k) tv[k] = load4<FULL>(te, local_base(k), n_valid);
+    load_tile(te, tv, n_valid);
 
     float acc[SUBROWS][4];
 #pragma unroll
@@ -658,7 +903,7 @@ __device__ __forceinline__ void server_tile(const Layout &L, const Scratch &X, c
                 const int j = local_base(k) + c;
                 segi[k][c] = (j < n_valid) ? seg[j] : 0;
             }
-        __syncthreads();        // S.val is reused by compress_tile
+        __syncthreads();        // S.val is reused by compress_mixed
     }
     for (int i = 0; i < A.M; ++i) {
         const float *sc_i = A.scales_in + (int64_t)i * L.B + fb;
@@ -683,18 +928,18 @@ __device__ __forceinline__ void server_tile(const Layout &L, const Scratch &X, c
         p[k].z = acc[k][2] / Mf + r * tv[k].z;
         p[k].w = acc[k][3] / Mf + r * tv[k].w;
     }
-    const SetCtx C = make_ctx(X, L, set, A.scales);
-    compress_tile<FULL>(p, L, tile, n_valid, A.signs, te, C, S);
+    Posted P;
+    if (fb != lb || n_valid != TILE) {
+        compress_mixed(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
+        resolve_posted(P, L, X, set, A.scales, S);
+    } else {
+        const int kind = compress_uniform(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
+        resolve_posted(P, L, X, set, A.scales, S);
+        if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, P.b[0], ~0ull, te, L, X, set, S);
+    }
 }
 
-__global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerArgs A, int set)
-{
-    __shared__ TileShared S;
-    const int32_t tile = blockIdx.x;
-    const int64_t left = L.d - (int64_t)tile * TILE;
-    if (left >= TILE) server_tile<true>(L, X, A, tile, set, TILE, S);
-    else server_tile<false>(L, X, A, tile, set, (int)left, S);
-}
+// ---------------------------------------------------- second-pass kernels ---
 
 // e <- p - Delta on one open segment of a tile whose p was parked in the
 // residual buffer (e_{t+1} = p_t - Delta_t of Algorithm 4), now that every scale
@@ -704,8 +949,7 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
                                                  const float *scales)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
-    const int64_t left = L.d - tile_start;
-    const int n_valid = left >= TILE ? TILE : (int)left;
+    const int n_valid = tile_valid(L, tile);
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     float *err_tile = err_set + tile_start;
     int lo, hi;
@@ -725,10 +969,7 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
         if (lb0 >= hi || lb0 + 4 <= lo) continue;
         if (lb0 >= lo && lb0 + 4 <= hi) {
             float4 v = *reinterpret_cast<const float4 *>(err_tile + lb0);
-            v.x = residual(v.x, s);
-            v.y = residual(v.y, s);
-            v.z = residual(v.z, s);
-            v.w = residual(v.w, s);
+            residual4(v, s);
             *reinterpret_cast<float4 *>(err_tile + lb0) = v;
         } else {
             // the other elements of this float4 belong to another segment, which
@@ -742,20 +983,19 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
     }
 }
 
-// Scales the first kernel of a call did not write: those of blocks larger than
-// fuse_limit (list fixed per layout: workgroups 0 .. n_big*nsets-1) and those
-// whose first tile gave up waiting (list filled by the first kernel: the last
-// DEFER_WGS workgroups).
-__global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X, const int32_t *big_blocks,
-                                                             int n_big, int nsets, float *scales)
+// Scales the first kernels of a call did not write: those of the blocks on the
+// per-layout list (crossing blocks without a uniform tile, blocks larger than
+// fuse_limit: workgroups 0 .. n_late*nsets-1) and those whose last arriver gave
+// up gathering (list filled at run time: the last DEFER_WGS workgroups).
+__global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X, const int32_t *late_blocks,
+                                                             int n_late, int nsets, float *scales)
 {
     __shared__ double red[NWAVES];
-    const int n_static = n_big * nsets;
+    const int n_static = n_late * nsets;
     if ((int)blockIdx.x < n_static) {
-        const int64_t b = big_blocks[blockIdx.x % n_big];
-        const int w = blockIdx.x / n_big;
-        const double total =
-            sum_block_partials(L, b, X.part + (int64_t)(X.set_base + w) * 2 * L.ntiles, red);
+        const int64_t b = late_blocks[blockIdx.x % n_late];
+        const int w = blockIdx.x / n_late;
+        const double total = sum_block_partials(L, b, set_part(X, L, X.set_base + w), red);
         if (threadIdx.x == 0) scales[(int64_t)w * L.B + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
         return;
     }
@@ -764,24 +1004,26 @@ __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X
         const unsigned long long it = X.fin_list[i];
         const int set = (int)(it >> 32);
         const int64_t b = (int64_t)(it & 0xffffffffull);
-        const double total = sum_block_partials(L, b, X.part + (int64_t)set * 2 * L.ntiles, red);
+        const double total = sum_block_partials(L, b, set_part(X, L, set), red);
         if (threadIdx.x == 0)
             scales[(int64_t)(set - X.set_base) * L.B + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
     }
 }
 
-// e <- p - Delta wherever the first kernel parked p: the open segments of blocks
-// larger than fuse_limit (list fixed per layout: workgroups 0 .. n_items*nsets-1)
-// and the segments whose wait ran out (list filled by the first kernel: the last
-// DEFER_WGS workgroups).  Also clears the list counters the next call will use.
+// e <- p - Delta wherever the first kernels parked p: the segments on the
+// per-layout list (open segments of mixed tiles, tiles of blocks larger than
+// fuse_limit: workgroups 0 .. n_items*nsets-1) and the tiles whose wait ran out
+// (list filled at run time: the last DEFER_WGS workgroups).  Also clears the
+// counters the next call will use.
 __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X, const uint32_t *items,
                                                              int n_items, int nsets, unsigned int *next_defer_cnt,
-                                                             unsigned int *next_fin_cnt, float *err,
-                                                             int64_t err_stride, const float *scales)
+                                                             unsigned int *next_fin_cnt, unsigned int *next_ticket,
+                                                             float *err, int64_t err_stride, const float *scales)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *next_defer_cnt = 0u;
         *next_fin_cnt = 0u;
+        *next_ticket = 0u;
     }
     const int n_static = n_items * nsets;
     if ((int)blockIdx.x < n_static) {
@@ -800,11 +1042,15 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X
     }
 }
 
+// ----------------------------------------------------------- apply kernel ---
+
 // Parameter update x <- x - eta * Delta~ (Algorithm 4).
-template <bool FULL>
-__device__ __forceinline__ void apply_tile(const Layout &L, int32_t tile, int n_valid, float *x,
-                                           const uint64_t *signs, const float *scales, float eta, TileShared &S)
+__global__ __launch_bounds__(THREADS) void k_apply(Layout L, float *x, const uint64_t *signs,
+                                                   const float *scales, float eta)
 {
+    __shared__ TileShared S;
+    const int32_t tile = blockIdx.x;
+    const int n_valid = tile_valid(L, tile);
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     float *xt = x + tile_start;
@@ -812,37 +1058,28 @@ __device__ __forceinline__ void apply_tile(const Layout &L, int32_t tile, int n_
     const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
     const int64_t n_hw = 2 * L.W;
     const int *seg = reinterpret_cast<const int *>(S.val);
+    float4 xv4[SUBROWS];
+    load_tile(xt, xv4, n_valid);
     if (fb != lb) build_segment_index(L, tile, n_valid, fb, lb - fb + 1, S);
     const float s_uniform = scales[fb];
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         const int lb0 = local_base(k);
-        if (!FULL && lb0 >= n_valid) continue;
-        const float4 v = load4<FULL>(xt, lb0, n_valid);
         const int64_t hw = (tile_start + lb0) >> 5;
         const uint32_t word = (hw < n_hw) ? s32[hw] : 0u;
         const unsigned nibble = (word >> sh) & 0xFu;
-        float xv[4] = {v.x, v.y, v.z, v.w};
+        float xv[4] = {xv4[k].x, xv4[k].y, xv4[k].z, xv4[k].w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int j = lb0 + c;
             float s = s_uniform;
-            if (fb != lb) s = scales[fb + ((FULL || j < n_valid) ? seg[j] : 0)];
+            if (fb != lb) s = scales[fb + ((j < n_valid) ? seg[j] : 0)];
             const float u = eta * signed_scale(s, (nibble >> c) & 1u);
             xv[c] = xv[c] - u;
         }
-        store4<FULL>(xt, lb0, n_valid, make_float4(xv[0], xv[1], xv[2], xv[3]));
+        xv4[k] = make_float4(xv[0], xv[1], xv[2], xv[3]);
     }
-}
-
-__global__ __launch_bounds__(THREADS) void k_apply(Layout L, float *x, const uint64_t *signs,
-                                                   const float *scales, float eta)
-{
-    __shared__ TileShared S;
-    const int32_t tile = blockIdx.x;
-    const int64_t left = L.d - (int64_t)tile * TILE;
-    if (left >= TILE) apply_tile<true>(L, tile, TILE, x, signs, scales, eta, S);
-    else apply_tile<false>(L, tile, (int)left, x, signs, scales, eta, S);
+    store_tile(xt, xv4, n_valid);
 }
 
 }  // namespace ef

@@ -71,6 +71,11 @@ class GpuState:
             self.plan.tune(spin_limit=0)
         elif route == "mixed":           # blocks of <= 2 tiles in one pass, larger ones in two
             self.plan.tune(fuse_limit=2)
+        elif route == "persistent":      # pipelined persistent kernel over the single-block tiles
+            self.plan.set_persistent(True)
+        elif route == "persistent_deferred":
+            self.plan.set_persistent(True)
+            self.plan.tune(spin_limit=0)
         elif route != "one_pass":
             raise ValueError(route)
         ds = ((self.d + 3) // 4) * 4 + 4 * pad           # row stride, multiple of 4

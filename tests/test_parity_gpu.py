@@ -59,7 +59,7 @@ def _grads(rng, T, M, d, zeros=0.0, scale=1.0):
     return g
 
 
-ROUTES = ["one_pass", "two_pass", "deferred", "mixed"]
+ROUTES = ["one_pass", "two_pass", "deferred", "mixed", "persistent", "persistent_deferred"]
 
 
 @pytest.mark.parametrize("route", ROUTES)
@@ -89,7 +89,7 @@ def test_server_worker_counts(M):
     offs = _offs(LAYOUTS["mixed_tiny_and_big"])
     d = int(offs[-1])
     rng = np.random.default_rng(M)
-    st = GpuState(offs, M, route=ROUTES[M % 4])
+    st = GpuState(offs, M, route=ROUTES[M % len(ROUTES)])
     eta_prev = 0.0
     for t in range(2):
         st.set_grads(_grads(rng, 1, M, d)[0])
