@@ -96,9 +96,9 @@ int ef_plan_fuse_limit(const ef_plan *plan);
 
 /*
  * Which kernel ef_worker_step runs over the tiles that lie inside one block:
- * on = 0 (default) one workgroup per tile that waits in place for its block's
- * scale; on = 1 a persistent kernel whose workgroups take tiles from a ticket
- * counter and keep several tiles in registers while their scales form.  Same
+ * on = 1 (default) a persistent kernel whose workgroups take tiles from a ticket
+ * counter and keep several tiles in registers while their scales form; on = 0
+ * one workgroup per tile that waits in place for its block's scale.  Same
  * results either way.  Synchronises the device.
  */
 int ef_plan_set_persistent(ef_plan *plan, int on);

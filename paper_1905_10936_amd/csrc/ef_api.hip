@@ -231,7 +231,7 @@ int build_device(ef_plan *p)
         p->L.fuse_limit = (int32_t)lim;
     }
     p->spin_limit = 1 << 14;
-    p->persistent = 0;
+    p->persistent = 1;
     p->calls = 0;
     int rc = upload_static_list(p);
     if (rc) return rc;

@@ -351,24 +351,37 @@ __device__ __forceinline__ void clear_posted(Posted &P)
 // count the arrival.  which: 0 = the tile's first (or only) segment, 1 = its
 // last segment.  Never waits, not even for the counter's answer: that is looked
 // at in resolve_posted, after other work has been issued.
-__device__ __forceinline__ void post_partial(double partial, int which, int32_t tile, int64_t b, const Layout &L,
-                                             const Scratch &X, int set, Posted &P)
+__device__ __forceinline__ void store_partial(double partial, int which, int32_t tile, const Layout &L,
+                                              const Scratch &X, int set)
 {
-    const BlockSpan sp = block_span(L, b);
-    const bool counted = is_counted(L, sp);
-    P.b[which] = counted ? (int)b : -1;
-    P.n[which] = sp.n;
     if (threadIdx.x == 0) {
         const unsigned long long w =
             (unsigned long long)__double_as_longlong(partial) | (set_tag(X, set) ? TAG_BIT : 0ull);
         __hip_atomic_store(set_part(X, L, set) + 2 * (int64_t)tile + which, w, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
-        // The store above need not have landed when the count does: whoever
-        // reads the partials checks their tags.
-        if (counted)
-            P.prev[which] =
-                __hip_atomic_fetch_add(set_cnt(X, L, set) + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+}
+
+// Count this tile's arrival at block b if b is a counted block.  The count may
+// run ahead of the partials: whoever reads the partials checks their tags, so a
+// tile may announce itself before it has even loaded its data (which takes the
+// counter's round trip off the critical path).  Never waits for the answer.
+__device__ __forceinline__ void announce_arrival(int which, int64_t b, const Layout &L, const Scratch &X, int set,
+                                                 Posted &P)
+{
+    const BlockSpan sp = block_span(L, b);
+    const bool counted = is_counted(L, sp);
+    P.b[which] = counted ? (int)b : -1;
+    P.n[which] = sp.n;
+    if (threadIdx.x == 0 && counted)
+        P.prev[which] = __hip_atomic_fetch_add(set_cnt(X, L, set) + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void post_partial(double partial, int which, int32_t tile, int64_t b, const Layout &L,
+                                             const Scratch &X, int set, Posted &P)
+{
+    store_partial(partial, which, tile, L, X, set);
+    announce_arrival(which, b, L, X, set, P);
 }
 
 // Sum of block b's partials once the kernel that posted them has finished.
@@ -612,13 +625,24 @@ __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layou
 //               until the block's scale is posted.
 enum { UNI_DONE = 0, UNI_PARKED = 1, UNI_PENDING = 2 };
 
-__device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
-                                                uint64_t *signs, float *scales_out, float *err_tile,
-                                                const Scratch &X, int set, TileShared &S, Posted &P)
+// The caller has announced the tile beforehand (announce_uniform), P is its
+// record.
+__device__ __forceinline__ void announce_uniform(const Layout &L, int32_t tile, const Scratch &X, int set, Posted &P)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t b = L.tile_fb[tile];
     clear_posted(P);
+    const int64_t bs = L.offs[b], be = L.offs[b + 1];
+    if (bs >= tile_start && be <= tile_start + TILE) return;     // the block is this tile alone
+    announce_arrival(0, b, L, X, set, P);
+}
+
+__device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
+                                                uint64_t *signs, float *scales_out, float *err_tile,
+                                                const Scratch &X, int set, TileShared &S, const Posted &P)
+{
+    const int64_t tile_start = (int64_t)tile * TILE;
+    const int32_t b = L.tile_fb[tile];
     store_signs(p, n_valid, signs, tile_start, L.W);
     const double total = block_sum(abs_sum(p, n_valid), S.red);
     const int64_t bs = L.offs[b], be = L.offs[b + 1];
@@ -630,7 +654,7 @@ __device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layo
         store_tile(err_tile, p, n_valid);
         return UNI_DONE;
     }
-    post_partial(total, 0, tile, b, L, X, set, P);
+    store_partial(total, 0, tile, L, X, set);
     if (P.b[0] < 0) {
         store_tile(err_tile, p, n_valid);
         return UNI_PARKED;
@@ -798,6 +822,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
         HeldTile &old = held[0];
         const unsigned long long peeked = peek_ready(old.b, L, X, old.b >= 0 ? old.set : 0);
         resolve_posted(posted, L, X, posted_set, A.scales + (int64_t)posted_set * L.B, S);
+        announce_uniform(L, tile, X, worker, posted);
         if (old.b >= 0) {
             float *e_old = A.err + (int64_t)old.set * A.state_stride + (int64_t)old.tile * TILE;
             finish_uniform(old.p, old.tile, TILE, old.b, peeked, e_old, L, X, old.set, S);
@@ -848,13 +873,14 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
     const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
     float *m = A.mom + (int64_t)worker * A.state_stride + tile_start;
     float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
+    Posted P;
+    announce_uniform(L, tile, X, worker, P);       // the counter's answer returns under the loads
     float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
     load_tile(g, gv, n_valid);
     load_tile(m, mv, n_valid);
     load_tile(e, pv, n_valid);
     worker_values(gv, mv, pv, A.mu, A.r);
     store_tile(m, mv, n_valid);
-    Posted P;
     float *scales_out = A.scales + (int64_t)worker * L.B;
     const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W, scales_out, e, X, worker,
                                       S, P);
@@ -875,6 +901,10 @@ __global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerA
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     float *te = A.err + tile_start;
+    const bool uniform = (fb == lb) && (n_valid == TILE);
+    Posted P;
+    clear_posted(P);
+    if (uniform) announce_uniform(L, tile, X, set, P);   // the counter's answer returns under the loads
     float4 tv[SUBROWS];
     load_tile(te, tv, n_valid);
 
@@ -928,8 +958,7 @@ __global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerA
         p[k].z = acc[k][2] / Mf + r * tv[k].z;
         p[k].w = acc[k][3] / Mf + r * tv[k].w;
     }
-    Posted P;
-    if (fb != lb || n_valid != TILE) {
+    if (!uniform) {
         compress_mixed(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
         resolve_posted(P, L, X, set, A.scales, S);
     } else {

@@ -65,17 +65,16 @@ class GpuState:
         self.W = (self.d + 63) // 64
         self.plan = ef.ef_plan_create(self.offs, max(M, 1))
         # which way e <- p - Delta is finished for blocks that span several tiles
+        if route in ("direct", "direct_deferred", "direct_mixed"):
+            self.plan.set_persistent(False)      # one workgroup per tile, waiting in place
         if route == "two_pass":          # every such block through the second kernel
             self.plan.tune(fuse_limit=0)
-        elif route == "deferred":        # every wait gives up at once -> deferral list
+        elif route in ("deferred", "direct_deferred"):   # every wait gives up at once -> deferral list
             self.plan.tune(spin_limit=0)
-        elif route == "mixed":           # blocks of <= 2 tiles in one pass, larger ones in two
+        elif route in ("mixed", "direct_mixed"):         # blocks of <= 2 tiles in one pass, larger ones in two
             self.plan.tune(fuse_limit=2)
-        elif route == "persistent":      # pipelined persistent kernel over the single-block tiles
-            self.plan.set_persistent(True)
-        elif route == "persistent_deferred":
-            self.plan.set_persistent(True)
-            self.plan.tune(spin_limit=0)
+        elif route == "direct":
+            pass
         elif route != "one_pass":
             raise ValueError(route)
         ds = ((self.d + 3) // 4) * 4 + 4 * pad           # row stride, multiple of 4

@@ -59,7 +59,7 @@ def _grads(rng, T, M, d, zeros=0.0, scale=1.0):
     return g
 
 
-ROUTES = ["one_pass", "two_pass", "deferred", "mixed", "persistent", "persistent_deferred"]
+ROUTES = ["one_pass", "two_pass", "deferred", "mixed", "direct", "direct_deferred", "direct_mixed"]
 
 
 @pytest.mark.parametrize("route", ROUTES)
