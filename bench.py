@@ -27,9 +27,10 @@ import paper_1905_10936_amd as ef  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE +
-# WRITE_SIZE, scaled by a copy kernel of known size); None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE, scaled by a torch add kernel of known size run
+# in the same process): see profiles/ef_step_flat_2p28.md.  None where not measured.
+MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43303450389}
 
 
 def algorithmic_bytes(d, B, M):
@@ -73,6 +74,8 @@ def main():
     ap.add_argument("--fuse-limit", type=int, default=-1, help="override the plan's one-pass block limit")
     ap.add_argument("--spin-limit", type=int, default=-1, help="override the plan's wait budget")
     ap.add_argument("--persistent", type=int, default=-1, help="1/0: force the persistent worker kernel on/off")
+    ap.add_argument("--calib", action="store_true",
+                    help="also run a plain 1 GiB -> 1 GiB elementwise kernel (known size) for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs M simulated workers and the server on ONE GPU; "
@@ -128,6 +131,15 @@ def main():
         state["eta_prev"] = w.eta
         state["t"] += 1
 
+    if args.calib:
+        # known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE: reads 2^28 floats, writes 2^28 floats
+        ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        cb = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        for _ in range(3):
+            torch.add(ca, 1.0, out=cb)
+        torch.cuda.synchronize()
+        del ca, cb
+
     first_payload = None
     for k in range(args.warmup):
         step()
@@ -170,7 +182,8 @@ def main():
                        d_per_step_Gelem_s=round(d / (ms_per_step * 1e-3) / 1e9, 3)),
         "roofline": {
             "bound": "hbm",
-            "kernel": "ef_worker_step (k_worker_pass1 + k_residual_pass2), all M workers in one call",
+            "kernel": "ef::k_worker_uniform (the persistent worker kernel; timed as the whole ef_worker_step call, "
+                      "whose two list kernels add well under 1%), all M workers in one launch",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
