@@ -1,0 +1,218 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (all M workers in one ef_worker_step call, default
+plan settings).
+
+Every stage of Algorithm 4 is block-separable (a block's outputs depend only on
+that block's inputs), so the oracle is run on a sample of whole blocks: their
+state is gathered from the GPU before the step, the oracle steps the
+concatenation of those blocks, and its outputs are compared with the GPU's
+outputs on the same blocks.  Bar as in tests/parity_util.py: sign bits and
+momentum bit-exact, scales within 1e-6 relative, residuals and parameters
+bit-exact where the block's scale is bit-equal and within 1e-6 of the scale
+otherwise.  On top of the samples, properties that hold at any size are checked
+over the whole vectors on the GPU (payload padding bits, Proposition 1 energy
+identity, the reconstruction p = C(p) + e').
+"""
+import numpy as np
+import pytest
+import torch
+
+import ef_workloads as wl
+import oracle
+import paper_1905_10936_amd as ef
+from tests.parity_util import F, check_scales, check_vector
+
+pytestmark = pytest.mark.gpu
+
+
+def _cat(t, offs, blocks):
+    """Concatenate the element ranges of `blocks` from the last dim of t -> numpy."""
+    parts = [t[..., int(offs[b]):int(offs[b + 1])] for b in blocks]
+    return torch.cat(parts, dim=-1).cpu().numpy()
+
+
+def _bits(words, offs, blocks):
+    """Sign bits (0/1 uint8) of the element ranges of `blocks`; words: int64 tensor [..., W]."""
+    out = []
+    for b in blocks:
+        a, e = int(offs[b]), int(offs[b + 1])
+        w0, w1 = a // 64, (e + 63) // 64
+        w = words[..., w0:w1].cpu().numpy().view(np.uint64)
+        bits = np.unpackbits(w.view(np.uint8), axis=-1, bitorder="little")
+        out.append(bits[..., a - 64 * w0:e - 64 * w0])
+    return np.concatenate(out, axis=-1)
+
+
+def _pack(bits):
+    """uint8 bits [..., n] -> uint64 words [..., ceil(n/64)], LSB first."""
+    n = bits.shape[-1]
+    pad = (-n) % 64
+    if pad:
+        bits = np.concatenate([bits, np.zeros(bits.shape[:-1] + (pad,), np.uint8)], axis=-1)
+    return np.ascontiguousarray(np.packbits(bits, axis=-1, bitorder="little")).view(np.uint64)
+
+
+def _sample_blocks(w, rng, n_random, max_elems):
+    sizes = np.diff(w.offsets)
+    picks = {0, w.B - 1, int(np.argmax(sizes)), int(np.argmin(sizes))}
+    # blocks around tile boundaries of the largest block, and some random ones
+    picks.update(int(b) for b in rng.choice(w.B, size=min(n_random, w.B), replace=False))
+    picks = sorted(picks)
+    # respect the element budget, keeping the largest block if it fits
+    out, tot = [], 0
+    for b in sorted(picks, key=lambda b: -sizes[b]):
+        if tot + sizes[b] <= max_elems:
+            out.append(b)
+            tot += int(sizes[b])
+    return sorted(out)
+
+
+def _run_sampled(w, steps, blocks, workers=None, check_props=True):
+    dev = torch.device("cuda")
+    d, B, M = w.d, w.B, w.M
+    W = (d + 63) // 64
+    offs = w.offsets
+    sizes = np.diff(offs)[blocks]
+    sub_offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    workers = list(range(M)) if workers is None else workers
+    plan = ef.ef_plan_create(offs, M)
+    ds = (d + 3) // 4 * 4                  # row stride: the ABI wants a multiple of 4 elements
+    g_rows = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+    m_rows = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+    e_rows = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+    g, m, e = g_rows[:, :d], m_rows[:, :d], e_rows[:, :d]
+    te = torch.zeros(d, dtype=torch.float32, device=dev)
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
+    wc = torch.zeros((M, B), dtype=torch.float32, device=dev)
+    ss = torch.zeros(W, dtype=torch.int64, device=dev)
+    sc = torch.zeros(B, dtype=torch.float32, device=dev)
+    bsel = torch.as_tensor(blocks, device=dev)
+    eta_prev = 0.0
+    loose = 0
+    for t in range(steps):
+        print("[%s] step %d: generating gradients" % (w.name, t), flush=True)
+        for i in range(M):
+            w.grad(t, i, device=dev, out=g[i])
+        # ---- state of the sampled blocks before the step
+        g_s, m_s, e_s = _cat(g, offs, blocks), _cat(m, offs, blocks), _cat(e, offs, blocks)
+        te_s, x_s = _cat(te, offs, blocks), _cat(x, offs, blocks)
+        if check_props:
+            p_full = w.mu * (w.mu * m[0].double() + g[0].double()) + g[0].double()
+            mag = w.mu * w.mu * m[0].double().abs() + (1 + w.mu) * g[0].double().abs()   # size of the fp32 terms
+            if eta_prev:
+                p_full += e[0].double()           # constant stepsize: ratio 1
+                mag += e[0].double().abs()
+        ws.fill_(0x5555555555555555)
+        wc.fill_(-7.0)
+        print("[%s] step %d: worker step on the GPU" % (w.name, t), flush=True)
+        ef.ef_worker_step(plan, g_rows, m_rows, e_rows, w.mu, eta_prev, w.eta, ws, wc)
+        torch.cuda.synchronize()
+        print("[%s] step %d: oracle on %d sampled elements x %d workers" % (w.name, t, int(sub_offs[-1]), len(workers)),
+              flush=True)
+        wbits = _bits(ws, offs, blocks)
+        wc_s = wc[:, bsel].cpu().numpy()
+        m_out, e_out = _cat(m, offs, blocks), _cat(e, offs, blocks)
+        for i in workers:
+            mi, ei = np.ascontiguousarray(m_s[i]), np.ascontiguousarray(e_s[i])
+            s_ref, c_ref = oracle.worker_step(np.ascontiguousarray(g_s[i]), mi, ei, sub_offs, F(w.mu), F(eta_prev),
+                                              F(w.eta))
+            tag = "%s step %d worker %d" % (w.name, t, i)
+            ref_bits = np.unpackbits(s_ref.view(np.uint8), bitorder="little")[:wbits.shape[-1]]
+            assert np.array_equal(wbits[i], ref_bits), "%s: %d sign bits differ" % (tag, (wbits[i] != ref_bits).sum())
+            assert np.array_equal(m_out[i].view(np.uint32), mi.view(np.uint32)), tag + ": momentum differs"
+            same = check_scales(wc_s[i], c_ref, tag)
+            loose += int((~same).sum())
+            check_vector(e_out[i], ei, c_ref, same, sub_offs, tag + " residual")
+        if check_props:
+            print("[%s] step %d: whole-vector properties" % (w.name, t), flush=True)
+            # properties over the whole vector of worker 0 (fp64 on the GPU)
+            bid = torch.repeat_interleave(torch.arange(B, device=dev), torch.as_tensor(np.diff(offs), device=dev))
+            dec = wc[0][bid].double()
+            bits0 = ((ws[0][torch.arange(d, device=dev) // 64] >> (torch.arange(d, device=dev) % 64)) & 1).bool()
+            dec = torch.where(bits0, dec, -dec)
+            rec = dec + e[0].double()
+            scale_b = wc[0][bid].double()
+            assert bool(((rec - p_full).abs() <= 2e-6 * (mag + scale_b) + 1e-30).all()), \
+                "%s step %d: p = C(p) + e' violated" % (w.name, t)
+            assert bool((bits0 == (p_full >= 0))[p_full.abs() > 1e-5 * (mag + scale_b)].all())
+            # per-block sums as differences of fp64 running sums (index_add_ would serialise
+            # millions of atomic adds on the one address of a large block)
+            ends = torch.as_tensor(offs[1:] - 1, device=dev)
+
+            def block_sums(v):
+                cs = torch.cumsum(v, 0)[ends]
+                return torch.diff(cs, prepend=torch.zeros(1, dtype=torch.float64, device=dev))
+
+            l1, l2, en = block_sums(p_full.abs()), block_sums(p_full * p_full), block_sums(e[0].double() ** 2)
+            db = torch.as_tensor(np.diff(offs), device=dev).double()
+            tot = float(p_full.abs().sum())          # the running sums carry ~1e-16 * total of rounding
+            assert bool(((en - (l2 - l1 * l1 / db)).abs() <= 1e-5 * l2 + 1e-12 * tot * tot + 1e-30).all()), \
+                "Prop. 1 identity violated"
+            assert bool(((wc[0].double() - l1 / db).abs() <= 2e-6 * (l1 / db) + 1e-12 * tot + 1e-30).all())
+            del bid, dec, bits0, rec, scale_b, l1, l2, en, db, p_full, ends, mag
+            if d % 64:
+                assert int(ws[0, -1].item()) >> (d % 64) == 0, "padding bits set"
+        # ---- server on the GPU's worker payloads
+        ss.fill_(0x5555555555555555)
+        sc.fill_(-7.0)
+        print("[%s] step %d: server step" % (w.name, t), flush=True)
+        ef.ef_server_step(plan, M, ws, wc, te, eta_prev, w.eta, ss, sc)
+        torch.cuda.synchronize()
+        te_ref = np.ascontiguousarray(te_s)
+        ss_ref, sc_ref = oracle.server_step(_pack(wbits), np.ascontiguousarray(wc_s), te_ref, sub_offs, F(eta_prev),
+                                            F(w.eta))
+        sbits = _bits(ss, offs, blocks)
+        ref_bits = np.unpackbits(ss_ref.view(np.uint8), bitorder="little")[:sbits.shape[-1]]
+        tag = "%s step %d server" % (w.name, t)
+        assert np.array_equal(sbits, ref_bits), "%s: %d sign bits differ" % (tag, (sbits != ref_bits).sum())
+        sc_s = sc[bsel].cpu().numpy()
+        same = check_scales(sc_s, sc_ref, tag)
+        loose += int((~same).sum())
+        check_vector(_cat(te, offs, blocks), te_ref, sc_ref, same, sub_offs, tag + " residual")
+        # ---- apply
+        ef.ef_apply(plan, x, ss, sc, w.eta)
+        torch.cuda.synchronize()
+        x_ref = np.ascontiguousarray(x_s)
+        oracle.apply(x_ref, _pack(sbits), np.ascontiguousarray(sc_s), sub_offs, F(w.eta))
+        assert np.array_equal(_cat(x, offs, blocks).view(np.uint32), x_ref.view(np.uint32)), tag + ": apply differs"
+        eta_prev = w.eta
+    return loose
+
+
+def test_resnet50_like_full():
+    """Configuration 2: all 161 blocks of every worker through the oracle."""
+    w = wl.get("resnet50_like")
+    _run_sampled(w, w.steps, list(range(w.B)))
+
+
+def test_flat_2p28_sampled():
+    """Configuration 3 (the benchmark workload): first, middle and last block of
+    each of the 8 workers, momentum and residuals carried over 3 steps."""
+    w = wl.get("flat_2p28")
+    _run_sampled(w, 3, [0, 1, 127, 255], check_props=False)
+
+
+def test_skewed_blocks_sampled():
+    """Configuration 4: blocks of 1..64 elements next to 8 Mi-element blocks
+    (larger than the one-pass limit), 5 % exact zeros."""
+    w = wl.get("skewed_blocks")
+    sizes = np.diff(w.offsets)
+    big = [int(b) for b in np.nonzero(sizes > 64)[0]]
+    rng = np.random.default_rng(4)
+    # one big block with its small neighbours, plus runs of small blocks at random places
+    blocks = set()
+    blocks.update(range(max(0, big[1] - 300), min(w.B, big[1] + 300)))
+    for s in rng.choice(w.B - 5000, size=6, replace=False):
+        blocks.update(range(int(s), int(s) + 4000))
+    blocks.update([0, w.B - 1])
+    _run_sampled(w, w.steps, sorted(blocks))
+
+
+def test_transformer_like_sampled():
+    """Configuration 5: the 51 M-element embedding block (several times the
+    one-pass limit), one layer's 12 tensors and the last block, for 2 of the 16
+    workers on the oracle side; the GPU runs all 16."""
+    w = wl.get("transformer_like")
+    blocks = [0] + list(range(1, 13)) + [w.B - 1]
+    _run_sampled(w, w.steps, blocks, workers=[0, 15], check_props=False)
