@@ -98,12 +98,13 @@ def main():
 
     # gradient sets resident in HBM, cycled over the steps
     n_sets = args.grad_sets or max(1, min(args.steps + args.warmup, int(64e9 // (4.0 * d * M)), 4))
-    grads = torch.empty((n_sets, M, d), dtype=torch.float32, device=dev)
+    ds = (d + 3) // 4 * 4           # row stride in elements: the ABI wants a multiple of 4
+    grads = torch.zeros((n_sets, M, ds), dtype=torch.float32, device=dev)
     for s in range(n_sets):
         for i in range(M):
-            w.grad(s, i, device=dev, out=grads[s, i])
-    mom = torch.zeros((M, d), dtype=torch.float32, device=dev)
-    err = torch.zeros((M, d), dtype=torch.float32, device=dev)
+            w.grad(s, i, device=dev, out=grads[s, i, :d])
+    mom = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+    err = torch.zeros((M, ds), dtype=torch.float32, device=dev)
     te = torch.zeros(d, dtype=torch.float32, device=dev)
     x = torch.zeros(d, dtype=torch.float32, device=dev)
     ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
@@ -157,6 +158,13 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    # untimed diagnostic: one more worker and server call, asking each how many tiles left the one-pass route
+    g = grads[state["t"] % n_sets]
+    ef.ef_worker_step(plan, g, mom, err, w.mu, w.eta, w.eta, ws, wc)
+    fb_worker = plan.last_fallbacks()
+    ef.ef_server_step(plan, M, ws, wc, te, w.eta, w.eta, ss, sc)
+    fb_server = plan.last_fallbacks()
+
     t_worker = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     t_server = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     t_apply = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
@@ -195,6 +203,8 @@ def main():
         "per_call_ms": {"ef_worker_step": round(t_worker, 4), "ef_server_step": round(t_server, 4),
                         "ef_apply": round(t_apply, 4)},
         "step_hbm_frac_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "run_time_fallbacks": {"worker_parked_tiles": fb_worker[0], "worker_late_blocks": fb_worker[1],
+                               "server_parked_tiles": fb_server[0], "server_late_blocks": fb_server[1]},
     }
 
     if not args.no_cpu:

@@ -103,6 +103,16 @@ int ef_plan_fuse_limit(const ef_plan *plan);
  */
 int ef_plan_set_persistent(ef_plan *plan, int on);
 
+/*
+ * How often the most recent ef_worker_step / ef_server_step on this plan left
+ * the one-pass route at run time: tiles whose wait for the block scale was not
+ * taken or ran out (p parked, finished by the second pass) and blocks whose
+ * scale had to be formed by the second pass.  Results do not depend on these
+ * counts; they are a performance diagnostic.  Synchronises the device.  Either
+ * pointer may be NULL (HOST pointers).
+ */
+int ef_plan_last_fallbacks(ef_plan *plan, unsigned int *parked_tiles, unsigned int *late_blocks);
+
 int64_t ef_plan_d(const ef_plan *plan);          /* d = block_offsets[B] */
 int64_t ef_plan_blocks(const ef_plan *plan);     /* B */
 int64_t ef_plan_sign_words(const ef_plan *plan); /* W = ceil(d/64) */

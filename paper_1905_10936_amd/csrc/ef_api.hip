@@ -16,11 +16,14 @@ struct ef_plan {
     int device;
     int spin_limit;
     unsigned int calls;             // calls issued so far; its parity picks the list counters
+    unsigned int epoch;             // number of the last call, skipping 0; carried by the ready words
+    unsigned int *last_defer_cnt, *last_fin_cnt;   // list counters of the most recent call
     std::vector<uint8_t> set_tag;   // tag the last call that used a set gave its partial words
     std::vector<int64_t> offs_host;
     std::vector<int32_t> fb_host, lb_host;
     uint32_t n_static;              // segments whose p the first kernels always park
     uint32_t n_late;                // blocks whose scale the first kernels never write
+    uint32_t n_counted;             // one-pass blocks (arrival counters in use)
     // device allocations owned by the plan
     int64_t *d_offs;
     int32_t *d_tile_fb;
@@ -35,6 +38,7 @@ struct ef_plan {
     unsigned long long *d_fin_list;
     uint32_t *d_static;             // [2*ntiles] capacity
     int32_t *d_late;                // [min(B, 2*ntiles)] capacity
+    int32_t *d_counted;             // [min(B, 2*ntiles)] capacity
     int32_t *d_mixed, *d_uniform;   // tile lists
 };
 
@@ -87,6 +91,7 @@ void destroy_device(ef_plan *p)
     if (p->d_fin_list) (void)hipFree(p->d_fin_list);
     if (p->d_static) (void)hipFree(p->d_static);
     if (p->d_late) (void)hipFree(p->d_late);
+    if (p->d_counted) (void)hipFree(p->d_counted);
     if (p->d_mixed) (void)hipFree(p->d_mixed);
     if (p->d_uniform) (void)hipFree(p->d_uniform);
 }
@@ -110,12 +115,17 @@ bool has_uniform_tile(const ef_plan *p, int64_t b)
 int upload_static_list(ef_plan *p)
 {
     std::vector<uint32_t> items;
-    std::vector<int32_t> late;
+    std::vector<int32_t> late, counted;
     const int64_t *o = p->offs_host.data();
     for (int64_t b = 0; b < p->L.B; ++b) {
         const int64_t n = tiles_of_block(p, b);
-        if (n >= 2 && (n > p->L.fuse_limit || !has_uniform_tile(p, b))) late.push_back((int32_t)b);
+        if (n < 2) continue;
+        if (n > p->L.fuse_limit || !has_uniform_tile(p, b)) late.push_back((int32_t)b);
+        else counted.push_back((int32_t)b);
     }
+    p->n_counted = (uint32_t)counted.size();
+    if (!counted.empty())
+        EF_HIP(hipMemcpy(p->d_counted, counted.data(), sizeof(int32_t) * counted.size(), hipMemcpyHostToDevice));
     for (int32_t t = 0; t < p->L.ntiles; ++t) {
         const int64_t start = (int64_t)t * ef::TILE, end = start + ef::TILE;
         const int32_t fb = p->fb_host[t], lb = p->lb_host[t];
@@ -180,6 +190,7 @@ int build_device(ef_plan *p)
     EF_HIP(hipMalloc(&p->d_fin_list, sizeof(unsigned long long) * max_cross * nsets));
     EF_HIP(hipMalloc(&p->d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
     EF_HIP(hipMalloc(&p->d_late, sizeof(int32_t) * max_cross));
+    EF_HIP(hipMalloc(&p->d_counted, sizeof(int32_t) * max_cross));
     {
         std::vector<int32_t> mixed, uniform;
         for (int32_t t = 0; t < ntiles; ++t) {
@@ -233,6 +244,8 @@ int build_device(ef_plan *p)
     p->spin_limit = 1 << 14;
     p->persistent = 1;
     p->calls = 0;
+    p->epoch = 0;
+    p->last_defer_cnt = p->last_fin_cnt = nullptr;
     int rc = upload_static_list(p);
     if (rc) return rc;
     EF_HIP(hipDeviceSynchronize());
@@ -260,8 +273,13 @@ CallScratch next_call(const ef_plan *plan_c, int set_base, int nsets)
     c.X.spin_limit = plan->spin_limit;
     const unsigned cur = plan->calls & 1u, nxt = cur ^ 1u;
     plan->calls += 1;
+    plan->epoch += 1;
+    if (plan->epoch == 0) plan->epoch = 1;       // 0 marks "no scale posted"
+    c.X.epoch = plan->epoch;
     c.X.defer_cnt = plan->d_list_cnt + cur;
     c.X.fin_cnt = plan->d_list_cnt + 2 + cur;
+    plan->last_defer_cnt = c.X.defer_cnt;
+    plan->last_fin_cnt = c.X.fin_cnt;
     c.X.ticket = plan->d_list_cnt + 4 + cur;
     c.next_defer_cnt = plan->d_list_cnt + nxt;
     c.next_fin_cnt = plan->d_list_cnt + 2 + nxt;
@@ -277,8 +295,9 @@ int launch_second_pass(const ef_plan *plan, const CallScratch &c, int nsets, flo
                        plan->L, c.X, (const int32_t *)plan->d_late, (int)plan->n_late, nsets, scales);
     EF_HIP(hipGetLastError());
     hipLaunchKernelGGL(ef::k_residual_parked, dim3(plan->n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
-                       plan->L, c.X, (const uint32_t *)plan->d_static, (int)plan->n_static, nsets, c.next_defer_cnt,
-                       c.next_fin_cnt, c.next_ticket, err, err_stride, (const float *)scales);
+                       plan->L, c.X, (const uint32_t *)plan->d_static, (int)plan->n_static, nsets,
+                       (const int32_t *)plan->d_counted, (int)plan->n_counted, c.next_defer_cnt, c.next_fin_cnt,
+                       c.next_ticket, err, err_stride, (const float *)scales);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
@@ -315,6 +334,8 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_fin_list = nullptr;
     p->d_static = nullptr;
     p->d_late = nullptr;
+    p->d_counted = nullptr;
+    p->n_counted = 0;
     p->d_mixed = p->d_uniform = nullptr;
     p->n_static = 0;
     p->n_late = 0;
@@ -351,6 +372,20 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
 }
 
 int ef_plan_fuse_limit(const ef_plan *plan) { return plan ? plan->L.fuse_limit : 0; }
+
+int ef_plan_last_fallbacks(ef_plan *plan, unsigned int *parked_tiles, unsigned int *late_blocks)
+{
+    if (!plan) return EF_ERR_NULL;
+    EF_HIP(hipDeviceSynchronize());
+    unsigned int a = 0, b = 0;
+    if (plan->last_defer_cnt) {
+        EF_HIP(hipMemcpy(&a, plan->last_defer_cnt, sizeof a, hipMemcpyDeviceToHost));
+        EF_HIP(hipMemcpy(&b, plan->last_fin_cnt, sizeof b, hipMemcpyDeviceToHost));
+    }
+    if (parked_tiles) *parked_tiles = a;
+    if (late_blocks) *late_blocks = b;
+    return EF_OK;
+}
 
 int ef_plan_set_persistent(ef_plan *plan, int on)
 {

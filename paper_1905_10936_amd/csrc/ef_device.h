@@ -78,14 +78,15 @@ struct Layout {
 // Scratch of one call.  A "set" is one worker, or the server.
 struct Scratch {
     unsigned long long *part;   // [nsets][2*ntiles] tagged fp64 partial sums of open segments
-    unsigned int *cnt;          // [nsets][B] arrivals per one-pass block, 0 between calls
-    unsigned long long *ready;  // [nsets][B] (tag << 32) | scale bits, posted by the last arriver
+    unsigned int *cnt;          // [nsets][B] arrivals per one-pass block; zeroed again by the call's last kernel
+    unsigned long long *ready;  // [nsets][B] (epoch << 32) | scale bits, posted by the last arriver
     unsigned int *defer_cnt;    // entries in defer_list for this call
     unsigned long long *defer_list;  // parked segments: (set << 33) | (tile << 1) | slot
     unsigned int *fin_cnt;      // entries in fin_list for this call
     unsigned long long *fin_list;    // blocks whose scale is still to be written: (set << 32) | block
     unsigned int *ticket;       // next chunk of tiles to hand out (persistent kernels), 0 at call start
-    unsigned long long tags;    // bit i = this call's tag of set (set_base + i)
+    unsigned long long tags;    // bit i = this call's tag of set (set_base + i), carried by its partial words
+    unsigned int epoch;         // this call's number on the plan (never 0), carried by the ready words
     int set_base;               // first set this call uses (0 for workers, max_workers for the server)
     int spin_limit;             // polls before a waiting workgroup gives up and parks p
 };
@@ -451,12 +452,11 @@ __device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const S
     float s;
     const bool ok = gather_scale(b, L, X, set, S, &s);
     if (threadIdx.x == 0) {
-        __hip_atomic_store(set_cnt(X, L, set) + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (ok) {
             scales_out[b] = s;
             __hip_atomic_store(set_ready(X, L, set) + b,
-                               (set_tag(X, set) << 32) | (unsigned long long)__float_as_uint(s), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+                               ((unsigned long long)X.epoch << 32) | (unsigned long long)__float_as_uint(s),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else {
             const unsigned k = atomicAdd(X.fin_cnt, 1u);
             X.fin_list[k] = ((unsigned long long)set << 32) | (unsigned long long)b;
@@ -484,7 +484,7 @@ __device__ __forceinline__ void resolve_posted(const Posted &P, const Layout &L,
 // Thread 0's early look at the ready word of block b (b < 0: none).
 __device__ __forceinline__ unsigned long long peek_ready(int b, const Layout &L, const Scratch &X, int set)
 {
-    unsigned long long w = ~0ull;          // its tag field can never match
+    unsigned long long w = 0ull;           // epoch 0 is never used
     if (threadIdx.x == 0 && b >= 0)
         w = __hip_atomic_load(set_ready(X, L, set) + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return w;
@@ -497,13 +497,12 @@ __device__ __forceinline__ bool wait_ready(int64_t b, unsigned long long peeked,
                                            int set, TileShared &S, float *s)
 {
     if (threadIdx.x == 0) {
-        const unsigned long long tag = set_tag(X, set);
         const unsigned long long *word = set_ready(X, L, set) + b;
         unsigned long long w = peeked;
-        int found = ((w >> 32) == tag) ? 1 : 0;
+        int found = ((unsigned)(w >> 32) == X.epoch) ? 1 : 0;
         for (int it = 0; !found && it < X.spin_limit; ++it) {
             w = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            found = ((w >> 32) == tag) ? 1 : 0;
+            found = ((unsigned)(w >> 32) == X.epoch) ? 1 : 0;
             if (!found) __builtin_amdgcn_s_sleep(8);
         }
         if (X.spin_limit <= 0) found = 0;   // a zero budget means: never take the one-pass route
@@ -667,10 +666,10 @@ __device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layo
 // the wait runs out, p is parked and the segment deferred.
 __device__ __forceinline__ void finish_uniform(float4 (&p)[SUBROWS], int32_t tile, int n_valid, int b,
                                                unsigned long long peeked, float *err_tile, const Layout &L,
-                                               const Scratch &X, int set, TileShared &S)
+                                               const Scratch &X, int set, TileShared &S, bool may_wait = true)
 {
-    float s;
-    const bool ok = wait_ready(b, peeked, L, X, set, S, &s);
+    float s = 0.f;
+    const bool ok = may_wait && wait_ready(b, peeked, L, X, set, S, &s);
     if (ok) {
 #pragma unroll
         for (int k = 0; k < SUBROWS; ++k) residual4(p[k], s);
@@ -822,10 +821,17 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
         HeldTile &old = held[0];
         const unsigned long long peeked = peek_ready(old.b, L, X, old.b >= 0 ? old.set : 0);
         resolve_posted(posted, L, X, posted_set, A.scales + (int64_t)posted_set * L.B, S);
+        // The new tile announces itself now, so that the counter's answer returns under the loads.
         announce_uniform(L, tile, X, worker, posted);
         if (old.b >= 0) {
+            // The block of the oldest tile cannot complete while this workgroup sits on a tile of
+            // the same block that is not posted yet (the new one, or the rest of its ticket): then
+            // do not wait, park p and leave the tile to the second pass.  Across different blocks a
+            // wait only ever depends on workgroups waiting for strictly older blocks.
+            bool may_wait = !(old.set == worker && L.tile_fb[tile] == old.b);
+            for (int c = cur; c < cur_end; ++c) may_wait = may_wait && !(old.set == worker && L.tile_fb[L.uniform_tiles[c]] == old.b);
             float *e_old = A.err + (int64_t)old.set * A.state_stride + (int64_t)old.tile * TILE;
-            finish_uniform(old.p, old.tile, TILE, old.b, peeked, e_old, L, X, old.set, S);
+            finish_uniform(old.p, old.tile, TILE, old.b, peeked, e_old, L, X, old.set, S, may_wait);
         }
 #pragma unroll
         for (int q = 0; q + 1 < PIPE_DEPTH; ++q) held[q] = held[q + 1];
@@ -853,7 +859,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
     for (int q = 0; q < PIPE_DEPTH; ++q) {
         if (held[q].b >= 0) {
             float *e_q = A.err + (int64_t)held[q].set * A.state_stride + (int64_t)held[q].tile * TILE;
-            finish_uniform(held[q].p, held[q].tile, TILE, held[q].b, ~0ull, e_q, L, X, held[q].set, S);
+            finish_uniform(held[q].p, held[q].tile, TILE, held[q].b, 0ull, e_q, L, X, held[q].set, S);
         }
     }
 }
@@ -885,7 +891,7 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
     const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W, scales_out, e, X, worker,
                                       S, P);
     resolve_posted(P, L, X, worker, scales_out, S);
-    if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, P.b[0], ~0ull, e, L, X, worker, S);
+    if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, P.b[0], 0ull, e, L, X, worker, S);
 }
 
 // --------------------------------------------------------- server kernel ---
@@ -964,7 +970,7 @@ __global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerA
     } else {
         const int kind = compress_uniform(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
         resolve_posted(P, L, X, set, A.scales, S);
-        if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, P.b[0], ~0ull, te, L, X, set, S);
+        if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, P.b[0], 0ull, te, L, X, set, S);
     }
 }
 
@@ -1043,9 +1049,10 @@ __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X
 // per-layout list (open segments of mixed tiles, tiles of blocks larger than
 // fuse_limit: workgroups 0 .. n_items*nsets-1) and the tiles whose wait ran out
 // (list filled at run time: the last DEFER_WGS workgroups).  Also clears the
-// counters the next call will use.
+// list counters the next call will use and this call's arrival counters.
 __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X, const uint32_t *items,
-                                                             int n_items, int nsets, unsigned int *next_defer_cnt,
+                                                             int n_items, int nsets, const int32_t *counted_blocks,
+                                                             int n_counted, unsigned int *next_defer_cnt,
                                                              unsigned int *next_fin_cnt, unsigned int *next_ticket,
                                                              float *err, int64_t err_stride, const float *scales)
 {
@@ -1054,6 +1061,10 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X
         *next_fin_cnt = 0u;
         *next_ticket = 0u;
     }
+    // every arrival of this call has been counted by now: back to zero for the next call
+    for (int64_t i = (int64_t)blockIdx.x * THREADS + threadIdx.x; i < (int64_t)n_counted * nsets;
+         i += (int64_t)gridDim.x * THREADS)
+        set_cnt(X, L, X.set_base + (int)(i / n_counted))[counted_blocks[i % n_counted]] = 0u;
     const int n_static = n_items * nsets;
     if ((int)blockIdx.x < n_static) {
         const uint32_t it = items[blockIdx.x % n_items];
