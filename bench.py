@@ -190,8 +190,9 @@ def main():
                        d_per_step_Gelem_s=round(d / (ms_per_step * 1e-3) / 1e9, 3)),
         "roofline": {
             "bound": "hbm",
-            "kernel": "ef::k_worker_uniform (the persistent worker kernel; timed as the whole ef_worker_step call, "
-                      "whose two list kernels add well under 1%), all M workers in one launch",
+            "kernel": ("ef::k_worker_uniform (persistent)" if plan.persistent else "ef::k_worker_uniform_direct") +
+                      ", all M workers in one launch; timed as the whole ef_worker_step call (its mixed-tile and "
+                      "list kernels included)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -203,6 +204,7 @@ def main():
         "per_call_ms": {"ef_worker_step": round(t_worker, 4), "ef_server_step": round(t_server, 4),
                         "ef_apply": round(t_apply, 4)},
         "step_hbm_frac_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "worker_fuse_limit_tiles": plan.fuse_limit,
         "run_time_fallbacks": {"worker_parked_tiles": fb_worker[0], "worker_late_blocks": fb_worker[1],
                                "server_parked_tiles": fb_server[0], "server_late_blocks": fb_server[1]},
     }

@@ -88,20 +88,26 @@ int ef_plan_destroy(ef_plan *plan);
  * that larger blocks always take.  Results are identical on either route.
  * Negative values leave a setting unchanged; fuse_limit = 0 sends every block
  * through two passes, spin_limit = 0 makes every wait give up at once (used by
- * tests to exercise the fallback).  Synchronises the device.  The default
- * fuse_limit is half the number of workgroups resident on the device at once.
+ * tests to exercise the fallback).  Synchronises the device.  By default each
+ * kernel gets its own limit: half the tiles its workgroups can hold at once
+ * (resident workgroups, times three for the persistent worker kernel), at most
+ * 1536 tiles.  A limit set here applies to worker and server alike.
  */
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
-int ef_plan_fuse_limit(const ef_plan *plan);
+int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit in force */
 
 /*
  * Which kernel ef_worker_step runs over the tiles that lie inside one block:
- * on = 1 (default) a persistent kernel whose workgroups take tiles from a ticket
- * counter and keep several tiles in registers while their scales form; on = 0
- * one workgroup per tile that waits in place for its block's scale.  Same
- * results either way.  Synchronises the device.
+ * on = 1 a persistent kernel whose workgroups take tiles from a ticket counter
+ * and keep several tiles in registers while their scales form; on = 0 one
+ * workgroup per tile that waits in place for its block's scale; on < 0 the
+ * choice plan creation made for this layout (persistent when every workgroup
+ * gets at least 64 tiles and the largest one-pass block is small next to the
+ * distance between two tickets of one workgroup).  Same results either way.
+ * Synchronises the device.
  */
 int ef_plan_set_persistent(ef_plan *plan, int on);
+int ef_plan_is_persistent(const ef_plan *plan);
 
 /*
  * How often the most recent ef_worker_step / ef_server_step on this plan left

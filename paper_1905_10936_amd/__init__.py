@@ -23,7 +23,7 @@ EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1
 EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
-    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
     "ef_sign_words", "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
 )
 
@@ -57,6 +57,8 @@ def lib():
     L.ef_plan_tune.argtypes = [vp, c_int, c_int]
     L.ef_plan_set_persistent.restype = c_int
     L.ef_plan_set_persistent.argtypes = [vp, c_int]
+    L.ef_plan_is_persistent.restype = c_int
+    L.ef_plan_is_persistent.argtypes = [vp]
     L.ef_plan_last_fallbacks.restype = c_int
     L.ef_plan_last_fallbacks.argtypes = [vp, ctypes.POINTER(ctypes.c_uint), ctypes.POINTER(ctypes.c_uint)]
     L.ef_plan_fuse_limit.restype = c_int
@@ -134,7 +136,12 @@ class Plan:
         _check(lib().ef_plan_tune(self._h, int(fuse_limit), int(spin_limit)))
 
     def set_persistent(self, on):
-        _check(lib().ef_plan_set_persistent(self._h, int(bool(on))))
+        """True/False, or None for the choice made at plan creation."""
+        _check(lib().ef_plan_set_persistent(self._h, -1 if on is None else int(bool(on))))
+
+    @property
+    def persistent(self):
+        return bool(lib().ef_plan_is_persistent(self._h))
 
     def last_fallbacks(self):
         """(parked_tiles, late_blocks) of the most recent worker/server call."""
@@ -168,6 +175,10 @@ def ef_plan_tune(plan, fuse_limit=-1, spin_limit=-1):
 
 def ef_plan_set_persistent(plan, on):
     plan.set_persistent(on)
+
+
+def ef_plan_is_persistent(plan):
+    return plan.persistent
 
 
 def ef_plan_last_fallbacks(plan):

@@ -21,9 +21,19 @@ struct ef_plan {
     std::vector<uint8_t> set_tag;   // tag the last call that used a set gave its partial words
     std::vector<int64_t> offs_host;
     std::vector<int32_t> fb_host, lb_host;
-    uint32_t n_static;              // segments whose p the first kernels always park
-    uint32_t n_late;                // blocks whose scale the first kernels never write
-    uint32_t n_counted;             // one-pass blocks (arrival counters in use)
+    // What depends on the one-pass limit, which differs between the worker kernels and the
+    // server kernel (each is bounded by what its own grid keeps resident): role 0 = worker, 1 = server.
+    struct Role {
+        int32_t fuse_limit;
+        uint32_t n_static;          // segments whose p the first kernels always park
+        uint32_t n_late;            // blocks whose scale the first kernels never write
+        uint32_t n_counted;         // one-pass blocks (arrival counters in use)
+        uint32_t *d_static;         // [2*ntiles] capacity
+        int32_t *d_late;            // [min(B, 2*ntiles)] capacity
+        int32_t *d_counted;         // [min(B, 2*ntiles)] capacity
+    } role[2];
+    int32_t lim_persistent, lim_direct, lim_server;   // automatic limits
+    int32_t user_fuse_limit;        // >= 0: set through ef_plan_tune, overrides the automatic limits
     // device allocations owned by the plan
     int64_t *d_offs;
     int32_t *d_tile_fb;
@@ -34,11 +44,9 @@ struct ef_plan {
     unsigned int *d_list_cnt;       // [6]: defer_cnt[2], fin_cnt[2], ticket[2], alternating between calls
     int worker_grid;                // workgroups of the persistent worker kernel
     int persistent;                 // 1: pipelined persistent worker kernel, 0: one workgroup per tile
+    int persistent_auto;            // what plan creation chose for this layout
     unsigned long long *d_defer_list;
     unsigned long long *d_fin_list;
-    uint32_t *d_static;             // [2*ntiles] capacity
-    int32_t *d_late;                // [min(B, 2*ntiles)] capacity
-    int32_t *d_counted;             // [min(B, 2*ntiles)] capacity
     int32_t *d_mixed, *d_uniform;   // tile lists
 };
 
@@ -89,9 +97,11 @@ void destroy_device(ef_plan *p)
     if (p->d_list_cnt) (void)hipFree(p->d_list_cnt);
     if (p->d_defer_list) (void)hipFree(p->d_defer_list);
     if (p->d_fin_list) (void)hipFree(p->d_fin_list);
-    if (p->d_static) (void)hipFree(p->d_static);
-    if (p->d_late) (void)hipFree(p->d_late);
-    if (p->d_counted) (void)hipFree(p->d_counted);
+    for (auto &r : p->role) {
+        if (r.d_static) (void)hipFree(r.d_static);
+        if (r.d_late) (void)hipFree(r.d_late);
+        if (r.d_counted) (void)hipFree(r.d_counted);
+    }
     if (p->d_mixed) (void)hipFree(p->d_mixed);
     if (p->d_uniform) (void)hipFree(p->d_uniform);
 }
@@ -112,7 +122,7 @@ bool has_uniform_tile(const ef_plan *p, int64_t b)
 // them: the scales of crossing blocks that have no uniform tile or span more
 // than fuse_limit tiles, and the residual of every open segment of a mixed tile
 // and of every tile of a block larger than fuse_limit.
-int upload_static_list(ef_plan *p)
+int upload_static_list(ef_plan *p, ef_plan::Role &r)
 {
     std::vector<uint32_t> items;
     std::vector<int32_t> late, counted;
@@ -120,12 +130,9 @@ int upload_static_list(ef_plan *p)
     for (int64_t b = 0; b < p->L.B; ++b) {
         const int64_t n = tiles_of_block(p, b);
         if (n < 2) continue;
-        if (n > p->L.fuse_limit || !has_uniform_tile(p, b)) late.push_back((int32_t)b);
+        if (n > r.fuse_limit || !has_uniform_tile(p, b)) late.push_back((int32_t)b);
         else counted.push_back((int32_t)b);
     }
-    p->n_counted = (uint32_t)counted.size();
-    if (!counted.empty())
-        EF_HIP(hipMemcpy(p->d_counted, counted.data(), sizeof(int32_t) * counted.size(), hipMemcpyHostToDevice));
     for (int32_t t = 0; t < p->L.ntiles; ++t) {
         const int64_t start = (int64_t)t * ef::TILE, end = start + ef::TILE;
         const int32_t fb = p->fb_host[t], lb = p->lb_host[t];
@@ -133,17 +140,38 @@ int upload_static_list(ef_plan *p)
         if (fb == lb) {
             // a full tile parks p only for blocks beyond fuse_limit, the ragged last tile always
             const bool open = (o[fb] < start) || (o[fb + 1] > end);
-            if (open && (!full || tiles_of_block(p, fb) > p->L.fuse_limit)) items.push_back(((uint32_t)t << 1) | 0u);
+            if (open && (!full || tiles_of_block(p, fb) > r.fuse_limit)) items.push_back(((uint32_t)t << 1) | 0u);
         } else {
             if (o[fb] < start) items.push_back(((uint32_t)t << 1) | 0u);
             if (o[lb + 1] > end) items.push_back(((uint32_t)t << 1) | 1u);
         }
     }
-    p->n_late = (uint32_t)late.size();
-    p->n_static = (uint32_t)items.size();
-    if (!late.empty()) EF_HIP(hipMemcpy(p->d_late, late.data(), sizeof(int32_t) * late.size(), hipMemcpyHostToDevice));
+    r.n_counted = (uint32_t)counted.size();
+    r.n_late = (uint32_t)late.size();
+    r.n_static = (uint32_t)items.size();
+    if (!counted.empty())
+        EF_HIP(hipMemcpy(r.d_counted, counted.data(), sizeof(int32_t) * counted.size(), hipMemcpyHostToDevice));
+    if (!late.empty()) EF_HIP(hipMemcpy(r.d_late, late.data(), sizeof(int32_t) * late.size(), hipMemcpyHostToDevice));
     if (!items.empty())
-        EF_HIP(hipMemcpy(p->d_static, items.data(), sizeof(uint32_t) * items.size(), hipMemcpyHostToDevice));
+        EF_HIP(hipMemcpy(r.d_static, items.data(), sizeof(uint32_t) * items.size(), hipMemcpyHostToDevice));
+    return EF_OK;
+}
+
+// Pick each role's one-pass limit and rebuild the lists that depend on it.
+int refresh_limits(ef_plan *p)
+{
+    auto clamp = [](int64_t v) { return (int32_t)(v < 0 ? 0 : (v > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : v)); };
+    if (p->user_fuse_limit >= 0) {
+        p->role[0].fuse_limit = p->role[1].fuse_limit = clamp(p->user_fuse_limit);
+    } else {
+        p->role[0].fuse_limit = clamp(p->persistent ? p->lim_persistent : p->lim_direct);
+        p->role[1].fuse_limit = clamp(p->lim_server);
+    }
+    p->L.fuse_limit = p->role[0].fuse_limit;
+    for (auto &r : p->role) {
+        int rc = upload_static_list(p, r);
+        if (rc) return rc;
+    }
     return EF_OK;
 }
 
@@ -188,9 +216,11 @@ int build_device(ef_plan *p)
     EF_HIP(hipMalloc(&p->d_list_cnt, sizeof(unsigned int) * 6));
     EF_HIP(hipMalloc(&p->d_defer_list, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
     EF_HIP(hipMalloc(&p->d_fin_list, sizeof(unsigned long long) * max_cross * nsets));
-    EF_HIP(hipMalloc(&p->d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
-    EF_HIP(hipMalloc(&p->d_late, sizeof(int32_t) * max_cross));
-    EF_HIP(hipMalloc(&p->d_counted, sizeof(int32_t) * max_cross));
+    for (auto &r : p->role) {
+        EF_HIP(hipMalloc(&r.d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
+        EF_HIP(hipMalloc(&r.d_late, sizeof(int32_t) * max_cross));
+        EF_HIP(hipMalloc(&r.d_counted, sizeof(int32_t) * max_cross));
+    }
     {
         std::vector<int32_t> mixed, uniform;
         for (int32_t t = 0; t < ntiles; ++t) {
@@ -228,25 +258,34 @@ int build_device(ef_plan *p)
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server, ef::THREADS, 0));
         if (occ_w < 1) occ_w = 1;
         p->worker_grid = prop.multiProcessorCount * occ_w;
-        // one-pass blocks must fit, with a factor 2 to spare, both into the tiles the
-        // persistent worker grid holds at once and into the server kernel's resident tiles
+        // one-pass blocks must fit, with a factor 2 to spare, into the tiles a kernel's
+        // workgroups hold at once: grid x PIPE_DEPTH for the persistent worker kernel, the
+        // resident workgroups for the kernels that run one workgroup per tile
         int occ_d = 0;
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, ef::k_worker_uniform_direct, ef::THREADS, 0));
-        int64_t lim_w = (int64_t)p->worker_grid * ef::PIPE_DEPTH / 2;
-        const int64_t lim_d = (int64_t)prop.multiProcessorCount * occ_d / 2;
-        if (lim_d < lim_w) lim_w = lim_d;
-        const int64_t lim_s = (int64_t)prop.multiProcessorCount * occ_s / 2;
-        int64_t lim = lim_w < lim_s ? lim_w : lim_s;
-        if (lim < 1) lim = 1;
-        if (lim > ef::FUSE_LIMIT_MAX) lim = ef::FUSE_LIMIT_MAX;
-        p->L.fuse_limit = (int32_t)lim;
+        p->lim_persistent = (int32_t)((int64_t)p->worker_grid * ef::PIPE_DEPTH / 2);
+        p->lim_direct = (int32_t)((int64_t)prop.multiProcessorCount * occ_d / 2);
+        p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
+    }
+    p->user_fuse_limit = -1;
+    // The persistent kernel pays off when every workgroup gets many tiles and a block's tiles
+    // are few next to the distance between two tickets of one workgroup (else it keeps running
+    // into tiles of a block it still holds and parks them); otherwise one workgroup per tile.
+    {
+        int64_t largest = 0;
+        for (int64_t b = 0; b < B; ++b) {
+            const int64_t n = tiles_of_block(p, b);
+            if (n >= 2 && n <= p->lim_persistent && n > largest) largest = n;
+        }
+        const int64_t tiles_per_wg = (int64_t)p->L.n_uniform * p->max_workers / (p->worker_grid > 0 ? p->worker_grid : 1);
+        p->persistent_auto = (tiles_per_wg >= 64 && largest * 4 <= (int64_t)p->worker_grid * ef::TICKET_TILES) ? 1 : 0;
     }
     p->spin_limit = 1 << 14;
-    p->persistent = 1;
+    p->persistent = p->persistent_auto;
     p->calls = 0;
     p->epoch = 0;
     p->last_defer_cnt = p->last_fin_cnt = nullptr;
-    int rc = upload_static_list(p);
+    int rc = refresh_limits(p);
     if (rc) return rc;
     EF_HIP(hipDeviceSynchronize());
     return EF_OK;
@@ -288,16 +327,25 @@ CallScratch next_call(const ef_plan *plan_c, int set_base, int nsets)
 }
 
 // The two short kernels after the main one: missing scales, then parked residuals.
-int launch_second_pass(const ef_plan *plan, const CallScratch &c, int nsets, float *err, int64_t err_stride,
-                       float *scales, hipStream_t s)
+ef::Layout role_layout(const ef_plan *plan, int role)
 {
-    hipLaunchKernelGGL(ef::k_finalize_scales, dim3(plan->n_late * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
-                       plan->L, c.X, (const int32_t *)plan->d_late, (int)plan->n_late, nsets, scales);
+    ef::Layout L = plan->L;
+    L.fuse_limit = plan->role[role].fuse_limit;
+    return L;
+}
+
+int launch_second_pass(const ef_plan *plan, int role, const CallScratch &c, int nsets, float *err,
+                       int64_t err_stride, float *scales, hipStream_t s)
+{
+    const ef_plan::Role &r = plan->role[role];
+    const ef::Layout L = role_layout(plan, role);
+    hipLaunchKernelGGL(ef::k_finalize_scales, dim3(r.n_late * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s, L, c.X,
+                       (const int32_t *)r.d_late, (int)r.n_late, nsets, scales);
     EF_HIP(hipGetLastError());
-    hipLaunchKernelGGL(ef::k_residual_parked, dim3(plan->n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s,
-                       plan->L, c.X, (const uint32_t *)plan->d_static, (int)plan->n_static, nsets,
-                       (const int32_t *)plan->d_counted, (int)plan->n_counted, c.next_defer_cnt, c.next_fin_cnt,
-                       c.next_ticket, err, err_stride, (const float *)scales);
+    hipLaunchKernelGGL(ef::k_residual_parked, dim3(r.n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s, L,
+                       c.X, (const uint32_t *)r.d_static, (int)r.n_static, nsets, (const int32_t *)r.d_counted,
+                       (int)r.n_counted, c.next_defer_cnt, c.next_fin_cnt, c.next_ticket, err, err_stride,
+                       (const float *)scales);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
@@ -332,13 +380,14 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_list_cnt = nullptr;
     p->d_defer_list = nullptr;
     p->d_fin_list = nullptr;
-    p->d_static = nullptr;
-    p->d_late = nullptr;
-    p->d_counted = nullptr;
-    p->n_counted = 0;
+    for (auto &r : p->role) {
+        r.d_static = nullptr;
+        r.d_late = r.d_counted = nullptr;
+        r.n_static = r.n_late = r.n_counted = 0;
+        r.fuse_limit = 0;
+    }
     p->d_mixed = p->d_uniform = nullptr;
-    p->n_static = 0;
-    p->n_late = 0;
+
     rc = build_device(p);
     if (rc) {
         destroy_device(p);
@@ -364,14 +413,14 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
     EF_HIP(hipDeviceSynchronize());
     if (spin_limit >= 0) plan->spin_limit = spin_limit;
     if (fuse_limit >= 0) {
-        plan->L.fuse_limit = fuse_limit > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : fuse_limit;
-        int rc = upload_static_list(plan);
-        if (rc) return rc;
+        plan->user_fuse_limit = fuse_limit;
+        return refresh_limits(plan);
     }
     return EF_OK;
 }
 
-int ef_plan_fuse_limit(const ef_plan *plan) { return plan ? plan->L.fuse_limit : 0; }
+int ef_plan_fuse_limit(const ef_plan *plan) { return plan ? plan->role[0].fuse_limit : 0; }
+int ef_plan_is_persistent(const ef_plan *plan) { return plan ? plan->persistent : 0; }
 
 int ef_plan_last_fallbacks(ef_plan *plan, unsigned int *parked_tiles, unsigned int *late_blocks)
 {
@@ -391,8 +440,8 @@ int ef_plan_set_persistent(ef_plan *plan, int on)
 {
     if (!plan) return EF_ERR_NULL;
     EF_HIP(hipDeviceSynchronize());
-    plan->persistent = on ? 1 : 0;
-    return EF_OK;
+    plan->persistent = on < 0 ? plan->persistent_auto : (on ? 1 : 0);
+    return refresh_limits(plan);
 }
 
 int64_t ef_plan_d(const ef_plan *plan) { return plan ? plan->L.d : 0; }
@@ -425,23 +474,23 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
     A.scales = scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const CallScratch c = next_call(plan, 0, n_workers);
+    const ef::Layout L = role_layout(plan, 0);
     if (plan->L.n_mixed) {
         hipLaunchKernelGGL(ef::k_worker_mixed, dim3((unsigned)plan->L.n_mixed, (unsigned)n_workers),
-                           dim3(ef::THREADS), 0, s, plan->L, c.X, A);
+                           dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
     if (plan->L.n_uniform && plan->persistent) {
         int64_t wgs = (int64_t)plan->L.n_uniform * n_workers;
         if (wgs > plan->worker_grid) wgs = plan->worker_grid;
-        hipLaunchKernelGGL(ef::k_worker_uniform, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, plan->L, c.X, A,
-                           n_workers);
+        hipLaunchKernelGGL(ef::k_worker_uniform, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A, n_workers);
         EF_HIP(hipGetLastError());
     } else if (plan->L.n_uniform) {
         hipLaunchKernelGGL(ef::k_worker_uniform_direct, dim3((unsigned)plan->L.n_uniform, (unsigned)n_workers),
-                           dim3(ef::THREADS), 0, s, plan->L, c.X, A);
+                           dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
-    return launch_second_pass(plan, c, n_workers, err, state_stride, scales, s);
+    return launch_second_pass(plan, 0, c, n_workers, err, state_stride, scales, s);
 }
 
 int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, const float *scales,
@@ -467,9 +516,9 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)plan->L.ntiles, 1u);
     const CallScratch c = next_call(plan, plan->max_workers, 1);
-    hipLaunchKernelGGL(ef::k_server, grid, dim3(ef::THREADS), 0, s, plan->L, c.X, A, plan->max_workers);
+    hipLaunchKernelGGL(ef::k_server, grid, dim3(ef::THREADS), 0, s, role_layout(plan, 1), c.X, A, plan->max_workers);
     EF_HIP(hipGetLastError());
-    return launch_second_pass(plan, c, 1, server_err, (int64_t)0, out_scales, s);
+    return launch_second_pass(plan, 1, c, 1, server_err, (int64_t)0, out_scales, s);
 }
 
 int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, const float *scales, float eta,

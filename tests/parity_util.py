@@ -65,8 +65,8 @@ class GpuState:
         self.W = (self.d + 63) // 64
         self.plan = ef.ef_plan_create(self.offs, max(M, 1))
         # which way e <- p - Delta is finished for blocks that span several tiles
-        if route in ("direct", "direct_deferred", "direct_mixed"):
-            self.plan.set_persistent(False)      # one workgroup per tile, waiting in place
+        # the two kernels for single-block tiles: persistent and pipelined, or one workgroup per tile
+        self.plan.set_persistent(route not in ("direct", "direct_deferred", "direct_mixed"))
         if route == "two_pass":          # every such block through the second kernel
             self.plan.tune(fuse_limit=0)
         elif route in ("deferred", "direct_deferred"):   # every wait gives up at once -> deferral list
