@@ -255,7 +255,7 @@ int build_device(ef_plan *p)
         EF_HIP(hipGetDeviceProperties(&prop, p->device));
         int occ_w = 0, occ_s = 0;
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_w, ef::k_worker_uniform, ef::THREADS, 0));
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server, ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server_uniform, ef::THREADS, 0));
         if (occ_w < 1) occ_w = 1;
         p->worker_grid = prop.multiProcessorCount * occ_w;
         // one-pass blocks must fit, with a factor 2 to spare, into the tiles a kernel's
@@ -511,13 +511,23 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
     A.err = server_err;
     A.r = eta_prev / eta;
     A.Mf = (float)M;
+    A.Minv = (M & (M - 1)) == 0 ? 1.0f / (float)M : 0.0f;
     A.signs = out_signs;
     A.scales = out_scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    dim3 grid((unsigned)plan->L.ntiles, 1u);
     const CallScratch c = next_call(plan, plan->max_workers, 1);
-    hipLaunchKernelGGL(ef::k_server, grid, dim3(ef::THREADS), 0, s, role_layout(plan, 1), c.X, A, plan->max_workers);
-    EF_HIP(hipGetLastError());
+    const ef::Layout L = role_layout(plan, 1);
+    // mixed tiles first: they never wait, and the uniform tiles' gathers need their partials
+    if (L.n_mixed) {
+        hipLaunchKernelGGL(ef::k_server_mixed, dim3((unsigned)L.n_mixed), dim3(ef::THREADS), 0, s, L, c.X, A,
+                           plan->max_workers);
+        EF_HIP(hipGetLastError());
+    }
+    if (L.n_uniform) {
+        hipLaunchKernelGGL(ef::k_server_uniform, dim3((unsigned)L.n_uniform), dim3(ef::THREADS), 0, s, L, c.X, A,
+                           plan->max_workers);
+        EF_HIP(hipGetLastError());
+    }
     return launch_second_pass(plan, 1, c, 1, server_err, (int64_t)0, out_scales, s);
 }
 

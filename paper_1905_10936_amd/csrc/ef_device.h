@@ -104,6 +104,7 @@ struct ServerArgs {
     const float *scales_in;     // [M][B]
     float *err;                 // server residual
     float r, Mf;
+    float Minv;                 // 1/M if M is a power of two (exact), else 0
     uint64_t *signs; float *scales;
 };
 
@@ -894,23 +895,95 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
     if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, P.b[0], 0ull, e, L, X, worker, S);
 }
 
-// --------------------------------------------------------- server kernel ---
+// -------------------------------------------------------- server kernels ---
 
-// Server (Algorithm 4, "on server"): decode and add the M payloads in worker
-// order, divide by M, add the rescaled server residual, compress.  One
-// workgroup per tile; a uniform tile of a counted block waits in the kernel.
-__global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerArgs A, int set)
+// (1/M) * acc as Algorithm 4 writes it: one correctly rounded fp32 division, or,
+// when M is a power of two, the product with the exact reciprocal, which is the
+// same real number and therefore rounds to the same bits.
+__device__ __forceinline__ float mean_of(float acc, float Mf, float Minv)
+{
+    return Minv != 0.0f ? acc * Minv : acc / Mf;
+}
+
+constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight together
+
+// Server (Algorithm 4, "on server") on the tiles that lie inside one block:
+// decode and add the M payloads in worker order, divide by M, add the rescaled
+// server residual, compress.  One workgroup per tile; it waits in the kernel
+// for its block's scale.  The sign words of SERVER_CHUNK workers are loaded
+// together (one 32-bit word per worker and sub-row holds this lane's 4 bits),
+// the block's M scales come through scalar loads.
+__global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X, ServerArgs A, int set)
 {
     __shared__ TileShared S;
-    const int32_t tile = blockIdx.x;
+    const int32_t tile = L.uniform_tiles[blockIdx.x];
+    constexpr int n_valid = TILE;
+    const int64_t tile_start = (int64_t)tile * TILE;
+    const int32_t b = L.tile_fb[tile];
+    float *te = A.err + tile_start;
+    Posted P;
+    announce_uniform(L, tile, X, set, P);        // the counter's answer returns under the loads
+    float4 tv[SUBROWS];
+    load_tile(te, tv, n_valid);
+
+    float acc[SUBROWS][4];
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[k][c] = 0.0f;
+
+    const uint32_t *s32 = reinterpret_cast<const uint32_t *>(A.signs_in);
+    const int64_t n_hw = 2 * L.W;
+    const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
+    // half-word index of sub-row k for this lane: consecutive sub-rows are 8 half-words apart
+    const int64_t hw0 = (tile_start + local_base(0)) >> 5;
+
+    for (int i0 = 0; i0 < A.M; i0 += SERVER_CHUNK) {
+        uint32_t word[SERVER_CHUNK][SUBROWS];
+        float sc[SERVER_CHUNK];
+#pragma unroll
+        for (int u = 0; u < SERVER_CHUNK; ++u) {
+            const int i = min(i0 + u, A.M - 1);          // past M: a valid address whose value is not used
+            sc[u] = A.scales_in[(int64_t)i * L.B + b];
+#pragma unroll
+            for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * n_hw + hw0 + 8 * k];
+        }
+#pragma unroll
+        for (int u = 0; u < SERVER_CHUNK; ++u) {
+            if (i0 + u < A.M) {
+#pragma unroll
+                for (int k = 0; k < SUBROWS; ++k) {
+                    const unsigned nibble = (word[u][k] >> sh) & 0xFu;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[k][c] = acc[k][c] + signed_scale(sc[u], (nibble >> c) & 1u);
+                }
+            }
+        }
+    }
+    float4 p[SUBROWS];
+    const float r = A.r, Mf = A.Mf, Minv = A.Minv;
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k) {
+        p[k].x = mean_of(acc[k][0], Mf, Minv) + r * tv[k].x;
+        p[k].y = mean_of(acc[k][1], Mf, Minv) + r * tv[k].y;
+        p[k].z = mean_of(acc[k][2], Mf, Minv) + r * tv[k].z;
+        p[k].w = mean_of(acc[k][3], Mf, Minv) + r * tv[k].w;
+    }
+    const int kind = compress_uniform(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
+    resolve_posted(P, L, X, set, A.scales, S);
+    if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, P.b[0], 0ull, te, L, X, set, S);
+}
+
+// Server on the mixed tiles (several blocks meet, or the ragged last tile): a
+// per-element segment index in LDS selects each worker's scale.  Never waits.
+__global__ __launch_bounds__(THREADS) void k_server_mixed(Layout L, Scratch X, ServerArgs A, int set)
+{
+    __shared__ TileShared S;
+    const int32_t tile = L.mixed_tiles[blockIdx.x];
     const int n_valid = tile_valid(L, tile);
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     float *te = A.err + tile_start;
-    const bool uniform = (fb == lb) && (n_valid == TILE);
-    Posted P;
-    clear_posted(P);
-    if (uniform) announce_uniform(L, tile, X, set, P);   // the counter's answer returns under the loads
     float4 tv[SUBROWS];
     load_tile(te, tv, n_valid);
 
@@ -929,8 +1002,8 @@ __global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerA
     const int64_t n_hw = 2 * L.W;
 
     int segi[SUBROWS][4];
-    if (fb != lb) {
-        build_segment_index(L, tile, n_valid, fb, lb - fb + 1, S);
+    build_segment_index(L, tile, n_valid, fb, lb - fb + 1, S);
+    {
         const int *seg = reinterpret_cast<const int *>(S.val);
 #pragma unroll
         for (int k = 0; k < SUBROWS; ++k)
@@ -939,39 +1012,31 @@ __global__ __launch_bounds__(THREADS) void k_server(Layout L, Scratch X, ServerA
                 const int j = local_base(k) + c;
                 segi[k][c] = (j < n_valid) ? seg[j] : 0;
             }
-        __syncthreads();        // S.val is reused by compress_mixed
     }
+    __syncthreads();            // S.val is reused by compress_mixed
     for (int i = 0; i < A.M; ++i) {
         const float *sc_i = A.scales_in + (int64_t)i * L.B + fb;
-        const float s_uniform = sc_i[0];
 #pragma unroll
         for (int k = 0; k < SUBROWS; ++k) {
             const uint32_t word = (hw[k] < n_hw) ? s32[(int64_t)i * n_hw + hw[k]] : 0u;
             const unsigned nibble = (word >> sh) & 0xFu;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const float s = (fb == lb) ? s_uniform : sc_i[segi[k][c]];
-                acc[k][c] = acc[k][c] + signed_scale(s, (nibble >> c) & 1u);
-            }
+            for (int c = 0; c < 4; ++c)
+                acc[k][c] = acc[k][c] + signed_scale(sc_i[segi[k][c]], (nibble >> c) & 1u);
         }
     }
     float4 p[SUBROWS];
-    const float r = A.r, Mf = A.Mf;
+    const float r = A.r, Mf = A.Mf, Minv = A.Minv;
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
-        p[k].x = acc[k][0] / Mf + r * tv[k].x;
-        p[k].y = acc[k][1] / Mf + r * tv[k].y;
-        p[k].z = acc[k][2] / Mf + r * tv[k].z;
-        p[k].w = acc[k][3] / Mf + r * tv[k].w;
+        p[k].x = mean_of(acc[k][0], Mf, Minv) + r * tv[k].x;
+        p[k].y = mean_of(acc[k][1], Mf, Minv) + r * tv[k].y;
+        p[k].z = mean_of(acc[k][2], Mf, Minv) + r * tv[k].z;
+        p[k].w = mean_of(acc[k][3], Mf, Minv) + r * tv[k].w;
     }
-    if (!uniform) {
-        compress_mixed(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
-        resolve_posted(P, L, X, set, A.scales, S);
-    } else {
-        const int kind = compress_uniform(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
-        resolve_posted(P, L, X, set, A.scales, S);
-        if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, P.b[0], 0ull, te, L, X, set, S);
-    }
+    Posted P;
+    compress_mixed(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
+    resolve_posted(P, L, X, set, A.scales, S);
 }
 
 // ---------------------------------------------------- second-pass kernels ---
