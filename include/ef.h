@@ -97,7 +97,7 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
 int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit in force */
 
 /*
- * Which kernel ef_worker_step runs over the tiles that lie inside one block:
+ * Which kernel ef_worker_step and ef_server_step run over the tiles that lie inside one block:
  * on = 1 a persistent kernel whose workgroups take tiles from a ticket counter
  * and keep several tiles in registers while their scales form; on = 0 one
  * workgroup per tile that waits in place for its block's scale; on < 0 the

@@ -32,7 +32,7 @@ struct ef_plan {
         int32_t *d_late;            // [min(B, 2*ntiles)] capacity
         int32_t *d_counted;         // [min(B, 2*ntiles)] capacity
     } role[2];
-    int32_t lim_persistent, lim_direct, lim_server;   // automatic limits
+    int32_t lim_persistent, lim_direct, lim_server, lim_server_persistent;   // automatic limits
     int32_t user_fuse_limit;        // >= 0: set through ef_plan_tune, overrides the automatic limits
     // device allocations owned by the plan
     int64_t *d_offs;
@@ -43,8 +43,10 @@ struct ef_plan {
     unsigned long long *d_ready;
     unsigned int *d_list_cnt;       // [6]: defer_cnt[2], fin_cnt[2], ticket[2], alternating between calls
     int worker_grid;                // workgroups of the persistent worker kernel
-    int persistent;                 // 1: pipelined persistent worker kernel, 0: one workgroup per tile
+    int persistent;                 // worker: 1 pipelined persistent kernel, 0 one workgroup per tile
     int persistent_auto;            // what plan creation chose for this layout
+    int server_grid;                // workgroups of the persistent server kernel
+    int server_persistent, server_persistent_auto;
     unsigned long long *d_defer_list;
     unsigned long long *d_fin_list;
     int32_t *d_mixed, *d_uniform;   // tile lists
@@ -165,7 +167,7 @@ int refresh_limits(ef_plan *p)
         p->role[0].fuse_limit = p->role[1].fuse_limit = clamp(p->user_fuse_limit);
     } else {
         p->role[0].fuse_limit = clamp(p->persistent ? p->lim_persistent : p->lim_direct);
-        p->role[1].fuse_limit = clamp(p->lim_server);
+        p->role[1].fuse_limit = clamp(p->server_persistent ? p->lim_server_persistent : p->lim_server);
     }
     p->L.fuse_limit = p->role[0].fuse_limit;
     for (auto &r : p->role) {
@@ -266,6 +268,11 @@ int build_device(ef_plan *p)
         p->lim_persistent = (int32_t)((int64_t)p->worker_grid * ef::PIPE_DEPTH / 2);
         p->lim_direct = (int32_t)((int64_t)prop.multiProcessorCount * occ_d / 2);
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
+        int occ_sp = 0;
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_sp, ef::k_server_uniform_persistent, ef::THREADS, 0));
+        if (occ_sp < 1) occ_sp = 1;
+        p->server_grid = prop.multiProcessorCount * occ_sp;
+        p->lim_server_persistent = (int32_t)((int64_t)p->server_grid * ef::PIPE_DEPTH / 2);
     }
     p->user_fuse_limit = -1;
     // The persistent kernel pays off when every workgroup gets many tiles and a block's tiles
@@ -279,9 +286,18 @@ int build_device(ef_plan *p)
         }
         const int64_t tiles_per_wg = (int64_t)p->L.n_uniform * p->max_workers / (p->worker_grid > 0 ? p->worker_grid : 1);
         p->persistent_auto = (tiles_per_wg >= 64 && largest * 4 <= (int64_t)p->worker_grid * ef::TICKET_TILES) ? 1 : 0;
+        int64_t largest_s = 0;
+        for (int64_t b = 0; b < B; ++b) {
+            const int64_t n = tiles_of_block(p, b);
+            if (n >= 2 && n <= p->lim_server_persistent && n > largest_s) largest_s = n;
+        }
+        const int64_t tiles_per_wg_s = (int64_t)p->L.n_uniform / (p->server_grid > 0 ? p->server_grid : 1);
+        p->server_persistent_auto =
+            (tiles_per_wg_s >= 64 && largest_s * 4 <= (int64_t)p->server_grid * ef::TICKET_TILES) ? 1 : 0;
     }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
+    p->server_persistent = p->server_persistent_auto;
     p->calls = 0;
     p->epoch = 0;
     p->last_defer_cnt = p->last_fin_cnt = nullptr;
@@ -441,6 +457,7 @@ int ef_plan_set_persistent(ef_plan *plan, int on)
     if (!plan) return EF_ERR_NULL;
     EF_HIP(hipDeviceSynchronize());
     plan->persistent = on < 0 ? plan->persistent_auto : (on ? 1 : 0);
+    plan->server_persistent = on < 0 ? plan->server_persistent_auto : (on ? 1 : 0);
     return refresh_limits(plan);
 }
 
@@ -523,7 +540,11 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
                            plan->max_workers);
         EF_HIP(hipGetLastError());
     }
-    if (L.n_uniform) {
+    if (L.n_uniform && plan->server_persistent) {
+        const int wgs = L.n_uniform < plan->server_grid ? L.n_uniform : plan->server_grid;
+        hipLaunchKernelGGL(ef::k_server_uniform_persistent, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A);
+        EF_HIP(hipGetLastError());
+    } else if (L.n_uniform) {
         hipLaunchKernelGGL(ef::k_server_uniform, dim3((unsigned)L.n_uniform), dim3(ef::THREADS), 0, s, L, c.X, A,
                            plan->max_workers);
         EF_HIP(hipGetLastError());

@@ -754,7 +754,7 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
     resolve_posted(P, L, X, worker, scales_out, S);
 }
 
-// Uniform tiles of all workers, as a persistent kernel.
+// Uniform tiles as a persistent kernel (worker and server alike).
 //
 // Every workgroup loops: take the next tile, issue its loads, and while they
 // are in flight write out the oldest of the PIPE_DEPTH tiles it holds in
@@ -762,34 +762,41 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
 // the wait is normally over before it starts); then compute the new tile, post
 // its partial sum and keep it in turn.  Tiles are handed out through one ticket
 // counter, TICKET_TILES at a time, so at any moment the resident workgroups
-// work on one compact, advancing window of the five fp32 streams (best DRAM
-// page locality, no dependence on dispatch order), and a workgroup never waits
-// while it holds a tile it has not posted: a wait can only starve if one block
-// had more than (resident workgroups x PIPE_DEPTH) uniform tiles, which
-// fuse_limit rules out, and is bounded by spin_limit in any case.
+// work on one compact, advancing window of the fp32 streams (best DRAM page
+// locality, no dependence on dispatch order).  A workgroup never waits for a
+// block of which it still holds an unposted tile, so a wait only ever depends
+// on workgroups that wait for strictly older blocks; it could starve only if
+// one block had more than (resident workgroups x PIPE_DEPTH) uniform tiles,
+// which fuse_limit rules out, and it is bounded by spin_limit in any case.
+//
+// What is streamed differs per role and comes from a producer:
+//   issue(L, idx, tile)        start the tile's loads (idx: worker, or 0 for the server)
+//   produce(L, idx, tile, p)   the corrected values p of Algorithm 4 (and the role's other stores)
+//   signs(L, idx), scales(L, idx), err_tile(idx, tile)   where that participant's outputs go
 struct HeldTile {
     float4 p[SUBROWS];
     int32_t tile;
-    int set;
+    int idx;
     int b;                      // < 0: slot empty
 };
 
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
+template <class Producer>
+__device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratch &X, Producer &prod, int n_part,
+                                                   TileShared &S)
 {
-    __shared__ TileShared S;
     const unsigned nchunks = (unsigned)((L.n_uniform + TICKET_TILES - 1) / TICKET_TILES);
-    const unsigned total = nchunks * (unsigned)n_workers;
+    const unsigned total = nchunks * (unsigned)n_part;
 
     HeldTile held[PIPE_DEPTH];
 #pragma unroll
     for (int q = 0; q < PIPE_DEPTH; ++q) held[q].b = -1;
     Posted posted;
     clear_posted(posted);
-    int posted_set = 0;
+    int posted_idx = 0;
 
     unsigned tk_next = 0;       // thread 0: the ticket taken ahead of need
     if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);
-    int cur = 0, cur_end = 0, cur_set = 0;
+    int cur = 0, cur_end = 0, cur_idx = 0;
 
     for (;;) {
         // ---- next tile
@@ -799,77 +806,104 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
             const unsigned t = (unsigned)__builtin_amdgcn_readfirstlane((int)S.ticket);
             __syncthreads();
             if (t >= total) break;
-            cur_set = (int)(t / nchunks);
+            cur_idx = (int)(t / nchunks);
             cur = (int)(t % nchunks) * TICKET_TILES;
             cur_end = min(cur + TICKET_TILES, L.n_uniform);
             if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);   // answer is read at the next chunk
         }
         const int32_t tile = L.uniform_tiles[cur++];
-        const int worker = cur_set;
-        constexpr int n_valid = TILE;      // uniform tiles are full tiles
-        const int64_t tile_start = (int64_t)tile * TILE;
-        const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
-        float *m = A.mom + (int64_t)worker * A.state_stride + tile_start;
-        float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
+        const int idx = cur_idx;
+        const int set = X.set_base + idx;
 
         // ---- this tile's loads go out first
-        float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
-        load_tile(g, gv, n_valid);
-        load_tile(m, mv, n_valid);
-        load_tile(e, pv, n_valid);
+        prod.issue(L, idx, tile);
 
         // ---- while they fly: follow up on the previous tile's post, write out the oldest tile held
         HeldTile &old = held[0];
-        const unsigned long long peeked = peek_ready(old.b, L, X, old.b >= 0 ? old.set : 0);
-        resolve_posted(posted, L, X, posted_set, A.scales + (int64_t)posted_set * L.B, S);
+        const unsigned long long peeked = peek_ready(old.b, L, X, X.set_base + (old.b >= 0 ? old.idx : 0));
+        resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
         // The new tile announces itself now, so that the counter's answer returns under the loads.
-        announce_uniform(L, tile, X, worker, posted);
+        announce_uniform(L, tile, X, set, posted);
         if (old.b >= 0) {
             // The block of the oldest tile cannot complete while this workgroup sits on a tile of
             // the same block that is not posted yet (the new one, or the rest of its ticket): then
-            // do not wait, park p and leave the tile to the second pass.  Across different blocks a
-            // wait only ever depends on workgroups waiting for strictly older blocks.
-            bool may_wait = !(old.set == worker && L.tile_fb[tile] == old.b);
-            for (int c = cur; c < cur_end; ++c) may_wait = may_wait && !(old.set == worker && L.tile_fb[L.uniform_tiles[c]] == old.b);
-            float *e_old = A.err + (int64_t)old.set * A.state_stride + (int64_t)old.tile * TILE;
-            finish_uniform(old.p, old.tile, TILE, old.b, peeked, e_old, L, X, old.set, S, may_wait);
+            // do not wait, park p and leave the tile to the second pass.
+            bool may_wait = !(old.idx == idx && L.tile_fb[tile] == old.b);
+            for (int c = cur; c < cur_end; ++c)
+                may_wait = may_wait && !(old.idx == idx && L.tile_fb[L.uniform_tiles[c]] == old.b);
+            finish_uniform(old.p, old.tile, TILE, old.b, peeked, prod.err_tile(old.idx, old.tile), L, X,
+                           X.set_base + old.idx, S, may_wait);
         }
 #pragma unroll
         for (int q = 0; q + 1 < PIPE_DEPTH; ++q) held[q] = held[q + 1];
 
         // ---- the new tile
-        worker_values(gv, mv, pv, A.mu, A.r);
-        store_tile(m, mv, n_valid);
+        float4 pv[SUBROWS];
+        prod.produce(L, idx, tile, pv);
         HeldTile &slot = held[PIPE_DEPTH - 1];
-        const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W,
-                                          A.scales + (int64_t)worker * L.B, e, X, worker, S, posted);
-        posted_set = worker;
+        const int kind = compress_uniform(pv, L, tile, TILE, prod.signs(L, idx), prod.scales(L, idx),
+                                          prod.err_tile(idx, tile), X, set, S, posted);
+        posted_idx = idx;
         slot.b = -1;
         if (kind == UNI_PENDING) {
 #pragma unroll
             for (int k = 0; k < SUBROWS; ++k) slot.p[k] = pv[k];
             slot.tile = tile;
-            slot.set = worker;
+            slot.idx = idx;
             slot.b = posted.b[0];
         }
     }
 
     // ---- drain
-    resolve_posted(posted, L, X, posted_set, A.scales + (int64_t)posted_set * L.B, S);
+    resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
 #pragma unroll
     for (int q = 0; q < PIPE_DEPTH; ++q) {
-        if (held[q].b >= 0) {
-            float *e_q = A.err + (int64_t)held[q].set * A.state_stride + (int64_t)held[q].tile * TILE;
-            finish_uniform(held[q].p, held[q].tile, TILE, held[q].b, 0ull, e_q, L, X, held[q].set, S);
-        }
+        if (held[q].b >= 0)
+            finish_uniform(held[q].p, held[q].tile, TILE, held[q].b, 0ull, prod.err_tile(held[q].idx, held[q].tile), L,
+                           X, X.set_base + held[q].idx, S);
     }
+}
+
+struct WorkerProducer {
+    WorkerArgs A;
+    float4 gv[SUBROWS], mv[SUBROWS], ev[SUBROWS];
+
+    __device__ __forceinline__ uint64_t *signs(const Layout &L, int idx) const { return A.signs + (int64_t)idx * L.W; }
+    __device__ __forceinline__ float *scales(const Layout &L, int idx) const { return A.scales + (int64_t)idx * L.B; }
+    __device__ __forceinline__ float *err_tile(int idx, int32_t tile) const
+    {
+        return A.err + (int64_t)idx * A.state_stride + (int64_t)tile * TILE;
+    }
+    __device__ __forceinline__ void issue(const Layout &, int idx, int32_t tile)
+    {
+        const int64_t tile_start = (int64_t)tile * TILE;
+        load_tile(A.grad + (int64_t)idx * A.grad_stride + tile_start, gv, TILE);
+        load_tile(A.mom + (int64_t)idx * A.state_stride + tile_start, mv, TILE);
+        load_tile(A.err + (int64_t)idx * A.state_stride + tile_start, ev, TILE);
+    }
+    __device__ __forceinline__ void produce(const Layout &, int idx, int32_t tile, float4 (&p)[SUBROWS])
+    {
+        worker_values(gv, mv, ev, A.mu, A.r);
+        store_tile(A.mom + (int64_t)idx * A.state_stride + (int64_t)tile * TILE, mv, TILE);
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) p[k] = ev[k];
+    }
+};
+
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
+{
+    __shared__ TileShared S;
+    WorkerProducer prod;
+    prod.A = A;
+    persistent_uniform(L, X, prod, n_workers, S);
 }
 
 // Uniform tiles of all workers, one workgroup per (tile, worker): the same
 // steps without the pipeline; the workgroup waits in place for its block's
 // scale.  Relies on workgroups being dispatched in grid order (fuse_limit keeps
 // a block's tiles well inside what is resident at once) and on spin_limit.
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(6, 8)))
 void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
 {
     __shared__ TileShared S;
@@ -972,6 +1006,79 @@ __global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X,
     const int kind = compress_uniform(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
     resolve_posted(P, L, X, set, A.scales, S);
     if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, P.b[0], 0ull, te, L, X, set, S);
+}
+
+// The same server work as a persistent kernel (see persistent_uniform).  The
+// sign words of the first SERVER_CHUNK workers travel with the tile's loads;
+// further workers, if any, are fetched while the tile is produced.
+struct ServerProducer {
+    ServerArgs A;
+    float4 tv[SUBROWS];
+    uint32_t word[SERVER_CHUNK][SUBROWS];
+    float sc[SERVER_CHUNK];
+
+    __device__ __forceinline__ uint64_t *signs(const Layout &, int) const { return A.signs; }
+    __device__ __forceinline__ float *scales(const Layout &, int) const { return A.scales; }
+    __device__ __forceinline__ float *err_tile(int, int32_t tile) const { return A.err + (int64_t)tile * TILE; }
+    __device__ __forceinline__ void load_chunk(const Layout &L, int32_t tile, int i0)
+    {
+        const uint32_t *s32 = reinterpret_cast<const uint32_t *>(A.signs_in);
+        const int64_t n_hw = 2 * L.W;
+        const int64_t hw0 = ((int64_t)tile * TILE + local_base(0)) >> 5;
+        const int32_t b = L.tile_fb[tile];
+#pragma unroll
+        for (int u = 0; u < SERVER_CHUNK; ++u) {
+            const int i = min(i0 + u, A.M - 1);          // past M: a valid address whose value is not used
+            sc[u] = A.scales_in[(int64_t)i * L.B + b];
+#pragma unroll
+            for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * n_hw + hw0 + 8 * k];
+        }
+    }
+    __device__ __forceinline__ void issue(const Layout &L, int, int32_t tile)
+    {
+        load_tile(A.err + (int64_t)tile * TILE, tv, TILE);
+        load_chunk(L, tile, 0);
+    }
+    __device__ __forceinline__ void produce(const Layout &L, int, int32_t tile, float4 (&p)[SUBROWS])
+    {
+        const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
+        float acc[SUBROWS][4];
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[k][c] = 0.0f;
+        for (int i0 = 0; i0 < A.M; i0 += SERVER_CHUNK) {
+            if (i0 > 0) load_chunk(L, tile, i0);
+#pragma unroll
+            for (int u = 0; u < SERVER_CHUNK; ++u) {
+                if (i0 + u < A.M) {
+#pragma unroll
+                    for (int k = 0; k < SUBROWS; ++k) {
+                        const unsigned nibble = (word[u][k] >> sh) & 0xFu;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[k][c] = acc[k][c] + signed_scale(sc[u], (nibble >> c) & 1u);
+                    }
+                }
+            }
+        }
+        const float r = A.r, Mf = A.Mf, Minv = A.Minv;
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) {
+            p[k].x = mean_of(acc[k][0], Mf, Minv) + r * tv[k].x;
+            p[k].y = mean_of(acc[k][1], Mf, Minv) + r * tv[k].y;
+            p[k].z = mean_of(acc[k][2], Mf, Minv) + r * tv[k].z;
+            p[k].w = mean_of(acc[k][3], Mf, Minv) + r * tv[k].w;
+        }
+    }
+};
+
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 3)))
+void k_server_uniform_persistent(Layout L, Scratch X, ServerArgs A)
+{
+    __shared__ TileShared S;
+    ServerProducer prod;
+    prod.A = A;
+    persistent_uniform(L, X, prod, 1, S);
 }
 
 // Server on the mixed tiles (several blocks meet, or the ragged last tile): a
