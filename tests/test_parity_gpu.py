@@ -190,3 +190,82 @@ def test_abi_error_codes_on_device():
     with pytest.raises(ef.EfError) as ei:
         ef.ef_apply(st.plan, big[1:st.d + 1], st.ss, st.sc, 0.1)                          # misaligned
     assert ei.value.code == ef.EF_ERR_ALIGN
+
+
+def test_many_steps_with_changing_worker_count_and_stepsize():
+    """Twelve iterations on one plan, the number of workers per call varying
+    (the per-set tags and the call epoch must stay consistent), the stepsize
+    going up and down (Section 3.1: the residual is rescaled by eta_{t-1}/eta_t)."""
+    offs = _offs([3 * 4096 + 17, 40, 4096, 9 * 4096 - 57, 2, 6000])
+    d = int(offs[-1])
+    rng = np.random.default_rng(12)
+    st = GpuState(offs, 4, x0=rng.standard_normal(d).astype(F))
+    etas = [0.02, 0.05, 0.1, 0.1, 0.2, 0.1, 0.05, 0.05, 0.025, 0.0125, 0.1, 0.1]
+    eta_prev = 0.0
+    for t, eta in enumerate(etas):
+        st.set_grads(_grads(rng, 1, 4, d, zeros=0.02)[0])
+        if t % 3 == 1:
+            # a call with fewer workers in between: its outputs are checked against the oracle directly
+            n = 1 + t % 2
+            g, m, e = st.g[:n].clone(), st.m[:n].clone(), st.e[:n].clone()
+            ws = torch.zeros((n, st.W), dtype=torch.int64, device="cuda")
+            wc = torch.zeros((n, st.B), dtype=torch.float32, device="cuda")
+            hm, he = to_np(m[:, :d]).copy(), to_np(e[:, :d]).copy()
+            ef.ef_worker_step(st.plan, g, m, e, 0.9, eta_prev, eta, ws, wc)
+            torch.cuda.synchronize()
+            for i in range(n):
+                s_ref, c_ref = oracle.worker_step(to_np(g[i, :d]).copy(), hm[i], he[i], offs, F(0.9), F(eta_prev), F(eta))
+                assert np.array_equal(to_np(ws[i]), s_ref)
+                assert np.array_equal(to_np(wc[i]).view(np.uint32), c_ref.view(np.uint32))
+                assert np.array_equal(to_np(e[i, :d]).view(np.uint32), he[i].view(np.uint32))
+        synced_step(st, 0.9, eta_prev, eta, None, "long run step %d" % t)
+        eta_prev = eta
+
+
+def test_sixty_four_workers():
+    """EF_MAX_WORKERS workers in one call."""
+    offs = _offs([5000, 100, 8192, 77])
+    d = int(offs[-1])
+    rng = np.random.default_rng(64)
+    st = GpuState(offs, 64)
+    st.set_grads(_grads(rng, 1, 64, d)[0])
+    synced_step(st, 0.9, 0.0, 0.1, None, "64 workers")
+
+
+def test_calls_on_a_side_stream():
+    """The ABI takes the stream to enqueue on; results do not depend on it."""
+    offs = _offs(LAYOUTS["mixed_tiny_and_big"])
+    d = int(offs[-1])
+    rng = np.random.default_rng(5)
+    g = _grads(rng, 1, 2, d)[0]
+    outs = []
+    for use_side in (False, True):
+        st = GpuState(offs, 2)
+        st.set_grads(g)
+        torch.cuda.synchronize()
+        stream = torch.cuda.Stream() if use_side else torch.cuda.current_stream()
+        with torch.cuda.stream(stream):
+            ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.9, 0.0, 0.1, st.ws, st.wc, stream=stream)
+            ef.ef_server_step(st.plan, 2, st.ws, st.wc, st.te, 0.0, 0.1, st.ss, st.sc, stream=stream)
+            ef.ef_apply(st.plan, st.x, st.ss, st.sc, 0.1, stream=stream)
+        stream.synchronize()
+        outs.append([to_np(t).copy() for t in (st.ws, st.wc, st.ss, st.sc, st.m, st.e, st.te, st.x)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+def test_fallback_counters():
+    """The diagnostic counters: none on the one-pass route, every waiting tile
+    when the spin budget is zero."""
+    offs = _offs([4096 * 40, 4096 * 24 + 100, 50])
+    d = int(offs[-1])
+    rng = np.random.default_rng(8)
+    for route, expect_parked in (("direct", False), ("direct_deferred", True), ("one_pass", False), ("deferred", True)):
+        st = GpuState(offs, 2, route=route)
+        st.set_grads(_grads(rng, 1, 2, d)[0])
+        ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.9, 0.0, 0.1, st.ws, st.wc)
+        parked, late = st.plan.last_fallbacks()
+        if expect_parked:
+            assert parked >= 2 * (40 + 23) and late == 4     # every full single-block tile, both big blocks x 2 workers
+        else:
+            assert parked == 0 and late == 0
