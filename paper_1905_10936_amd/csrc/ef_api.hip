@@ -260,9 +260,10 @@ int build_device(ef_plan *p)
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server_uniform, ef::THREADS, 0));
         if (occ_w < 1) occ_w = 1;
         p->worker_grid = prop.multiProcessorCount * occ_w;
-        // one-pass blocks must fit, with a factor 2 to spare, into the tiles a kernel's
-        // workgroups hold at once: grid x PIPE_DEPTH for the persistent worker kernel, the
-        // resident workgroups for the kernels that run one workgroup per tile
+        // one-pass blocks must fit twice over into the tiles a kernel's workgroups hold at once:
+        // grid x PIPE_DEPTH for the persistent kernels, the resident workgroups for the kernels that
+        // run one workgroup per tile (dispatched in grid order).  Larger limits were measured slower:
+        // a block that fills most of the machine makes its first tiles wait for its last.
         int occ_d = 0;
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, ef::k_worker_uniform_direct, ef::THREADS, 0));
         p->lim_persistent = (int32_t)((int64_t)p->worker_grid * ef::PIPE_DEPTH / 2);
@@ -276,7 +277,7 @@ int build_device(ef_plan *p)
     }
     p->user_fuse_limit = -1;
     // The persistent kernel pays off when every workgroup gets many tiles and a block's tiles
-    // are few next to the distance between two tickets of one workgroup (else it keeps running
+    // are fewer than the distance between two tickets of one workgroup (else it keeps running
     // into tiles of a block it still holds and parks them); otherwise one workgroup per tile.
     {
         int64_t largest = 0;
@@ -285,7 +286,7 @@ int build_device(ef_plan *p)
             if (n >= 2 && n <= p->lim_persistent && n > largest) largest = n;
         }
         const int64_t tiles_per_wg = (int64_t)p->L.n_uniform * p->max_workers / (p->worker_grid > 0 ? p->worker_grid : 1);
-        p->persistent_auto = (tiles_per_wg >= 64 && largest * 4 <= (int64_t)p->worker_grid * ef::TICKET_TILES) ? 1 : 0;
+        p->persistent_auto = (tiles_per_wg >= 64 && largest <= (int64_t)p->worker_grid * ef::TICKET_TILES) ? 1 : 0;
         int64_t largest_s = 0;
         for (int64_t b = 0; b < B; ++b) {
             const int64_t n = tiles_of_block(p, b);
@@ -293,7 +294,7 @@ int build_device(ef_plan *p)
         }
         const int64_t tiles_per_wg_s = (int64_t)p->L.n_uniform / (p->server_grid > 0 ? p->server_grid : 1);
         p->server_persistent_auto =
-            (tiles_per_wg_s >= 64 && largest_s * 4 <= (int64_t)p->server_grid * ef::TICKET_TILES) ? 1 : 0;
+            (tiles_per_wg_s >= 64 && largest_s <= (int64_t)p->server_grid * ef::TICKET_TILES) ? 1 : 0;
     }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;

@@ -55,8 +55,14 @@ constexpr int SUBROWS = 4;      // float4 per thread
 constexpr int SMALL_SEG = 64;   // segments up to this length are summed by one thread
 constexpr int MAX_LONG = TILE / SMALL_SEG;
 constexpr int DEFER_WGS = 64;   // workgroups that serve the run-time lists of the second-pass kernels
-constexpr int PIPE_DEPTH = 3;   // tiles a persistent workgroup keeps in registers while their scales form
-constexpr int TICKET_TILES = 2; // consecutive tiles handed out per ticket
+#ifndef EF_PIPE_DEPTH
+#define EF_PIPE_DEPTH 3
+#endif
+#ifndef EF_TICKET_TILES
+#define EF_TICKET_TILES 1
+#endif
+constexpr int PIPE_DEPTH = EF_PIPE_DEPTH;     // tiles a persistent workgroup keeps in registers while their scales form
+constexpr int TICKET_TILES = EF_TICKET_TILES; // consecutive tiles handed out per ticket
 constexpr unsigned long long TAG_BIT = 1ull << 63;
 constexpr int MAX_PER_THREAD = 6;                        // partial words a thread gathers
 constexpr int FUSE_LIMIT_MAX = MAX_PER_THREAD * THREADS; // tiles of the largest one-pass block
@@ -761,7 +767,7 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
 // registers (their blocks' scales have had PIPE_DEPTH tile-times to form, so
 // the wait is normally over before it starts); then compute the new tile, post
 // its partial sum and keep it in turn.  Tiles are handed out through one ticket
-// counter, TICKET_TILES at a time, so at any moment the resident workgroups
+// counter (TICKET_TILES per ticket), so at any moment the resident workgroups
 // work on one compact, advancing window of the fp32 streams (best DRAM page
 // locality, no dependence on dispatch order).  A workgroup never waits for a
 // block of which it still holds an unposted tile, so a wait only ever depends
