@@ -55,6 +55,8 @@ def lib():
                                       ctypes.c_int64, ctypes.c_float, ctypes.c_float, _u64p, _f32p]
         L.efo_apply.argtypes = [_f32p, _u64p, _f32p, ctypes.c_int64, _i64p, ctypes.c_int64,
                                 ctypes.c_float]
+        L.efo_apply_wd.argtypes = [_f32p, _f32p, _u64p, _f32p, ctypes.c_int64, _i64p, ctypes.c_int64,
+                                   ctypes.c_float, ctypes.c_float, ctypes.c_float]
         L.efo_step.argtypes = [ctypes.c_int, _f32p, _f32p, _f32p, _f32p, _f32p, ctypes.c_int64,
                                _i64p, ctypes.c_int64, ctypes.c_float, ctypes.c_float,
                                ctypes.c_float, _u64p, _f32p, _u64p, _f32p]
@@ -172,6 +174,19 @@ def apply(x, signs, scales, offsets, eta):
     if signs.size != sign_words(d) or scales.size != B:
         raise OracleError("payload size does not match block_offsets")
     _chk(lib().efo_apply(_f(x), _u(signs), _f(scales), d, _i(offs), B, eta), "efo_apply")
+
+
+def apply_wd(x, mt, signs, scales, offsets, eta, mu, lam):
+    """Appendix A update with weight decay: mt <- mu*mt + lam*x; x <- x - eta*(decode + mu*mt + lam*x)."""
+    x = _arr(x, np.float32, "x", True)
+    mt = _arr(mt, np.float32, "mt", True)
+    signs = _arr(signs, np.uint64, "signs")
+    scales = _arr(scales, np.float32, "scales")
+    offs, B = _offs(offsets)
+    d = x.size
+    if mt.size != d or signs.size != sign_words(d) or scales.size != B:
+        raise OracleError("sizes do not match block_offsets")
+    _chk(lib().efo_apply_wd(_f(x), _f(mt), _u(signs), _f(scales), d, _i(offs), B, eta, mu, lam), "efo_apply_wd")
 
 
 def step(g, m, e, te, x, offsets, mu, eta_prev, eta):

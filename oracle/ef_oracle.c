@@ -10,6 +10,7 @@
  *   - blockwise scaled-sign compressor C_B            : Section 3.2
  *   - worker / server / parameter update of one step  : Algorithm 4
  *     (Algorithm 3 is the mu = 0 case, Eq. (1) is the B = 1 case)
+ *   - parameter update with weight decay outside compression : Appendix A
  *   - "sign is mapped to {-1, 1} and takes 1 bit",
  *     scale "stored in float32"                       : Appendix A, Section 3.2
  *
@@ -232,6 +233,44 @@ int efo_apply(float *x, const uint64_t *signs, const float *scales, int64_t d,
         for (j = 0; j < d; ++j) {
             float u = eta * delta[j];
             x[j] = x[j] - u;
+        }
+    free(delta);
+    return rc;
+}
+
+/* Parameter update with the weight decay kept outside the compressed signal
+ * (Appendix A): an extra momentum mt for the decay term on every machine,
+ *   mt <- mu*mt + lambda*x
+ *   x  <- x - eta * (Deltatilde + mu*mt + lambda*x)     (updated mt, old x)
+ * evaluated in fp32, one rounding per operation, left to right. */
+int efo_apply_wd(float *x, float *mt, const uint64_t *signs, const float *scales,
+                 int64_t d, const int64_t *offs, int64_t B, float eta, float mu,
+                 float lambda)
+{
+    int64_t j;
+    float *delta;
+    int rc = efo_check_offsets(offs, B, d);
+    if (rc)
+        return rc;
+    if (!x || !mt || !signs || !scales || !(eta > 0.0f))
+        return EFO_BAD_ARG;
+    if (!(mu >= 0.0f && mu < 1.0f) || !(lambda >= 0.0f))
+        return EFO_BAD_ARG;
+    delta = (float *)malloc((size_t)d * sizeof(float));
+    if (!delta)
+        return EFO_NO_MEM;
+    rc = efo_decode(signs, scales, d, offs, B, delta);
+    if (!rc)
+        for (j = 0; j < d; ++j) {
+            float lx = lambda * x[j];
+            float a = mu * mt[j];
+            float mnew = a + lx;
+            float b = mu * mnew;
+            float u1 = delta[j] + b;
+            float u = u1 + lx;
+            float step = eta * u;
+            mt[j] = mnew;
+            x[j] = x[j] - step;
         }
     free(delta);
     return rc;

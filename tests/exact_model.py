@@ -103,3 +103,16 @@ def pack(bits):
         if b:
             words[j // 64] |= 1 << (j % 64)
     return words
+
+
+def apply_wd(x, mt, bits, scales, offs, eta, mu, lam):
+    """Appendix A: mt <- mu*mt + lam*x ; x <- x - eta*(Delta + mu*mt + lam*x)."""
+    delta = decode(bits, scales, offs)
+    x_new, m_new = [], []
+    for j in range(len(x)):
+        lx = f32(lam * x[j])
+        mn = f32(f32(mu * mt[j]) + lx)
+        u = f32(f32(delta[j] + f32(mu * mn)) + lx)
+        m_new.append(mn)
+        x_new.append(f32(x[j] - f32(eta * u)))
+    return x_new, m_new

@@ -429,6 +429,54 @@ def test_restart_from_snapshot_is_bit_identical():
         assert np.array_equal(a, b)
 
 
+# ------------------------------------- Appendix A: weight decay outside C ---
+
+def test_apply_wd_reduces_to_apply_without_decay():
+    """lambda = 0 and a zero decay momentum: the Appendix A update is the plain
+    x <- x - eta*Delta of Algorithm 4, bit for bit."""
+    rng = np.random.default_rng(31)
+    offs = np.array([0, 7, 64, 200])
+    x0 = rng.standard_normal(200).astype(F)
+    signs, scales = oracle.compress(rng.standard_normal(200).astype(F), offs)
+    xa, xb, mt = x0.copy(), x0.copy(), np.zeros(200, F)
+    oracle.apply(xa, signs, scales, offs, F(0.1))
+    oracle.apply_wd(xb, mt, signs, scales, offs, F(0.1), F(0.9), F(0.0))
+    assert np.array_equal(xa, xb) and not mt.any()
+
+
+def test_apply_wd_zero_payload_is_momentum_weight_decay():
+    """With a zero payload the update is m~ <- mu m~ + lam x, x <- x - eta (mu m~ + lam x):
+    run in float64 on dyadic values, where every fp32 operation is exact."""
+    offs = np.array([0, 4, 9])
+    d = 9
+    x = (np.arange(d) - 4).astype(F)               # small integers
+    mt = np.zeros(d, F)
+    signs = np.zeros(1, np.uint64)
+    scales = np.zeros(2, F)
+    xr, mr = x.astype(np.float64), np.zeros(d)
+    for _ in range(4):
+        mr = 0.5 * mr + 0.25 * xr
+        xr = xr - 0.5 * (0.5 * mr + 0.25 * xr)
+        oracle.apply_wd(x, mt, signs, scales, offs, F(0.5), F(0.5), F(0.25))
+        assert np.array_equal(x.astype(np.float64), xr) and np.array_equal(mt.astype(np.float64), mr)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_apply_wd_bruteforce(seed):
+    """Appendix A update against the exact-rational model, inexact constants."""
+    rng = np.random.default_rng(seed)
+    offs = [0, 3, 4, 8]
+    x = rng.standard_normal(8).astype(F)
+    mt = (0.1 * rng.standard_normal(8)).astype(F)
+    signs, scales = oracle.compress(rng.standard_normal(8).astype(F), offs)
+    bits = [int(b) for b in _bits(signs, 8)]
+    eta, mu, lam = F(0.1), F(0.9), F(5e-4)
+    xe, me = xm.apply_wd(_fr(x), _fr(mt), bits, _fr(scales), offs, Fraction(float(eta)), Fraction(float(mu)),
+                         Fraction(float(lam)))
+    oracle.apply_wd(x, mt, signs, scales, offs, eta, mu, lam)
+    assert _fr(x) == xe and _fr(mt) == me
+
+
 # ------------------------------------------------------- argument checks ---
 
 def test_oracle_rejects_bad_partitions():
