@@ -5,9 +5,10 @@
  *
  * One training iteration t of Algorithm 4 is, for M workers on one GPU:
  *
- *     ef_worker_step   (all M workers in one call)   "on each worker i"
- *     ef_server_step                                 "on server"
+ *     ef_worker_step   (all M workers in one call)   the per-worker part
+ *     ef_server_step                                 the parameter-server part
  *     ef_apply                                       x_{t+1} = x_t - eta_t * Delta~_t
+ *       (ef_apply_wd: the same update with weight decay, Appendix A)
  *
  * Conventions shared by every entry point
  * ---------------------------------------
@@ -173,6 +174,56 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
  */
 int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, const float *scales,
              float eta, void *stream);
+
+/*
+ * Parameter update with weight decay kept outside the compressed signal
+ * (Appendix A): every machine holds one more momentum buffer for the decay term,
+ *     decay_mom <- mu * decay_mom + lambda * x
+ *     x         <- x - eta * ((Delta~ + mu * decay_mom) + lambda * x)
+ * with the updated decay_mom and the old x on the right-hand side; lambda * x is
+ * rounded once and used in both lines.  lambda = 0 with a zero decay_mom gives
+ * exactly ef_apply.
+ *
+ *   params        in/out  float[d]
+ *   decay_mom     in/out  float[d], zero before the first iteration
+ *   packed_signs  in      uint64[W]
+ *   scales        in      float[B]
+ *   mu in [0, 1), lambda >= 0, eta > 0 (EF_ERR_ARG otherwise)
+ */
+int ef_apply_wd(const ef_plan *plan, float *params, float *decay_mom, const uint64_t *packed_signs,
+                const float *scales, float eta, float mu, float lambda, void *stream);
+
+/*
+ * Fused messages (Section 4.2: sign words and scales sent as two separate
+ * messages cost the server latency; one message per worker avoids that).
+ *
+ * One message is a single contiguous buffer of ef_payload_bytes(plan) bytes:
+ *     bytes [0, 8*W)                : the W sign words (layout as above)
+ *     bytes [8*W, 8*W + 4*B)        : the B fp32 scales
+ *     padding up to a multiple of 16 bytes (never read, never written)
+ * ef_payload_scales_offset(plan) returns 8*W.  A buffer of n messages holds
+ * message i at byte offset i * ef_payload_bytes(plan); buffers must be 16-byte
+ * aligned (EF_ERR_ALIGN otherwise).  The three calls below compute exactly what
+ * ef_worker_step / ef_server_step / ef_apply compute, bit for bit, with the
+ * same kernels; only the addresses of the payload parts differ, so a worker's
+ * message can be handed to a transport as one buffer and the server consumes
+ * the M received messages in place.
+ *
+ *   ef_worker_step_fused : payloads     out  n_workers messages
+ *   ef_server_step_fused : payloads     in   M messages
+ *                          out_payload  out  one message, not overlapping the input
+ *                                            (EF_ERR_ARG otherwise)
+ *   ef_apply_fused       : payload      in   one message
+ * All other arguments are those of the unfused calls.
+ */
+size_t ef_payload_bytes(const ef_plan *plan);
+size_t ef_payload_scales_offset(const ef_plan *plan);
+int ef_worker_step_fused(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride,
+                         float *mom, float *err, int64_t state_stride, float mu, float eta_prev,
+                         float eta, void *payloads, void *stream);
+int ef_server_step_fused(const ef_plan *plan, int M, const void *payloads, float *server_err,
+                         float eta_prev, float eta, void *out_payload, void *stream);
+int ef_apply_fused(const ef_plan *plan, float *params, const void *payload, float eta, void *stream);
 
 /* Static text for an error code; for EF_ERR_HIP the text of the last HIP error
  * seen by this thread is appended.  The returned pointer stays valid until the

@@ -11,8 +11,8 @@
  *   - worker / server / parameter update of one step  : Algorithm 4
  *     (Algorithm 3 is the mu = 0 case, Eq. (1) is the B = 1 case)
  *   - parameter update with weight decay outside compression : Appendix A
- *   - "sign is mapped to {-1, 1} and takes 1 bit",
- *     scale "stored in float32"                       : Appendix A, Section 3.2
+ *   - one bit per coordinate for the sign in {-1, +1},
+ *     one fp32 scale per block                        : Appendix A, Section 3.2
  *
  * Readings where the paper is silent (kept identical on the GPU side by
  * construction of the tests, not by shared code):

@@ -24,7 +24,8 @@ EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
     "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
-    "ef_sign_words", "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
+    "ef_sign_words", "ef_worker_step", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
+    "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused",
 )
 
 
@@ -71,6 +72,18 @@ def lib():
     L.ef_server_step.argtypes = [vp, c_int, vp, vp, vp, f32, f32, vp, vp, vp]
     L.ef_apply.restype = c_int
     L.ef_apply.argtypes = [vp, vp, vp, vp, f32, vp]
+    L.ef_payload_bytes.restype = ctypes.c_size_t
+    L.ef_payload_bytes.argtypes = [vp]
+    L.ef_payload_scales_offset.restype = ctypes.c_size_t
+    L.ef_payload_scales_offset.argtypes = [vp]
+    L.ef_worker_step_fused.restype = c_int
+    L.ef_worker_step_fused.argtypes = [vp, c_int, vp, i64, vp, vp, i64, f32, f32, f32, vp, vp]
+    L.ef_server_step_fused.restype = c_int
+    L.ef_server_step_fused.argtypes = [vp, c_int, vp, vp, f32, f32, vp, vp]
+    L.ef_apply_fused.restype = c_int
+    L.ef_apply_fused.argtypes = [vp, vp, vp, f32, vp]
+    L.ef_apply_wd.restype = c_int
+    L.ef_apply_wd.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, vp]
     L.ef_strerror.restype = ctypes.c_char_p
     L.ef_strerror.argtypes = [c_int]
     _lib = L
@@ -230,4 +243,60 @@ def ef_apply(plan, params, packed_signs, scales, eta, stream=None):
     rc = lib().ef_apply(plan._h, _ptr(params, torch.float32, "params"),
                         _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
                         _ptr(scales, torch.float32, "scales"), float(eta), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_apply_wd(plan, params, decay_mom, packed_signs, scales, eta, mu, lam, stream=None):
+    if (params.numel() != plan.d or decay_mom.numel() != plan.d or packed_signs.numel() != plan.W
+            or scales.numel() != plan.B):
+        raise TypeError("params/decay_mom/packed_signs/scales must hold d/d/W/B entries")
+    rc = lib().ef_apply_wd(plan._h, _ptr(params, torch.float32, "params"),
+                           _ptr(decay_mom, torch.float32, "decay_mom"),
+                           _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                           _ptr(scales, torch.float32, "scales"), float(eta), float(mu), float(lam),
+                           _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_payload_bytes(plan):
+    return int(lib().ef_payload_bytes(plan._h))
+
+
+def ef_payload_scales_offset(plan):
+    return int(lib().ef_payload_scales_offset(plan._h))
+
+
+def _messages(t, n, plan, name):
+    """A uint8 buffer of n fused messages (Section 4.2: one message per worker)."""
+    if t.numel() != n * ef_payload_bytes(plan):
+        raise TypeError("%s must hold %d messages of %d bytes" % (name, n, ef_payload_bytes(plan)))
+    return _ptr(t, torch.uint8, name)
+
+
+def ef_worker_step_fused(plan, grad, mom, err, mu, eta_prev, eta, payloads, stream=None):
+    n = 1 if grad.dim() == 1 else grad.shape[0]
+    gs, ss = _stride(grad, plan.d, "grad"), _stride(mom, plan.d, "mom")
+    if _stride(err, plan.d, "err") != ss or mom.shape != err.shape:
+        raise TypeError("mom and err must share shape and stride")
+    rc = lib().ef_worker_step_fused(plan._h, n, _ptr(grad, torch.float32, "grad"), gs,
+                                    _ptr(mom, torch.float32, "mom"), _ptr(err, torch.float32, "err"), ss,
+                                    float(mu), float(eta_prev), float(eta), _messages(payloads, n, plan, "payloads"),
+                                    _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_server_step_fused(plan, M, payloads, server_err, eta_prev, eta, out_payload, stream=None):
+    if payloads.numel() < M * ef_payload_bytes(plan) or server_err.numel() != plan.d:
+        raise TypeError("payloads must hold M messages and server_err d floats")
+    rc = lib().ef_server_step_fused(plan._h, int(M), _ptr(payloads, torch.uint8, "payloads"),
+                                    _ptr(server_err, torch.float32, "server_err"), float(eta_prev), float(eta),
+                                    _messages(out_payload, 1, plan, "out_payload"), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_apply_fused(plan, params, payload, eta, stream=None):
+    if params.numel() != plan.d:
+        raise TypeError("params must hold d floats")
+    rc = lib().ef_apply_fused(plan._h, _ptr(params, torch.float32, "params"), _messages(payload, 1, plan, "payload"),
+                              float(eta), _stream_ptr(stream))
     _check(rc)

@@ -352,20 +352,34 @@ ef::Layout role_layout(const ef_plan *plan, int role)
 }
 
 int launch_second_pass(const ef_plan *plan, int role, const CallScratch &c, int nsets, float *err,
-                       int64_t err_stride, float *scales, hipStream_t s)
+                       int64_t err_stride, float *scales, int64_t scales_stride, hipStream_t s)
 {
     const ef_plan::Role &r = plan->role[role];
     const ef::Layout L = role_layout(plan, role);
     hipLaunchKernelGGL(ef::k_finalize_scales, dim3(r.n_late * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s, L, c.X,
-                       (const int32_t *)r.d_late, (int)r.n_late, nsets, scales);
+                       (const int32_t *)r.d_late, (int)r.n_late, nsets, scales, scales_stride);
     EF_HIP(hipGetLastError());
     hipLaunchKernelGGL(ef::k_residual_parked, dim3(r.n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s, L,
                        c.X, (const uint32_t *)r.d_static, (int)r.n_static, nsets, (const int32_t *)r.d_counted,
                        (int)r.n_counted, c.next_defer_cnt, c.next_fin_cnt, c.next_ticket, err, err_stride,
-                       (const float *)scales);
+                       (const float *)scales, scales_stride);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
+
+// Bytes of one fused message: W sign words, then B fp32 scales, padded to 16.
+size_t payload_bytes(const ef_plan *plan)
+{
+    const size_t raw = (size_t)plan->L.W * 8u + (size_t)plan->L.B * 4u;
+    return (raw + 15u) / 16u * 16u;
+}
+
+int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
+                     float *err, int64_t state_stride, float mu, float eta_prev, float eta, uint64_t *packed_signs,
+                     int64_t signs_stride, float *scales, int64_t scales_stride, void *stream);
+int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, int64_t in_signs_stride,
+                     const float *scales, int64_t in_scales_stride, float *server_err, float eta_prev, float eta,
+                     uint64_t *out_signs, float *out_scales, void *stream);
 
 }  // namespace
 
@@ -470,6 +484,61 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
                    float *err, int64_t state_stride, float mu, float eta_prev, float eta,
                    uint64_t *packed_signs, float *scales, void *stream)
 {
+    if (!plan) return EF_ERR_NULL;
+    return worker_step_impl(plan, n_workers, grad, grad_stride, mom, err, state_stride, mu, eta_prev, eta,
+                            packed_signs, plan->L.W, scales, plan->L.B, stream);
+}
+
+size_t ef_payload_bytes(const ef_plan *plan) { return plan ? payload_bytes(plan) : 0; }
+size_t ef_payload_scales_offset(const ef_plan *plan) { return plan ? (size_t)plan->L.W * 8u : 0; }
+
+int ef_worker_step_fused(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
+                         float *err, int64_t state_stride, float mu, float eta_prev, float eta, void *payloads,
+                         void *stream)
+{
+    if (!plan || !payloads) return EF_ERR_NULL;
+    if (!aligned(payloads, 16)) return EF_ERR_ALIGN;
+    const size_t pb = payload_bytes(plan);
+    char *base = static_cast<char *>(payloads);
+    return worker_step_impl(plan, n_workers, grad, grad_stride, mom, err, state_stride, mu, eta_prev, eta,
+                            reinterpret_cast<uint64_t *>(base), (int64_t)(pb / 8u),
+                            reinterpret_cast<float *>(base + (size_t)plan->L.W * 8u), (int64_t)(pb / 4u), stream);
+}
+
+int ef_server_step_fused(const ef_plan *plan, int M, const void *payloads, float *server_err, float eta_prev,
+                         float eta, void *out_payload, void *stream)
+{
+    if (!plan || !payloads || !out_payload) return EF_ERR_NULL;
+    if (!aligned(payloads, 16) || !aligned(out_payload, 16)) return EF_ERR_ALIGN;
+    const size_t pb = payload_bytes(plan), so = (size_t)plan->L.W * 8u;
+    if (M >= 1) {  // the output message may not overlap any input message
+        const char *in0 = static_cast<const char *>(payloads), *o = static_cast<const char *>(out_payload);
+        if (o < in0 + pb * (size_t)M && in0 < o + pb) return EF_ERR_ARG;
+    }
+    const char *in = static_cast<const char *>(payloads);
+    char *out = static_cast<char *>(out_payload);
+    return server_step_impl(plan, M, reinterpret_cast<const uint64_t *>(in), (int64_t)(pb / 8u),
+                            reinterpret_cast<const float *>(in + so), (int64_t)(pb / 4u), server_err, eta_prev, eta,
+                            reinterpret_cast<uint64_t *>(out), reinterpret_cast<float *>(out + so), stream);
+}
+
+int ef_apply_fused(const ef_plan *plan, float *params, const void *payload, float eta, void *stream)
+{
+    if (!plan || !payload) return EF_ERR_NULL;
+    if (!aligned(payload, 16)) return EF_ERR_ALIGN;
+    const char *in = static_cast<const char *>(payload);
+    return ef_apply(plan, params, reinterpret_cast<const uint64_t *>(in),
+                    reinterpret_cast<const float *>(in + (size_t)plan->L.W * 8u), eta, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
+                     float *err, int64_t state_stride, float mu, float eta_prev, float eta, uint64_t *packed_signs,
+                     int64_t signs_stride, float *scales, int64_t scales_stride, void *stream)
+{
     if (!plan || !grad || !mom || !err || !packed_signs || !scales) return EF_ERR_NULL;
     if (n_workers < 1 || n_workers > plan->max_workers) return EF_ERR_ARG;
     if (!(mu >= 0.0f && mu < 1.0f) || !good_eta(eta_prev, eta)) return EF_ERR_ARG;
@@ -490,6 +559,8 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
     A.r = eta_prev / eta;
     A.signs = packed_signs;
     A.scales = scales;
+    A.signs_stride = signs_stride;
+    A.scales_stride = scales_stride;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const CallScratch c = next_call(plan, 0, n_workers);
     const ef::Layout L = role_layout(plan, 0);
@@ -508,12 +579,12 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
                            dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
-    return launch_second_pass(plan, 0, c, n_workers, err, state_stride, scales, s);
+    return launch_second_pass(plan, 0, c, n_workers, err, state_stride, scales, scales_stride, s);
 }
 
-int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, const float *scales,
-                   float *server_err, float eta_prev, float eta, uint64_t *out_signs, float *out_scales,
-                   void *stream)
+int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, int64_t in_signs_stride,
+                     const float *scales, int64_t in_scales_stride, float *server_err, float eta_prev, float eta,
+                     uint64_t *out_signs, float *out_scales, void *stream)
 {
     if (!plan || !packed_signs || !scales || !server_err || !out_signs || !out_scales) return EF_ERR_NULL;
     if (M < 1 || M > plan->max_workers) return EF_ERR_ARG;
@@ -526,6 +597,8 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
     A.M = M;
     A.signs_in = packed_signs;
     A.scales_in = scales;
+    A.in_signs_stride = in_signs_stride;
+    A.in_scales_stride = in_scales_stride;
     A.err = server_err;
     A.r = eta_prev / eta;
     A.Mf = (float)M;
@@ -550,7 +623,20 @@ int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, con
                            plan->max_workers);
         EF_HIP(hipGetLastError());
     }
-    return launch_second_pass(plan, 1, c, 1, server_err, (int64_t)0, out_scales, s);
+    return launch_second_pass(plan, 1, c, 1, server_err, (int64_t)0, out_scales, (int64_t)0, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, const float *scales,
+                   float *server_err, float eta_prev, float eta, uint64_t *out_signs, float *out_scales,
+                   void *stream)
+{
+    if (!plan) return EF_ERR_NULL;
+    return server_step_impl(plan, M, packed_signs, plan->L.W, scales, plan->L.B, server_err, eta_prev, eta,
+                            out_signs, out_scales, stream);
 }
 
 int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, const float *scales, float eta,
@@ -562,6 +648,23 @@ int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, c
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)plan->L.ntiles, 1u);
     hipLaunchKernelGGL(ef::k_apply, grid, dim3(ef::THREADS), 0, s, plan->L, params, packed_signs, scales, eta);
+    EF_HIP(hipGetLastError());
+    return EF_OK;
+}
+
+int ef_apply_wd(const ef_plan *plan, float *params, float *decay_mom, const uint64_t *packed_signs,
+                const float *scales, float eta, float mu, float lambda, void *stream)
+{
+    if (!plan || !params || !decay_mom || !packed_signs || !scales) return EF_ERR_NULL;
+    if (!(std::isfinite(eta) && eta > 0.0f)) return EF_ERR_ARG;
+    if (!(mu >= 0.0f && mu < 1.0f)) return EF_ERR_ARG;
+    if (!(std::isfinite(lambda) && lambda >= 0.0f)) return EF_ERR_ARG;
+    if (!aligned(params, 16) || !aligned(decay_mom, 16) || !aligned(packed_signs, 8) || !aligned(scales, 4))
+        return EF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)plan->L.ntiles, 1u);
+    hipLaunchKernelGGL(ef::k_apply_wd, grid, dim3(ef::THREADS), 0, s, plan->L, params, decay_mom, packed_signs,
+                       scales, eta, mu, lambda);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }

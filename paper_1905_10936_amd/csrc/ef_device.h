@@ -102,12 +102,15 @@ struct WorkerArgs {
     float *mom; float *err; int64_t state_stride;
     float mu, r;
     uint64_t *signs; float *scales;
+    int64_t signs_stride;       // 64-bit words between the payloads of two workers
+    int64_t scales_stride;      // floats between the scale arrays of two workers
 };
 
 struct ServerArgs {
     int M;
-    const uint64_t *signs_in;   // [M][W]
-    const float *scales_in;     // [M][B]
+    const uint64_t *signs_in;   // worker i at signs_in + i*in_signs_stride (64-bit words)
+    const float *scales_in;     // worker i at scales_in + i*in_scales_stride (floats)
+    int64_t in_signs_stride, in_scales_stride;
     float *err;                 // server residual
     float r, Mf;
     float Minv;                 // 1/M if M is a power of two (exact), else 0
@@ -755,8 +758,8 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
     worker_values(gv, mv, pv, A.mu, A.r);
     store_tile(m, mv, n_valid);
     Posted P;
-    float *scales_out = A.scales + (int64_t)worker * L.B;
-    compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W, scales_out, e, X, worker, S, P);
+    float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
+    compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker, S, P);
     resolve_posted(P, L, X, worker, scales_out, S);
 }
 
@@ -874,8 +877,8 @@ struct WorkerProducer {
     WorkerArgs A;
     float4 gv[SUBROWS], mv[SUBROWS], ev[SUBROWS];
 
-    __device__ __forceinline__ uint64_t *signs(const Layout &L, int idx) const { return A.signs + (int64_t)idx * L.W; }
-    __device__ __forceinline__ float *scales(const Layout &L, int idx) const { return A.scales + (int64_t)idx * L.B; }
+    __device__ __forceinline__ uint64_t *signs(const Layout &L, int idx) const { return A.signs + (int64_t)idx * A.signs_stride; }
+    __device__ __forceinline__ float *scales(const Layout &L, int idx) const { return A.scales + (int64_t)idx * A.scales_stride; }
     __device__ __forceinline__ float *err_tile(int idx, int32_t tile) const
     {
         return A.err + (int64_t)idx * A.state_stride + (int64_t)tile * TILE;
@@ -928,8 +931,8 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
     load_tile(e, pv, n_valid);
     worker_values(gv, mv, pv, A.mu, A.r);
     store_tile(m, mv, n_valid);
-    float *scales_out = A.scales + (int64_t)worker * L.B;
-    const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * L.W, scales_out, e, X, worker,
+    float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
+    const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker,
                                       S, P);
     resolve_posted(P, L, X, worker, scales_out, S);
     if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, P.b[0], 0ull, e, L, X, worker, S);
@@ -973,7 +976,7 @@ __global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X,
         for (int c = 0; c < 4; ++c) acc[k][c] = 0.0f;
 
     const uint32_t *s32 = reinterpret_cast<const uint32_t *>(A.signs_in);
-    const int64_t n_hw = 2 * L.W;
+    const int64_t in_hw = 2 * A.in_signs_stride;
     const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
     // half-word index of sub-row k for this lane: consecutive sub-rows are 8 half-words apart
     const int64_t hw0 = (tile_start + local_base(0)) >> 5;
@@ -984,9 +987,9 @@ __global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X,
 #pragma unroll
         for (int u = 0; u < SERVER_CHUNK; ++u) {
             const int i = min(i0 + u, A.M - 1);          // past M: a valid address whose value is not used
-            sc[u] = A.scales_in[(int64_t)i * L.B + b];
+            sc[u] = A.scales_in[(int64_t)i * A.in_scales_stride + b];
 #pragma unroll
-            for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * n_hw + hw0 + 8 * k];
+            for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * in_hw + hw0 + 8 * k];
         }
 #pragma unroll
         for (int u = 0; u < SERVER_CHUNK; ++u) {
@@ -1029,15 +1032,15 @@ struct ServerProducer {
     __device__ __forceinline__ void load_chunk(const Layout &L, int32_t tile, int i0)
     {
         const uint32_t *s32 = reinterpret_cast<const uint32_t *>(A.signs_in);
-        const int64_t n_hw = 2 * L.W;
+        const int64_t in_hw = 2 * A.in_signs_stride;
         const int64_t hw0 = ((int64_t)tile * TILE + local_base(0)) >> 5;
         const int32_t b = L.tile_fb[tile];
 #pragma unroll
         for (int u = 0; u < SERVER_CHUNK; ++u) {
             const int i = min(i0 + u, A.M - 1);          // past M: a valid address whose value is not used
-            sc[u] = A.scales_in[(int64_t)i * L.B + b];
+            sc[u] = A.scales_in[(int64_t)i * A.in_scales_stride + b];
 #pragma unroll
-            for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * n_hw + hw0 + 8 * k];
+            for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * in_hw + hw0 + 8 * k];
         }
     }
     __device__ __forceinline__ void issue(const Layout &L, int, int32_t tile)
@@ -1113,6 +1116,7 @@ __global__ __launch_bounds__(THREADS) void k_server_mixed(Layout L, Scratch X, S
     for (int k = 0; k < SUBROWS; ++k) hw[k] = (tile_start + local_base(k)) >> 5;
     const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
     const int64_t n_hw = 2 * L.W;
+    const int64_t in_hw = 2 * A.in_signs_stride;
 
     int segi[SUBROWS][4];
     build_segment_index(L, tile, n_valid, fb, lb - fb + 1, S);
@@ -1128,10 +1132,10 @@ __global__ __launch_bounds__(THREADS) void k_server_mixed(Layout L, Scratch X, S
     }
     __syncthreads();            // S.val is reused by compress_mixed
     for (int i = 0; i < A.M; ++i) {
-        const float *sc_i = A.scales_in + (int64_t)i * L.B + fb;
+        const float *sc_i = A.scales_in + (int64_t)i * A.in_scales_stride + fb;
 #pragma unroll
         for (int k = 0; k < SUBROWS; ++k) {
-            const uint32_t word = (hw[k] < n_hw) ? s32[(int64_t)i * n_hw + hw[k]] : 0u;
+            const uint32_t word = (hw[k] < n_hw) ? s32[(int64_t)i * in_hw + hw[k]] : 0u;
             const unsigned nibble = (word >> sh) & 0xFu;
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -1201,7 +1205,8 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
 // fuse_limit: workgroups 0 .. n_late*nsets-1) and those whose last arriver gave
 // up gathering (list filled at run time: the last DEFER_WGS workgroups).
 __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X, const int32_t *late_blocks,
-                                                             int n_late, int nsets, float *scales)
+                                                             int n_late, int nsets, float *scales,
+                                                             int64_t scales_stride)
 {
     __shared__ double red[NWAVES];
     const int n_static = n_late * nsets;
@@ -1209,7 +1214,7 @@ __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X
         const int64_t b = late_blocks[blockIdx.x % n_late];
         const int w = blockIdx.x / n_late;
         const double total = sum_block_partials(L, b, set_part(X, L, X.set_base + w), red);
-        if (threadIdx.x == 0) scales[(int64_t)w * L.B + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+        if (threadIdx.x == 0) scales[(int64_t)w * scales_stride + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
         return;
     }
     const unsigned n = *X.fin_cnt;
@@ -1219,7 +1224,7 @@ __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X
         const int64_t b = (int64_t)(it & 0xffffffffull);
         const double total = sum_block_partials(L, b, set_part(X, L, set), red);
         if (threadIdx.x == 0)
-            scales[(int64_t)(set - X.set_base) * L.B + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+            scales[(int64_t)(set - X.set_base) * scales_stride + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
     }
 }
 
@@ -1232,7 +1237,8 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X
                                                              int n_items, int nsets, const int32_t *counted_blocks,
                                                              int n_counted, unsigned int *next_defer_cnt,
                                                              unsigned int *next_fin_cnt, unsigned int *next_ticket,
-                                                             float *err, int64_t err_stride, const float *scales)
+                                                             float *err, int64_t err_stride, const float *scales,
+                                                             int64_t scales_stride)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *next_defer_cnt = 0u;
@@ -1248,7 +1254,7 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X
         const uint32_t it = items[blockIdx.x % n_items];
         const int w = blockIdx.x / n_items;
         residual_segment(L, (int32_t)(it >> 1), (int)(it & 1u), err + (int64_t)w * err_stride,
-                         scales + (int64_t)w * L.B);
+                         scales + (int64_t)w * scales_stride);
         return;
     }
     const unsigned n = *X.defer_cnt;
@@ -1256,28 +1262,33 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X
         const unsigned long long it = X.defer_list[i];
         const int w = (int)(it >> 33) - X.set_base;
         const int32_t tile = (int32_t)((it >> 1) & 0xffffffffull);
-        residual_segment(L, tile, (int)(it & 1ull), err + (int64_t)w * err_stride, scales + (int64_t)w * L.B);
+        residual_segment(L, tile, (int)(it & 1ull), err + (int64_t)w * err_stride, scales + (int64_t)w * scales_stride);
     }
 }
 
 // ----------------------------------------------------------- apply kernel ---
 
-// Parameter update x <- x - eta * Delta~ (Algorithm 4).
-__global__ __launch_bounds__(THREADS) void k_apply(Layout L, float *x, const uint64_t *signs,
-                                                   const float *scales, float eta)
+// Parameter update.  WD = false: x <- x - eta * Delta~ (Algorithm 4).
+// WD = true: weight decay kept outside the compressed signal (Appendix A),
+//   mt <- mu*mt + lambda*x ;  x <- x - eta*((Delta~ + mu*mt) + lambda*x),
+// one fp32 rounding per operation in the order written.
+template <bool WD>
+__device__ __forceinline__ void apply_tile(const Layout &L, float *x, float *mt, const uint64_t *signs,
+                                           const float *scales, float eta, float mu, float lambda, TileShared &S)
 {
-    __shared__ TileShared S;
     const int32_t tile = blockIdx.x;
     const int n_valid = tile_valid(L, tile);
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     float *xt = x + tile_start;
+    float *mtt = WD ? mt + tile_start : nullptr;
     const uint32_t *s32 = reinterpret_cast<const uint32_t *>(signs);
     const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
     const int64_t n_hw = 2 * L.W;
     const int *seg = reinterpret_cast<const int *>(S.val);
-    float4 xv4[SUBROWS];
+    float4 xv4[SUBROWS], mv4[SUBROWS];
     load_tile(xt, xv4, n_valid);
+    if (WD) load_tile(mtt, mv4, n_valid);
     if (fb != lb) build_segment_index(L, tile, n_valid, fb, lb - fb + 1, S);
     const float s_uniform = scales[fb];
 #pragma unroll
@@ -1287,17 +1298,52 @@ __global__ __launch_bounds__(THREADS) void k_apply(Layout L, float *x, const uin
         const uint32_t word = (hw < n_hw) ? s32[hw] : 0u;
         const unsigned nibble = (word >> sh) & 0xFu;
         float xv[4] = {xv4[k].x, xv4[k].y, xv4[k].z, xv4[k].w};
+        float mv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (WD) {
+            mv[0] = mv4[k].x;
+            mv[1] = mv4[k].y;
+            mv[2] = mv4[k].z;
+            mv[3] = mv4[k].w;
+        }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int j = lb0 + c;
             float s = s_uniform;
             if (fb != lb) s = scales[fb + ((j < n_valid) ? seg[j] : 0)];
-            const float u = eta * signed_scale(s, (nibble >> c) & 1u);
-            xv[c] = xv[c] - u;
+            const float delta = signed_scale(s, (nibble >> c) & 1u);
+            if (WD) {
+                const float lx = lambda * xv[c];
+                const float a = mu * mv[c];
+                mv[c] = a + lx;
+                const float b = mu * mv[c];
+                const float u1 = delta + b;
+                const float u = u1 + lx;
+                const float step = eta * u;
+                xv[c] = xv[c] - step;
+            } else {
+                const float u = eta * delta;
+                xv[c] = xv[c] - u;
+            }
         }
         xv4[k] = make_float4(xv[0], xv[1], xv[2], xv[3]);
+        if (WD) mv4[k] = make_float4(mv[0], mv[1], mv[2], mv[3]);
     }
     store_tile(xt, xv4, n_valid);
+    if (WD) store_tile(mtt, mv4, n_valid);
+}
+
+__global__ __launch_bounds__(THREADS) void k_apply(Layout L, float *x, const uint64_t *signs,
+                                                   const float *scales, float eta)
+{
+    __shared__ TileShared S;
+    apply_tile<false>(L, x, nullptr, signs, scales, eta, 0.0f, 0.0f, S);
+}
+
+__global__ __launch_bounds__(THREADS) void k_apply_wd(Layout L, float *x, float *mt, const uint64_t *signs,
+                                                      const float *scales, float eta, float mu, float lambda)
+{
+    __shared__ TileShared S;
+    apply_tile<true>(L, x, mt, signs, scales, eta, mu, lambda, S);
 }
 
 }  // namespace ef

@@ -57,7 +57,7 @@ def check_vector(gpu, cpu, scales_cpu, same_scale, offs, what):
 class GpuState:
     """Device tensors of M workers + server + parameters for one layout."""
 
-    def __init__(self, offs, M, device="cuda", x0=None, pad=0, route="one_pass"):
+    def __init__(self, offs, M, device="cuda", x0=None, pad=0, route="one_pass", fused=False):
         self.offs = np.asarray(offs, dtype=np.int64)
         self.d = int(self.offs[-1])
         self.B = self.offs.size - 1
@@ -91,6 +91,21 @@ class GpuState:
         self.wc = torch.zeros((M, self.B), dtype=torch.float32, device=dev)
         self.ss = torch.zeros(self.W, dtype=torch.int64, device=dev)
         self.sc = torch.zeros(self.B, dtype=torch.float32, device=dev)
+        # one contiguous message per worker (sign words, then scales) instead of two arrays
+        self.fused = fused
+        if fused:
+            self.pb = ef.ef_payload_bytes(self.plan)
+            self.so = ef.ef_payload_scales_offset(self.plan)
+            assert self.so == 8 * self.W and self.pb % 16 == 0 and 0 <= self.pb - (self.so + 4 * self.B) < 16
+            self.wmsg = torch.zeros((M, self.pb), dtype=torch.uint8, device=dev)
+            self.smsg = torch.zeros(self.pb, dtype=torch.uint8, device=dev)
+
+    def split(self, msg):
+        """Host copy of fused messages [n][pb] -> (sign words [n][W], scales [n][B], padding bytes)."""
+        a = to_np(msg).reshape(-1, self.pb)
+        signs = np.ascontiguousarray(a[:, :self.so]).view(np.uint64)
+        scales = np.ascontiguousarray(a[:, self.so:self.so + 4 * self.B]).view(np.float32)
+        return signs, scales, a[:, self.so + 4 * self.B:]
 
     def set_grads(self, g):
         self.g[:, :self.d].copy_(torch.as_tensor(g))
@@ -112,9 +127,17 @@ def synced_step(st, mu, eta_prev, eta, stats=None, tag=""):
     st.ss.fill_(0x5555555555555555)
     st.sc.fill_(-7.0)
     # ---- worker
-    ef.ef_worker_step(st.plan, st.g, st.m, st.e, mu, eta_prev, eta, st.ws, st.wc)
-    torch.cuda.synchronize()
-    ws, wc = to_np(st.ws), to_np(st.wc)
+    if st.fused:
+        st.wmsg.fill_(0xA5)
+        st.smsg.fill_(0xA5)
+        ef.ef_worker_step_fused(st.plan, st.g, st.m, st.e, mu, eta_prev, eta, st.wmsg)
+        torch.cuda.synchronize()
+        ws, wc, padding = st.split(st.wmsg)
+        assert (padding == 0xA5).all(), "%s: worker wrote into the padding of a message" % tag
+    else:
+        ef.ef_worker_step(st.plan, st.g, st.m, st.e, mu, eta_prev, eta, st.ws, st.wc)
+        torch.cuda.synchronize()
+        ws, wc = to_np(st.ws), to_np(st.wc)
     n_loose = 0
     for i in range(M):
         m_i, e_i = h["m"][i].copy(), h["e"][i].copy()
@@ -130,18 +153,29 @@ def synced_step(st, mu, eta_prev, eta, stats=None, tag=""):
     if st.stride > d:
         assert not to_np(st.m[:, d:]).any() and not to_np(st.e[:, d:]).any(), "%s: wrote past d" % tag
     # ---- server, fed with the GPU's worker payloads on both sides
-    ef.ef_server_step(st.plan, M, st.ws, st.wc, st.te, eta_prev, eta, st.ss, st.sc)
+    if st.fused:
+        ef.ef_server_step_fused(st.plan, M, st.wmsg, st.te, eta_prev, eta, st.smsg)
+    else:
+        ef.ef_server_step(st.plan, M, st.ws, st.wc, st.te, eta_prev, eta, st.ss, st.sc)
     torch.cuda.synchronize()
     te_ref = h["te"].copy()
     ss_ref, sc_ref = oracle.server_step(np.ascontiguousarray(ws), np.ascontiguousarray(wc), te_ref, offs,
                                         F(eta_prev), F(eta))
-    ss, sc = to_np(st.ss), to_np(st.sc)
+    if st.fused:
+        ss, sc, padding = st.split(st.smsg)
+        ss, sc = ss[0], sc[0]
+        assert (padding == 0xA5).all(), "%s: server wrote into the padding of its message" % tag
+    else:
+        ss, sc = to_np(st.ss), to_np(st.sc)
     assert np.array_equal(ss, ss_ref), "%s server: sign words differ (%d words)" % (tag, (ss != ss_ref).sum())
     same = check_scales(sc, sc_ref, "%s server" % tag)
     n_loose += int((~same).sum())
     check_vector(to_np(st.te), te_ref, sc_ref, same, offs, "%s server residual" % tag)
     # ---- apply, fed with the GPU's server payload on both sides
-    ef.ef_apply(st.plan, st.x, st.ss, st.sc, eta)
+    if st.fused:
+        ef.ef_apply_fused(st.plan, st.x, st.smsg, eta)
+    else:
+        ef.ef_apply(st.plan, st.x, st.ss, st.sc, eta)
     torch.cuda.synchronize()
     x_ref = h["x"].copy()
     oracle.apply(x_ref, np.ascontiguousarray(ss), np.ascontiguousarray(sc), offs, F(eta))
