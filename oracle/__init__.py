@@ -51,6 +51,8 @@ def lib():
         L.efo_decode.argtypes = [_u64p, _f32p, ctypes.c_int64, _i64p, ctypes.c_int64, _f32p]
         L.efo_worker_step.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int64, _i64p, ctypes.c_int64,
                                       ctypes.c_float, ctypes.c_float, ctypes.c_float, _u64p, _f32p]
+        L.efo_worker_step_sgd.argtypes = [_f32p, _f32p, ctypes.c_int64, _i64p, ctypes.c_int64,
+                                          ctypes.c_float, ctypes.c_float, _u64p, _f32p]
         L.efo_server_step.argtypes = [ctypes.c_int, _u64p, _f32p, _f32p, ctypes.c_int64, _i64p,
                                       ctypes.c_int64, ctypes.c_float, ctypes.c_float, _u64p, _f32p]
         L.efo_apply.argtypes = [_f32p, _u64p, _f32p, ctypes.c_int64, _i64p, ctypes.c_int64,
@@ -141,6 +143,21 @@ def worker_step(g, m, e, offsets, mu, eta_prev, eta):
     scales = np.zeros(B, dtype=np.float32)
     _chk(lib().efo_worker_step(_f(g), _f(m), _f(e), d, _i(offs), B, mu, eta_prev, eta,
                                _u(signs), _f(scales)), "efo_worker_step")
+    return signs, scales
+
+
+def worker_step_sgd(g, e, offsets, eta_prev, eta):
+    """One worker of Algorithm 3 (no momentum), one iteration.  e is updated in place."""
+    g = _arr(g, np.float32, "g")
+    e = _arr(e, np.float32, "e", True)
+    offs, B = _offs(offsets)
+    d = g.size
+    if e.size != d:
+        raise OracleError("g, e must have equal length")
+    signs = np.zeros(sign_words(d), dtype=np.uint64)
+    scales = np.zeros(B, dtype=np.float32)
+    _chk(lib().efo_worker_step_sgd(_f(g), _f(e), d, _i(offs), B, eta_prev, eta, _u(signs), _f(scales)),
+         "efo_worker_step_sgd")
     return signs, scales
 
 

@@ -25,13 +25,19 @@
  *   - (1/M) sum_i: fp32 running sum in worker order starting from +0, then one
  *     fp32 division by (float)M.
  *   - eta_{t-1}/eta_t: one fp32 division; eta_{-1} = 0 gives ratio 0.
+ *   - Appendix A update, per coordinate, one rounding per operation:
+ *     lx = lambda*x ; mt = mu*mt + lx ; x = x - eta*((Delta + mu*mt) + lx).
  *   - packing: flat index j -> bit (j mod 64) of 64-bit word floor(j/64),
  *     least significant bit first; bits past d are 0.
  *
  * Pins (tests/test_oracle_pins.py): every function here is pinned by closed
  * forms, the paper's constant-magnitude example, the Proposition 1 energy
  * identity, the Lemma 3 recurrence, brute force on tiny inputs, and special
- * cases (identity compressor, M = 1, majority vote).  Nothing is unpinned.
+ * cases (identity compressor, M = 1, majority vote).  The Algorithm 3 worker
+ * is pinned to the Algorithm 4 worker at mu = 0 (the reduction Section 4.1
+ * states) and to the brute force; the Appendix A update to efo_apply at
+ * lambda = 0, to a float64 run of the decay-momentum recursion on dyadic values
+ * (zero payload) and to the brute force.  Nothing is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -143,6 +149,47 @@ int efo_worker_step(const float *g, float *m, float *e, int64_t d,
         t2 = t1 + g[j];
         t3 = r * e[j];
         p[j] = t2 + t3;
+    }
+    rc = efo_compress(p, d, offs, B, signs, scales);
+    if (!rc)
+        rc = efo_decode(signs, scales, d, offs, B, delta);
+    if (!rc)
+        for (j = 0; j < d; ++j)
+            e[j] = p[j] - delta[j];
+    free(p);
+    free(delta);
+    return rc;
+}
+
+/* One worker's part of iteration t of Algorithm 3 (no momentum):
+ *   p  = g + (eta_prev/eta)*e
+ *   Delta = C_B(p)  -> (signs, scales)
+ *   e <- p - Delta
+ */
+int efo_worker_step_sgd(const float *g, float *e, int64_t d, const int64_t *offs,
+                        int64_t B, float eta_prev, float eta, uint64_t *signs,
+                        float *scales)
+{
+    int64_t j;
+    float r, *p, *delta;
+    int rc = efo_check_offsets(offs, B, d);
+    if (rc)
+        return rc;
+    if (!g || !e || !signs || !scales)
+        return EFO_BAD_ARG;
+    if (!(eta > 0.0f) || !(eta_prev >= 0.0f))
+        return EFO_BAD_ARG;
+    p = (float *)malloc((size_t)d * sizeof(float));
+    delta = (float *)malloc((size_t)d * sizeof(float));
+    if (!p || !delta) {
+        free(p);
+        free(delta);
+        return EFO_NO_MEM;
+    }
+    r = eta_prev / eta;
+    for (j = 0; j < d; ++j) {
+        float t = r * e[j];
+        p[j] = g[j] + t;
     }
     rc = efo_compress(p, d, offs, B, signs, scales);
     if (!rc)

@@ -116,3 +116,12 @@ def apply_wd(x, mt, bits, scales, offs, eta, mu, lam):
         m_new.append(mn)
         x_new.append(f32(x[j] - f32(eta * u)))
     return x_new, m_new
+
+
+def worker_sgd(g, e, offs, r):
+    """Algorithm 3 worker: p = g + r e."""
+    d = len(g)
+    p = [f32(g[j] + f32(r * e[j])) for j in range(d)]
+    bits, scales = compress(p, offs)
+    delta = decode(bits, scales, offs)
+    return [f32(p[j] - delta[j]) for j in range(d)], bits, scales

@@ -429,6 +429,43 @@ def test_restart_from_snapshot_is_bit_identical():
         assert np.array_equal(a, b)
 
 
+# ------------------------------------------- Algorithm 3 (no momentum) ---
+
+def test_sgd_worker_is_momentum_worker_at_mu_zero():
+    """Section 4.1: Algorithm 4 with mu = 0 is dist-EF-blockSGD (Algorithm 3).
+    Run both workers over several steps with a changing stepsize; payloads and
+    residuals agree (zeros compared by value: 0*m + g turns a -0 into +0)."""
+    rng = np.random.default_rng(5)
+    offs = np.array([0, 1, 9, 64, 65, 300])
+    d = 300
+    m, e4, e3 = np.zeros(d, F), np.zeros(d, F), np.zeros(d, F)
+    eta_prev = F(0)
+    for eta in (F(0.1), F(0.3), F(0.05), F(0.05)):
+        g = rng.standard_normal(d).astype(F)
+        g[rng.random(d) < 0.1] = 0.0
+        s4, c4 = oracle.worker_step(g, m, e4, offs, F(0), eta_prev, eta)
+        s3, c3 = oracle.worker_step_sgd(g, e3, offs, eta_prev, eta)
+        assert np.array_equal(s4, s3) and np.array_equal(c4, c3)
+        assert np.array_equal(e4, e3) and np.array_equal(m, g)
+        eta_prev = eta
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_sgd_worker_bruteforce(seed):
+    rng = np.random.default_rng(seed + 40)
+    offs = [0, 2, 3, 9]
+    e = np.zeros(9, F)
+    ee = _fr(e)
+    eta_prev = F(0)
+    for eta in (F(0.1), F(0.3), F(0.07)):
+        g = rng.standard_normal(9).astype(F)
+        r = xm.f32(Fraction(float(eta_prev)) / Fraction(float(eta)))
+        ee, bits, sc = xm.worker_sgd(_fr(g), ee, offs, r)
+        signs, scales = oracle.worker_step_sgd(g, e, offs, eta_prev, eta)
+        assert [int(b) for b in _bits(signs, 9)] == bits and _fr(scales) == sc and _fr(e) == ee
+        eta_prev = eta
+
+
 # ------------------------------------- Appendix A: weight decay outside C ---
 
 def test_apply_wd_reduces_to_apply_without_decay():
