@@ -147,6 +147,20 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
                    float eta, uint64_t *packed_signs, float *scales, void *stream);
 
 /*
+ * The same call for dist-EF-blockSGD (Algorithm 3; Section 4.1 notes that it is
+ * Algorithm 4 at mu = 0): no momentum buffer exists, so none is read or
+ * written,
+ *     p     = g + (eta_prev/eta) * e
+ *     Delta = C_B(p)  -> packed_signs, scales
+ *     e    <- p - Delta
+ * Arguments as for ef_worker_step.  Payloads and residuals equal those of
+ * ef_worker_step with mu = 0 (a zero of either sign may differ in sign).
+ */
+int ef_worker_step_sgd(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride,
+                       float *err, int64_t state_stride, float eta_prev, float eta,
+                       uint64_t *packed_signs, float *scales, void *stream);
+
+/*
  * Server side of iteration t of Algorithm 4:
  *     p~   = (1/M) * sum_i Delta_i + (eta_prev / eta) * e~
  *     push  Delta~ = C_B(p~)  -> out_signs, out_scales

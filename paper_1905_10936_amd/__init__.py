@@ -24,7 +24,7 @@ EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
     "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
-    "ef_sign_words", "ef_worker_step", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
+    "ef_sign_words", "ef_worker_step", "ef_worker_step_sgd", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
     "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused",
 )
 
@@ -68,6 +68,8 @@ def lib():
     L.ef_sign_words.argtypes = [i64]
     L.ef_worker_step.restype = c_int
     L.ef_worker_step.argtypes = [vp, c_int, vp, i64, vp, vp, i64, f32, f32, f32, vp, vp, vp]
+    L.ef_worker_step_sgd.restype = c_int
+    L.ef_worker_step_sgd.argtypes = [vp, c_int, vp, i64, vp, i64, f32, f32, vp, vp, vp]
     L.ef_server_step.restype = c_int
     L.ef_server_step.argtypes = [vp, c_int, vp, vp, vp, f32, f32, vp, vp, vp]
     L.ef_apply.restype = c_int
@@ -299,4 +301,17 @@ def ef_apply_fused(plan, params, payload, eta, stream=None):
         raise TypeError("params must hold d floats")
     rc = lib().ef_apply_fused(plan._h, _ptr(params, torch.float32, "params"), _messages(payload, 1, plan, "payload"),
                               float(eta), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_worker_step_sgd(plan, grad, err, eta_prev, eta, packed_signs, scales, stream=None):
+    """Algorithm 3 worker (no momentum buffer): shapes as for ef_worker_step."""
+    n = 1 if grad.dim() == 1 else grad.shape[0]
+    gs, ss = _stride(grad, plan.d, "grad"), _stride(err, plan.d, "err")
+    if packed_signs.numel() != n * plan.W or scales.numel() != n * plan.B:
+        raise TypeError("packed_signs must hold n*W words and scales n*B floats")
+    rc = lib().ef_worker_step_sgd(plan._h, n, _ptr(grad, torch.float32, "grad"), gs,
+                                  _ptr(err, torch.float32, "err"), ss, float(eta_prev), float(eta),
+                                  _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                                  _ptr(scales, torch.float32, "scales"), _stream_ptr(stream))
     _check(rc)

@@ -256,7 +256,7 @@ int build_device(ef_plan *p)
         hipDeviceProp_t prop;
         EF_HIP(hipGetDeviceProperties(&prop, p->device));
         int occ_w = 0, occ_s = 0;
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_w, ef::k_worker_uniform, ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_w, ef::k_worker_uniform<true>, ef::THREADS, 0));
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server_uniform, ef::THREADS, 0));
         if (occ_w < 1) occ_w = 1;
         p->worker_grid = prop.multiProcessorCount * occ_w;
@@ -265,7 +265,7 @@ int build_device(ef_plan *p)
         // run one workgroup per tile (dispatched in grid order).  Larger limits were measured slower:
         // a block that fills most of the machine makes its first tiles wait for its last.
         int occ_d = 0;
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, ef::k_worker_uniform_direct, ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, ef::k_worker_uniform_direct<true>, ef::THREADS, 0));
         p->lim_persistent = (int32_t)((int64_t)p->worker_grid * ef::PIPE_DEPTH / 2);
         p->lim_direct = (int32_t)((int64_t)prop.multiProcessorCount * occ_d / 2);
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
@@ -484,8 +484,17 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
                    float *err, int64_t state_stride, float mu, float eta_prev, float eta,
                    uint64_t *packed_signs, float *scales, void *stream)
 {
-    if (!plan) return EF_ERR_NULL;
+    if (!plan || !mom) return EF_ERR_NULL;
     return worker_step_impl(plan, n_workers, grad, grad_stride, mom, err, state_stride, mu, eta_prev, eta,
+                            packed_signs, plan->L.W, scales, plan->L.B, stream);
+}
+
+int ef_worker_step_sgd(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *err,
+                       int64_t state_stride, float eta_prev, float eta, uint64_t *packed_signs, float *scales,
+                       void *stream)
+{
+    if (!plan) return EF_ERR_NULL;
+    return worker_step_impl(plan, n_workers, grad, grad_stride, nullptr, err, state_stride, 0.0f, eta_prev, eta,
                             packed_signs, plan->L.W, scales, plan->L.B, stream);
 }
 
@@ -496,7 +505,7 @@ int ef_worker_step_fused(const ef_plan *plan, int n_workers, const float *grad, 
                          float *err, int64_t state_stride, float mu, float eta_prev, float eta, void *payloads,
                          void *stream)
 {
-    if (!plan || !payloads) return EF_ERR_NULL;
+    if (!plan || !payloads || !mom) return EF_ERR_NULL;
     if (!aligned(payloads, 16)) return EF_ERR_ALIGN;
     const size_t pb = payload_bytes(plan);
     char *base = static_cast<char *>(payloads);
@@ -539,14 +548,16 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
                      float *err, int64_t state_stride, float mu, float eta_prev, float eta, uint64_t *packed_signs,
                      int64_t signs_stride, float *scales, int64_t scales_stride, void *stream)
 {
-    if (!plan || !grad || !mom || !err || !packed_signs || !scales) return EF_ERR_NULL;
+    // mom == nullptr selects Algorithm 3 (callers of the momentum entry points have checked theirs)
+    const bool has_mom = mom != nullptr;
+    if (!plan || !grad || !err || !packed_signs || !scales) return EF_ERR_NULL;
     if (n_workers < 1 || n_workers > plan->max_workers) return EF_ERR_ARG;
     if (!(mu >= 0.0f && mu < 1.0f) || !good_eta(eta_prev, eta)) return EF_ERR_ARG;
     if (grad_stride < plan->L.d || state_stride < plan->L.d || grad_stride % 4 || state_stride % 4)
         return EF_ERR_ARG;
     if ((const void *)grad == (const void *)mom || (const void *)grad == (const void *)err || mom == err)
         return EF_ERR_ARG;
-    if (!aligned(grad, 16) || !aligned(mom, 16) || !aligned(err, 16) || !aligned(scales, 4) ||
+    if (!aligned(grad, 16) || (has_mom && !aligned(mom, 16)) || !aligned(err, 16) || !aligned(scales, 4) ||
         !aligned(packed_signs, 8))
         return EF_ERR_ALIGN;
     ef::WorkerArgs A;
@@ -565,18 +576,29 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
     const CallScratch c = next_call(plan, 0, n_workers);
     const ef::Layout L = role_layout(plan, 0);
     if (plan->L.n_mixed) {
-        hipLaunchKernelGGL(ef::k_worker_mixed, dim3((unsigned)plan->L.n_mixed, (unsigned)n_workers),
-                           dim3(ef::THREADS), 0, s, L, c.X, A);
+        const dim3 grid((unsigned)plan->L.n_mixed, (unsigned)n_workers);
+        if (has_mom)
+            hipLaunchKernelGGL(ef::k_worker_mixed<true>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
+        else
+            hipLaunchKernelGGL(ef::k_worker_mixed<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
     if (plan->L.n_uniform && plan->persistent) {
         int64_t wgs = (int64_t)plan->L.n_uniform * n_workers;
         if (wgs > plan->worker_grid) wgs = plan->worker_grid;
-        hipLaunchKernelGGL(ef::k_worker_uniform, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A, n_workers);
+        if (has_mom)
+            hipLaunchKernelGGL(ef::k_worker_uniform<true>, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A,
+                               n_workers);
+        else
+            hipLaunchKernelGGL(ef::k_worker_uniform<false>, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A,
+                               n_workers);
         EF_HIP(hipGetLastError());
     } else if (plan->L.n_uniform) {
-        hipLaunchKernelGGL(ef::k_worker_uniform_direct, dim3((unsigned)plan->L.n_uniform, (unsigned)n_workers),
-                           dim3(ef::THREADS), 0, s, L, c.X, A);
+        const dim3 grid((unsigned)plan->L.n_uniform, (unsigned)n_workers);
+        if (has_mom)
+            hipLaunchKernelGGL(ef::k_worker_uniform_direct<true>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
+        else
+            hipLaunchKernelGGL(ef::k_worker_uniform_direct<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
     return launch_second_pass(plan, 0, c, n_workers, err, state_stride, scales, scales_stride, s);

@@ -720,12 +720,24 @@ __device__ __forceinline__ void build_segment_index(const Layout &L, int32_t til
 
 // --------------------------------------------------------- worker kernels ---
 
-// m <- mu*m + g and p = mu*m + g + r*e (Algorithm 4, "on each worker i"), one
-// rounding per operation, left to right.  m is overwritten with the new
-// momentum, e with p.
+// The worker's corrected gradient, one rounding per operation, left to right.
+// MOM (Algorithm 4): m <- mu*m + g and p = mu*m + g + r*e; m is overwritten
+// with the new momentum, e with p.  !MOM (Algorithm 3, no momentum buffer):
+// p = g + r*e; m is not touched.
+template <bool MOM>
 __device__ __forceinline__ void worker_values(const float4 (&g)[SUBROWS], float4 (&m)[SUBROWS], float4 (&e)[SUBROWS],
                                               float mu, float r)
 {
+    if (!MOM) {
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) {
+            e[k].x = g[k].x + r * e[k].x;
+            e[k].y = g[k].y + r * e[k].y;
+            e[k].z = g[k].z + r * e[k].z;
+            e[k].w = g[k].w + r * e[k].w;
+        }
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         m[k].x = mu * m[k].x + g[k].x;
@@ -741,6 +753,7 @@ __device__ __forceinline__ void worker_values(const float4 (&g)[SUBROWS], float4
 
 // Mixed tiles of all workers, one workgroup per (tile, worker).  Runs before
 // the uniform-tile kernel of the same call.
+template <bool MOM>
 __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, WorkerArgs A)
 {
     __shared__ TileShared S;
@@ -749,14 +762,14 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
     const int n_valid = tile_valid(L, tile);
     const int64_t tile_start = (int64_t)tile * TILE;
     const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
-    float *m = A.mom + (int64_t)worker * A.state_stride + tile_start;
+    float *m = MOM ? A.mom + (int64_t)worker * A.state_stride + tile_start : nullptr;
     float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
     float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
     load_tile(g, gv, n_valid);
-    load_tile(m, mv, n_valid);
+    if (MOM) load_tile(m, mv, n_valid);
     load_tile(e, pv, n_valid);
-    worker_values(gv, mv, pv, A.mu, A.r);
-    store_tile(m, mv, n_valid);
+    worker_values<MOM>(gv, mv, pv, A.mu, A.r);
+    if (MOM) store_tile(m, mv, n_valid);
     Posted P;
     float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
     compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker, S, P);
@@ -873,6 +886,7 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
     }
 }
 
+template <bool MOM>
 struct WorkerProducer {
     WorkerArgs A;
     float4 gv[SUBROWS], mv[SUBROWS], ev[SUBROWS];
@@ -887,23 +901,24 @@ struct WorkerProducer {
     {
         const int64_t tile_start = (int64_t)tile * TILE;
         load_tile(A.grad + (int64_t)idx * A.grad_stride + tile_start, gv, TILE);
-        load_tile(A.mom + (int64_t)idx * A.state_stride + tile_start, mv, TILE);
+        if (MOM) load_tile(A.mom + (int64_t)idx * A.state_stride + tile_start, mv, TILE);
         load_tile(A.err + (int64_t)idx * A.state_stride + tile_start, ev, TILE);
     }
     __device__ __forceinline__ void produce(const Layout &, int idx, int32_t tile, float4 (&p)[SUBROWS])
     {
-        worker_values(gv, mv, ev, A.mu, A.r);
-        store_tile(A.mom + (int64_t)idx * A.state_stride + (int64_t)tile * TILE, mv, TILE);
+        worker_values<MOM>(gv, mv, ev, A.mu, A.r);
+        if (MOM) store_tile(A.mom + (int64_t)idx * A.state_stride + (int64_t)tile * TILE, mv, TILE);
 #pragma unroll
         for (int k = 0; k < SUBROWS; ++k) p[k] = ev[k];
     }
 };
 
+template <bool MOM>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
 {
     __shared__ TileShared S;
-    WorkerProducer prod;
+    WorkerProducer<MOM> prod;
     prod.A = A;
     persistent_uniform(L, X, prod, n_workers, S);
 }
@@ -912,6 +927,7 @@ void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
 // steps without the pipeline; the workgroup waits in place for its block's
 // scale.  Relies on workgroups being dispatched in grid order (fuse_limit keeps
 // a block's tiles well inside what is resident at once) and on spin_limit.
+template <bool MOM>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(6, 8)))
 void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
 {
@@ -921,16 +937,16 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
     constexpr int n_valid = TILE;
     const int64_t tile_start = (int64_t)tile * TILE;
     const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
-    float *m = A.mom + (int64_t)worker * A.state_stride + tile_start;
+    float *m = MOM ? A.mom + (int64_t)worker * A.state_stride + tile_start : nullptr;
     float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
     Posted P;
     announce_uniform(L, tile, X, worker, P);       // the counter's answer returns under the loads
     float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
     load_tile(g, gv, n_valid);
-    load_tile(m, mv, n_valid);
+    if (MOM) load_tile(m, mv, n_valid);
     load_tile(e, pv, n_valid);
-    worker_values(gv, mv, pv, A.mu, A.r);
-    store_tile(m, mv, n_valid);
+    worker_values<MOM>(gv, mv, pv, A.mu, A.r);
+    if (MOM) store_tile(m, mv, n_valid);
     float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
     const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker,
                                       S, P);
@@ -950,7 +966,7 @@ __device__ __forceinline__ float mean_of(float acc, float Mf, float Minv)
 
 constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight together
 
-// Server (Algorithm 4, "on server") on the tiles that lie inside one block:
+// Server part of Algorithm 4 on the tiles that lie inside one block:
 // decode and add the M payloads in worker order, divide by M, add the rescaled
 // server residual, compress.  One workgroup per tile; it waits in the kernel
 // for its block's scale.  The sign words of SERVER_CHUNK workers are loaded
