@@ -30,15 +30,16 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE, scaled by a torch add kernel of known size run
 # in the same process): see profiles/ef_step_flat_2p28.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43303450389}
+MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43316029609}
 
 
-def algorithmic_bytes(d, B, M):
+def algorithmic_bytes(d, B, M, variant="sgdm"):
     """Bytes the method itself must move per element of d (fp32 state read
     once and written once, sign bits, scales)."""
-    worker = M * (20.0 * d + d / 8.0 + 4.0 * B)             # g,m,e in; m,e out; signs; scales
+    state = 12.0 if variant == "sgd" else 20.0              # g,e in, e out (+ m in, m out with momentum)
+    worker = M * (state * d + d / 8.0 + 4.0 * B)            # + signs, scales
     server = 8.0 * d + (M + 1) * d / 8.0 + 4.0 * B * (M + 1)
-    apply_ = 8.0 * d + d / 8.0 + 4.0 * B
+    apply_ = (16.0 if variant == "wd" else 8.0) * d + d / 8.0 + 4.0 * B   # x (+ decay momentum) in and out
     return worker, server, apply_
 
 
@@ -74,6 +75,10 @@ def main():
     ap.add_argument("--fuse-limit", type=int, default=-1, help="override the plan's one-pass block limit")
     ap.add_argument("--spin-limit", type=int, default=-1, help="override the plan's wait budget")
     ap.add_argument("--persistent", type=int, default=-1, help="1/0: force the persistent worker kernel on/off")
+    ap.add_argument("--variant", default="sgdm", choices=["sgdm", "sgd", "fused", "wd"],
+                    help="sgdm: Algorithm 4 (the default, the metric's configuration); sgd: Algorithm 3 worker "
+                         "without a momentum buffer; fused: one message per worker (Section 4.2); wd: parameter "
+                         "update with weight decay (Appendix A)")
     ap.add_argument("--calib", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB elementwise kernel (known size) for counter calibration")
     args = ap.parse_args()
@@ -111,6 +116,13 @@ def main():
     wc = torch.zeros((M, B), dtype=torch.float32, device=dev)
     ss = torch.zeros(W, dtype=torch.int64, device=dev)
     sc = torch.zeros(B, dtype=torch.float32, device=dev)
+    variant = args.variant
+    if variant == "fused":
+        pb = ef.ef_payload_bytes(plan)
+        wmsg = torch.zeros((M, pb), dtype=torch.uint8, device=dev)
+        smsg = torch.zeros(pb, dtype=torch.uint8, device=dev)
+    if variant == "wd":
+        decay_mom = torch.zeros(d, dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
 
     stream = torch.cuda.current_stream()
@@ -120,13 +132,26 @@ def main():
         g = grads[state["t"] % n_sets]
         if ev:
             ev[0].record(stream)
-        ef.ef_worker_step(plan, g, mom, err, w.mu, state["eta_prev"], w.eta, ws, wc)
+        if variant == "fused":
+            ef.ef_worker_step_fused(plan, g, mom, err, w.mu, state["eta_prev"], w.eta, wmsg)
+        elif variant == "sgd":
+            ef.ef_worker_step_sgd(plan, g, err, state["eta_prev"], w.eta, ws, wc)
+        else:
+            ef.ef_worker_step(plan, g, mom, err, w.mu, state["eta_prev"], w.eta, ws, wc)
         if ev:
             ev[1].record(stream)
-        ef.ef_server_step(plan, M, ws, wc, te, state["eta_prev"], w.eta, ss, sc)
+        if variant == "fused":
+            ef.ef_server_step_fused(plan, M, wmsg, te, state["eta_prev"], w.eta, smsg)
+        else:
+            ef.ef_server_step(plan, M, ws, wc, te, state["eta_prev"], w.eta, ss, sc)
         if ev:
             ev[2].record(stream)
-        ef.ef_apply(plan, x, ss, sc, w.eta)
+        if variant == "fused":
+            ef.ef_apply_fused(plan, x, smsg, w.eta)
+        elif variant == "wd":
+            ef.ef_apply_wd(plan, x, decay_mom, ss, sc, w.eta, w.mu, 5e-4)
+        else:
+            ef.ef_apply(plan, x, ss, sc, w.eta)
         if ev:
             ev[3].record(stream)
         state["eta_prev"] = w.eta
@@ -146,7 +171,8 @@ def main():
         step()
         if k == 0:
             torch.cuda.synchronize()
-            first_payload = (ws.cpu().numpy().view(np.uint64).copy(), ss.cpu().numpy().view(np.uint64).copy())
+            if variant in ("sgdm", "wd"):
+                first_payload = (ws.cpu().numpy().view(np.uint64).copy(), ss.cpu().numpy().view(np.uint64).copy())
     torch.cuda.synchronize()
 
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
@@ -168,7 +194,7 @@ def main():
     t_worker = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     t_server = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     t_apply = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
-    bw, bs, ba = algorithmic_bytes(d, B, M)
+    bw, bs, ba = algorithmic_bytes(d, B, M, variant)
     step_bytes = bw + bs + ba
     achieved = bw / (t_worker * 1e-3) / 1e9
 
@@ -186,18 +212,18 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": dict(w.describe(), grad_sets_in_hbm=n_sets, elements_counted="(M+1)*d per step",
+        "config": dict(w.describe(), variant=variant, grad_sets_in_hbm=n_sets, elements_counted="(M+1)*d per step",
                        d_per_step_Gelem_s=round(d / (ms_per_step * 1e-3) / 1e9, 3)),
         "roofline": {
             "bound": "hbm",
-            "kernel": ("ef::k_worker_uniform (persistent)" if plan.persistent else "ef::k_worker_uniform_direct") +
+            "kernel": ("ef::k_worker_uniform<true> (persistent)" if plan.persistent else "ef::k_worker_uniform_direct<true>") +
                       ", all M workers in one launch; timed as the whole ef_worker_step call (its mixed-tile and "
                       "list kernels included)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if variant == "sgdm" else None,
             "algorithmic_bytes_per_launch": bw,
             "ms_per_launch": round(t_worker, 4),
         },
@@ -209,7 +235,7 @@ def main():
                                "server_parked_tiles": fb_server[0], "server_late_blocks": fb_server[1]},
     }
 
-    if not args.no_cpu:
+    if not args.no_cpu and variant in ("sgdm", "wd"):
         # bounded sample: a prefix of blocks sized for roughly 10-30 s of single-thread work
         avg_block = d / B
         n_blocks = args.cpu_blocks or int(max(1, min(B, round(2.4e7 / avg_block))))

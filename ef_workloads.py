@@ -199,12 +199,19 @@ def transformer(layers=24):
                     dist=("student_t3", 1e-3))
 
 
+def one_block(log2_d=28, M=8, steps=10):
+    """The non-block compressor of Eq. (1) as a layout: B = 1, one scale for the whole vector."""
+    d = 1 << log2_d
+    return Workload("one_block_2p%d" % log2_d, 6, [d], M=M, steps=steps, dist=("normal", 1.0))
+
+
 WORKLOADS = {
     "resnet20_like": resnet20,
     "resnet50_like": resnet50,
     "flat_2p28": flat,
     "skewed_blocks": skewed,
     "transformer_like": transformer,
+    "one_block_2p28": one_block,
 }
 
 
