@@ -34,9 +34,11 @@
 //   * a partial is never negative, so its sign bit carries a tag that flips on
 //     every call that uses the scratch set; one 64-bit store publishes value
 //     and tag together;
-//   * an arrival counter per block tells the workgroup that arrives last;
-//     it gathers the partials (re-reading those whose tag is still old),
-//     writes the scale and posts (tag, scale) in the block's "ready" word;
+//   * the workgroup that takes the block's last whole tile gathers the
+//     partials (re-reading those whose tag is still old: tiles are handed out
+//     in ascending order, so the others are at most a tile-time behind),
+//     writes the scale and posts (call number, scale) in the block's "ready"
+//     word -- no counter, hence no read-modify-write on a shared address;
 //   * the others look at the ready word when they come to write the tile.
 // Mixed tiles never wait: their open segments, like all tiles of blocks larger
 // than fuse_limit and any tile whose (bounded) wait ran out, get p parked in
@@ -58,11 +60,22 @@ constexpr int DEFER_WGS = 64;   // workgroups that serve the run-time lists of t
 #ifndef EF_PIPE_DEPTH
 #define EF_PIPE_DEPTH 3
 #endif
-#ifndef EF_TICKET_TILES
-#define EF_TICKET_TILES 1
+#ifndef EF_TICKET_TILES_WORKER
+#define EF_TICKET_TILES_WORKER 1
+#endif
+#ifndef EF_TICKET_TILES_SGD
+#define EF_TICKET_TILES_SGD 2
+#endif
+#ifndef EF_TICKET_TILES_SERVER
+#define EF_TICKET_TILES_SERVER 2
 #endif
 constexpr int PIPE_DEPTH = EF_PIPE_DEPTH;     // tiles a persistent workgroup keeps in registers while their scales form
-constexpr int TICKET_TILES = EF_TICKET_TILES; // consecutive tiles handed out per ticket
+// Consecutive tiles handed out per ticket of a persistent kernel.  One counter
+// serves about 84 tickets per microsecond, so a kernel whose tile takes less
+// than 12 ns of HBM time chip-wide needs more than one tile per ticket.
+constexpr int TICKET_TILES_WORKER = EF_TICKET_TILES_WORKER;   // Algorithm 4 worker: 80 KiB of traffic per tile
+constexpr int TICKET_TILES_SGD = EF_TICKET_TILES_SGD;         // Algorithm 3 worker: 48 KiB per tile
+constexpr int TICKET_TILES_SERVER = EF_TICKET_TILES_SERVER;   // server: 32 KiB + sign words per tile
 constexpr unsigned long long TAG_BIT = 1ull << 63;
 constexpr int MAX_PER_THREAD = 6;                        // partial words a thread gathers
 constexpr int FUSE_LIMIT_MAX = MAX_PER_THREAD * THREADS; // tiles of the largest one-pass block
@@ -84,8 +97,7 @@ struct Layout {
 // Scratch of one call.  A "set" is one worker, or the server.
 struct Scratch {
     unsigned long long *part;   // [nsets][2*ntiles] tagged fp64 partial sums of open segments
-    unsigned int *cnt;          // [nsets][B] arrivals per one-pass block; zeroed again by the call's last kernel
-    unsigned long long *ready;  // [nsets][B] (epoch << 32) | scale bits, posted by the last arriver
+    unsigned long long *ready;  // [nsets][B] (epoch << 32) | scale bits, posted by the block's gatherer
     unsigned int *defer_cnt;    // entries in defer_list for this call
     unsigned long long *defer_list;  // parked segments: (set << 33) | (tile << 1) | slot
     unsigned int *fin_cnt;      // entries in fin_list for this call
@@ -289,10 +301,6 @@ __device__ __forceinline__ unsigned long long *set_part(const Scratch &X, const 
 {
     return X.part + (int64_t)set * 2 * L.ntiles;
 }
-__device__ __forceinline__ unsigned int *set_cnt(const Scratch &X, const Layout &L, int set)
-{
-    return X.cnt + (int64_t)set * L.B;
-}
 __device__ __forceinline__ unsigned long long *set_ready(const Scratch &X, const Layout &L, int set)
 {
     return X.ready + (int64_t)set * L.B;
@@ -328,7 +336,7 @@ __device__ __forceinline__ bool has_uniform_tile(const BlockSpan &s)
     return s.n - ((s.bs % TILE) != 0 ? 1 : 0) - ((s.be % TILE) != 0 ? 1 : 0) >= 1;
 }
 
-// One-pass blocks: their arrivals are counted and their scale is posted.
+// One-pass blocks: their scale is formed and posted inside the first kernels.
 __device__ __forceinline__ bool is_counted(const Layout &L, const BlockSpan &s)
 {
     return s.n >= 2 && s.n <= L.fuse_limit && has_uniform_tile(s);
@@ -342,26 +350,22 @@ __device__ __forceinline__ int64_t part_index(int64_t t, const BlockSpan &s)
     return 2 * t + ((t == s.t0 && (s.bs % TILE) != 0) ? 1 : 0);
 }
 
-// What a tile has posted and may have to follow up on: for each of its (at most
-// two) open segments of counted blocks, the block, its tile count and -- in
-// thread 0 only -- the arrival count the block had before this tile.
-struct Posted {
-    int b[2];
-    int n[2];
-    unsigned prev[2];
-};
-
-__device__ __forceinline__ void clear_posted(Posted &P)
+// The block's last whole tile: the workgroup that takes it forms the scale.
+__device__ __forceinline__ int64_t gatherer_tile(const BlockSpan &s)
 {
-    P.b[0] = P.b[1] = -1;
-    P.n[0] = P.n[1] = 0;
-    P.prev[0] = P.prev[1] = 0;
+    return s.t0 + s.n - 1 - ((s.be % TILE) != 0 ? 1 : 0);
 }
 
-// Post the partial sum of an open segment of block b and, for a counted block,
-// count the arrival.  which: 0 = the tile's first (or only) segment, 1 = its
-// last segment.  Never waits, not even for the counter's answer: that is looked
-// at in resolve_posted, after other work has been issued.
+// What a uniform tile has to follow up on after posting its partial: the block
+// whose scale it must form (it is that block's last whole tile), or -1.
+struct Posted {
+    int gather;
+};
+
+__device__ __forceinline__ void clear_posted(Posted &P) { P.gather = -1; }
+
+// Post the partial sum of an open segment.  which: 0 = the tile's first (or
+// only) segment, 1 = its last segment.  Never waits.
 __device__ __forceinline__ void store_partial(double partial, int which, int32_t tile, const Layout &L,
                                               const Scratch &X, int set)
 {
@@ -371,28 +375,6 @@ __device__ __forceinline__ void store_partial(double partial, int which, int32_t
         __hip_atomic_store(set_part(X, L, set) + 2 * (int64_t)tile + which, w, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     }
-}
-
-// Count this tile's arrival at block b if b is a counted block.  The count may
-// run ahead of the partials: whoever reads the partials checks their tags, so a
-// tile may announce itself before it has even loaded its data (which takes the
-// counter's round trip off the critical path).  Never waits for the answer.
-__device__ __forceinline__ void announce_arrival(int which, int64_t b, const Layout &L, const Scratch &X, int set,
-                                                 Posted &P)
-{
-    const BlockSpan sp = block_span(L, b);
-    const bool counted = is_counted(L, sp);
-    P.b[which] = counted ? (int)b : -1;
-    P.n[which] = sp.n;
-    if (threadIdx.x == 0 && counted)
-        P.prev[which] = __hip_atomic_fetch_add(set_cnt(X, L, set) + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ void post_partial(double partial, int which, int32_t tile, int64_t b, const Layout &L,
-                                             const Scratch &X, int set, Posted &P)
-{
-    store_partial(partial, which, tile, L, X, set);
-    announce_arrival(which, b, L, X, set, P);
 }
 
 // Sum of block b's partials once the kernel that posted them has finished.
@@ -452,10 +434,10 @@ __device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const S
     return true;
 }
 
-// The workgroup that arrived last at counted block b forms the scale from the
-// partials (waiting, bounded, for those still in flight), writes it out and
-// posts it for the block's other tiles.  Called by every thread of that
-// workgroup.  Does not depend on the progress of any other workgroup.
+// The workgroup that holds the last whole tile of counted block b forms the
+// scale from the partials (waiting, bounded, for those still in flight: every
+// other tile of the block was handed out earlier), writes it out and posts it
+// for the block's other tiles.  Called by every thread of that workgroup.
 __device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const Scratch &X, int set,
                                              float *scales_out, TileShared &S)
 {
@@ -474,21 +456,12 @@ __device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const S
     }
 }
 
-// Follow up on what a tile posted: where this workgroup was the last to arrive
-// at a block, finish that block.  Called by every thread of the workgroup.
+// Follow up on what a uniform tile posted: if it is its block's last whole
+// tile, finish that block.  Called by every thread of the workgroup.
 __device__ __forceinline__ void resolve_posted(const Posted &P, const Layout &L, const Scratch &X, int set,
                                                float *scales_out, TileShared &S)
 {
-    if (P.b[0] < 0 && P.b[1] < 0) return;
-    if (threadIdx.x == 0) {
-        S.flag[0] = (P.b[0] >= 0 && P.prev[0] + 1u == (unsigned)P.n[0]) ? 1 : 0;
-        S.flag[1] = (P.b[1] >= 0 && P.prev[1] + 1u == (unsigned)P.n[1]) ? 1 : 0;
-    }
-    __syncthreads();
-    const bool last0 = S.flag[0] != 0, last1 = S.flag[1] != 0;
-    __syncthreads();
-    if (last0) finish_block(P.b[0], L, X, set, scales_out, S);
-    if (last1) finish_block(P.b[1], L, X, set, scales_out, S);
+    if (P.gather >= 0) finish_block(P.gather, L, X, set, scales_out, S);
 }
 
 // Thread 0's early look at the ready word of block b (b < 0: none).
@@ -500,7 +473,7 @@ __device__ __forceinline__ unsigned long long peek_ready(int b, const Layout &L,
     return w;
 }
 
-// Wait (bounded) until the last arriver has posted block b's scale of this call.
+// Wait (bounded) until the block's gatherer has posted block b's scale of this call.
 // `peeked` is thread 0's earlier look at the word (see peek_ready).  Called by
 // every thread of the workgroup; same answer to all of them.
 __device__ __forceinline__ bool wait_ready(int64_t b, unsigned long long peeked, const Layout &L, const Scratch &X,
@@ -545,11 +518,10 @@ __device__ __forceinline__ void defer_segment(int32_t tile, int which, const Scr
 // e_{t+1} = p_t - Delta_t of Algorithm 4.)
 __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
                                                uint64_t *signs, float *scales_out, float *err_tile,
-                                               const Scratch &X, int set, TileShared &S, Posted &P)
+                                               const Scratch &X, int set, TileShared &S)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
-    clear_posted(P);
     store_signs(p, n_valid, signs, tile_start, L.W);
 
     const int nseg = lb - fb + 1;
@@ -605,8 +577,8 @@ __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layou
     __syncthreads();
     const int head_end = head_open ? (int)min(L.offs[fb + 1] - tile_start, (int64_t)n_valid) : 0;
     const int tail_begin = tail_open ? (int)(L.offs[lb] - tile_start) : TILE;
-    if (head_open) post_partial(S.open_sum[0], 0, tile, fb, L, X, set, P);
-    if (tail_open) post_partial(S.open_sum[1], 1, tile, lb, L, X, set, P);
+    if (head_open) store_partial(S.open_sum[0], 0, tile, L, X, set);
+    if (tail_open) store_partial(S.open_sum[1], 1, tile, L, X, set);
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         const int lb0 = local_base(k);
@@ -630,33 +602,22 @@ __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layou
 //   UNI_DONE    the block is this tile alone: scale and residual written;
 //   UNI_PARKED  block larger than fuse_limit: partial posted, p parked for the
 //               second-pass kernels;
-//   UNI_PENDING partial posted and arrival counted (P): p stays with the caller
-//               until the block's scale is posted.
+//   UNI_PENDING partial posted: p stays with the caller until the block's
+//               scale is posted; P says whether this tile must form it.
 enum { UNI_DONE = 0, UNI_PARKED = 1, UNI_PENDING = 2 };
 
-// The caller has announced the tile beforehand (announce_uniform), P is its
-// record.
-__device__ __forceinline__ void announce_uniform(const Layout &L, int32_t tile, const Scratch &X, int set, Posted &P)
+__device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
+                                                uint64_t *signs, float *scales_out, float *err_tile,
+                                                const Scratch &X, int set, TileShared &S, Posted &P)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t b = L.tile_fb[tile];
     clear_posted(P);
-    const int64_t bs = L.offs[b], be = L.offs[b + 1];
-    if (bs >= tile_start && be <= tile_start + TILE) return;     // the block is this tile alone
-    announce_arrival(0, b, L, X, set, P);
-}
-
-__device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
-                                                uint64_t *signs, float *scales_out, float *err_tile,
-                                                const Scratch &X, int set, TileShared &S, const Posted &P)
-{
-    const int64_t tile_start = (int64_t)tile * TILE;
-    const int32_t b = L.tile_fb[tile];
     store_signs(p, n_valid, signs, tile_start, L.W);
     const double total = block_sum(abs_sum(p, n_valid), S.red);
-    const int64_t bs = L.offs[b], be = L.offs[b + 1];
-    if (bs >= tile_start && be <= tile_start + TILE) {
-        const float s = (float)(total / (double)(be - bs));
+    const BlockSpan sp = block_span(L, b);
+    if (sp.bs >= tile_start && sp.be <= tile_start + TILE) {
+        const float s = (float)(total / (double)(sp.be - sp.bs));
         if (threadIdx.x == 0) scales_out[b] = s;
 #pragma unroll
         for (int k = 0; k < SUBROWS; ++k) residual4(p[k], s);
@@ -664,10 +625,11 @@ __device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layo
         return UNI_DONE;
     }
     store_partial(total, 0, tile, L, X, set);
-    if (P.b[0] < 0) {
+    if (!is_counted(L, sp)) {
         store_tile(err_tile, p, n_valid);
         return UNI_PARKED;
     }
+    if ((int64_t)tile == gatherer_tile(sp)) P.gather = b;
     return UNI_PENDING;
 }
 
@@ -770,10 +732,8 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
     load_tile(e, pv, n_valid);
     worker_values<MOM>(gv, mv, pv, A.mu, A.r);
     if (MOM) store_tile(m, mv, n_valid);
-    Posted P;
     float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
-    compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker, S, P);
-    resolve_posted(P, L, X, worker, scales_out, S);
+    compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker, S);
 }
 
 // Uniform tiles as a persistent kernel (worker and server alike).
@@ -783,7 +743,7 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
 // registers (their blocks' scales have had PIPE_DEPTH tile-times to form, so
 // the wait is normally over before it starts); then compute the new tile, post
 // its partial sum and keep it in turn.  Tiles are handed out through one ticket
-// counter (TICKET_TILES per ticket), so at any moment the resident workgroups
+// counter (TT per ticket), so at any moment the resident workgroups
 // work on one compact, advancing window of the fp32 streams (best DRAM page
 // locality, no dependence on dispatch order).  A workgroup never waits for a
 // block of which it still holds an unposted tile, so a wait only ever depends
@@ -802,11 +762,11 @@ struct HeldTile {
     int b;                      // < 0: slot empty
 };
 
-template <class Producer>
+template <int TT, class Producer>
 __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratch &X, Producer &prod, int n_part,
                                                    TileShared &S)
 {
-    const unsigned nchunks = (unsigned)((L.n_uniform + TICKET_TILES - 1) / TICKET_TILES);
+    const unsigned nchunks = (unsigned)((L.n_uniform + TT - 1) / TT);
     const unsigned total = nchunks * (unsigned)n_part;
 
     HeldTile held[PIPE_DEPTH];
@@ -829,8 +789,8 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
             __syncthreads();
             if (t >= total) break;
             cur_idx = (int)(t / nchunks);
-            cur = (int)(t % nchunks) * TICKET_TILES;
-            cur_end = min(cur + TICKET_TILES, L.n_uniform);
+            cur = (int)(t % nchunks) * TT;
+            cur_end = min(cur + TT, L.n_uniform);
             if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);   // answer is read at the next chunk
         }
         const int32_t tile = L.uniform_tiles[cur++];
@@ -844,8 +804,6 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
         HeldTile &old = held[0];
         const unsigned long long peeked = peek_ready(old.b, L, X, X.set_base + (old.b >= 0 ? old.idx : 0));
         resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
-        // The new tile announces itself now, so that the counter's answer returns under the loads.
-        announce_uniform(L, tile, X, set, posted);
         if (old.b >= 0) {
             // The block of the oldest tile cannot complete while this workgroup sits on a tile of
             // the same block that is not posted yet (the new one, or the rest of its ticket): then
@@ -872,7 +830,7 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
             for (int k = 0; k < SUBROWS; ++k) slot.p[k] = pv[k];
             slot.tile = tile;
             slot.idx = idx;
-            slot.b = posted.b[0];
+            slot.b = L.tile_fb[tile];
         }
     }
 
@@ -920,7 +878,7 @@ void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
     __shared__ TileShared S;
     WorkerProducer<MOM> prod;
     prod.A = A;
-    persistent_uniform(L, X, prod, n_workers, S);
+    persistent_uniform<MOM ? TICKET_TILES_WORKER : TICKET_TILES_SGD>(L, X, prod, n_workers, S);
 }
 
 // Uniform tiles of all workers, one workgroup per (tile, worker): the same
@@ -940,7 +898,6 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
     float *m = MOM ? A.mom + (int64_t)worker * A.state_stride + tile_start : nullptr;
     float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
     Posted P;
-    announce_uniform(L, tile, X, worker, P);       // the counter's answer returns under the loads
     float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
     load_tile(g, gv, n_valid);
     if (MOM) load_tile(m, mv, n_valid);
@@ -951,7 +908,7 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
     const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker,
                                       S, P);
     resolve_posted(P, L, X, worker, scales_out, S);
-    if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, P.b[0], 0ull, e, L, X, worker, S);
+    if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, L.tile_fb[tile], 0ull, e, L, X, worker, S);
 }
 
 // -------------------------------------------------------- server kernels ---
@@ -962,6 +919,20 @@ void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
 __device__ __forceinline__ float mean_of(float acc, float Mf, float Minv)
 {
     return Minv != 0.0f ? acc * Minv : acc / Mf;
+}
+
+// acc[c] += (+s if bit sh+c of `word` is set, else -s), c = 0..3: what one
+// worker's payload stands for in this lane's four elements.  The sign bit of
+// the addend is sign(s) XOR NOT(bit), built without a compare: `flip` is ~0 for
+// s >= 0 and 0 for s < 0, so word ^ flip has a 1 exactly where the addend is
+// negative; that bit is extracted, shifted to the top and or-ed onto `mag`, the
+// magnitude bits of s (one bit-field extract, one shift-or, one add per
+// element).  Negation by sign bit is exact for every s.
+__device__ __forceinline__ void add_decoded4(float (&acc)[4], uint32_t word, unsigned sh, uint32_t flip, uint32_t mag)
+{
+    const uint32_t x = word ^ flip;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = acc[c] + __uint_as_float((((x >> (sh + c)) & 1u) << 31) | mag);
 }
 
 constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight together
@@ -981,7 +952,6 @@ __global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X,
     const int32_t b = L.tile_fb[tile];
     float *te = A.err + tile_start;
     Posted P;
-    announce_uniform(L, tile, X, set, P);        // the counter's answer returns under the loads
     float4 tv[SUBROWS];
     load_tile(te, tv, n_valid);
 
@@ -1010,12 +980,10 @@ __global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X,
 #pragma unroll
         for (int u = 0; u < SERVER_CHUNK; ++u) {
             if (i0 + u < A.M) {
+                const uint32_t sb = __float_as_uint(sc[u]);
+                const uint32_t flip = ~(uint32_t)((int32_t)sb >> 31), mag = sb & 0x7fffffffu;
 #pragma unroll
-                for (int k = 0; k < SUBROWS; ++k) {
-                    const unsigned nibble = (word[u][k] >> sh) & 0xFu;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[k][c] = acc[k][c] + signed_scale(sc[u], (nibble >> c) & 1u);
-                }
+                for (int k = 0; k < SUBROWS; ++k) add_decoded4(acc[k], word[u][k], sh, flip, mag);
             }
         }
     }
@@ -1030,7 +998,7 @@ __global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X,
     }
     const int kind = compress_uniform(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
     resolve_posted(P, L, X, set, A.scales, S);
-    if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, P.b[0], 0ull, te, L, X, set, S);
+    if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, b, 0ull, te, L, X, set, S);
 }
 
 // The same server work as a persistent kernel (see persistent_uniform).  The
@@ -1067,7 +1035,7 @@ struct ServerProducer {
     __device__ __forceinline__ void produce(const Layout &L, int, int32_t tile, float4 (&p)[SUBROWS])
     {
         const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
-        float acc[SUBROWS][4];
+            float acc[SUBROWS][4];
 #pragma unroll
         for (int k = 0; k < SUBROWS; ++k)
 #pragma unroll
@@ -1077,12 +1045,10 @@ struct ServerProducer {
 #pragma unroll
             for (int u = 0; u < SERVER_CHUNK; ++u) {
                 if (i0 + u < A.M) {
+                    const uint32_t sb = __float_as_uint(sc[u]);
+                    const uint32_t flip = ~(uint32_t)((int32_t)sb >> 31), mag = sb & 0x7fffffffu;
 #pragma unroll
-                    for (int k = 0; k < SUBROWS; ++k) {
-                        const unsigned nibble = (word[u][k] >> sh) & 0xFu;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) acc[k][c] = acc[k][c] + signed_scale(sc[u], (nibble >> c) & 1u);
-                    }
+                    for (int k = 0; k < SUBROWS; ++k) add_decoded4(acc[k], word[u][k], sh, flip, mag);
                 }
             }
         }
@@ -1103,7 +1069,7 @@ void k_server_uniform_persistent(Layout L, Scratch X, ServerArgs A)
     __shared__ TileShared S;
     ServerProducer prod;
     prod.A = A;
-    persistent_uniform(L, X, prod, 1, S);
+    persistent_uniform<TICKET_TILES_SERVER>(L, X, prod, 1, S);
 }
 
 // Server on the mixed tiles (several blocks meet, or the ragged last tile): a
@@ -1167,9 +1133,7 @@ __global__ __launch_bounds__(THREADS) void k_server_mixed(Layout L, Scratch X, S
         p[k].z = mean_of(acc[k][2], Mf, Minv) + r * tv[k].z;
         p[k].w = mean_of(acc[k][3], Mf, Minv) + r * tv[k].w;
     }
-    Posted P;
-    compress_mixed(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
-    resolve_posted(P, L, X, set, A.scales, S);
+    compress_mixed(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S);
 }
 
 // ---------------------------------------------------- second-pass kernels ---
@@ -1248,10 +1212,9 @@ __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X
 // per-layout list (open segments of mixed tiles, tiles of blocks larger than
 // fuse_limit: workgroups 0 .. n_items*nsets-1) and the tiles whose wait ran out
 // (list filled at run time: the last DEFER_WGS workgroups).  Also clears the
-// list counters the next call will use and this call's arrival counters.
+// list counters the next call will use.
 __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X, const uint32_t *items,
-                                                             int n_items, int nsets, const int32_t *counted_blocks,
-                                                             int n_counted, unsigned int *next_defer_cnt,
+                                                             int n_items, int nsets, unsigned int *next_defer_cnt,
                                                              unsigned int *next_fin_cnt, unsigned int *next_ticket,
                                                              float *err, int64_t err_stride, const float *scales,
                                                              int64_t scales_stride)
@@ -1261,10 +1224,6 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X
         *next_fin_cnt = 0u;
         *next_ticket = 0u;
     }
-    // every arrival of this call has been counted by now: back to zero for the next call
-    for (int64_t i = (int64_t)blockIdx.x * THREADS + threadIdx.x; i < (int64_t)n_counted * nsets;
-         i += (int64_t)gridDim.x * THREADS)
-        set_cnt(X, L, X.set_base + (int)(i / n_counted))[counted_blocks[i % n_counted]] = 0u;
     const int n_static = n_items * nsets;
     if ((int)blockIdx.x < n_static) {
         const uint32_t it = items[blockIdx.x % n_items];
