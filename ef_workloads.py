@@ -205,6 +205,12 @@ def one_block(log2_d=28, M=8, steps=10):
     return Workload("one_block_2p%d" % log2_d, 6, [d], M=M, steps=steps, dist=("normal", 1.0))
 
 
+def odd_tiles(M=8, steps=10):
+    """257 blocks of 255 x 4096 elements: every block holds an odd number of
+    whole tiles, so fixed-size groups of tiles would straddle block ends."""
+    return Workload("odd_tiles_257x255", 7, [255 * 4096] * 257, M=M, steps=steps, dist=("normal", 1.0))
+
+
 WORKLOADS = {
     "resnet20_like": resnet20,
     "resnet50_like": resnet50,
@@ -212,6 +218,7 @@ WORKLOADS = {
     "skewed_blocks": skewed,
     "transformer_like": transformer,
     "one_block_2p28": one_block,
+    "odd_tiles": odd_tiles,
 }
 
 

@@ -98,14 +98,15 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
 int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit in force */
 
 /*
- * Which kernel ef_worker_step and ef_server_step run over the tiles that lie inside one block:
+ * Which kernel the worker calls run over the tiles that lie inside one block:
  * on = 1 a persistent kernel whose workgroups take tiles from a ticket counter
  * and keep several tiles in registers while their scales form; on = 0 one
  * workgroup per tile that waits in place for its block's scale; on < 0 the
  * choice plan creation made for this layout (persistent when every workgroup
  * gets at least 64 tiles and the largest one-pass block is small next to the
- * distance between two tickets of one workgroup).  Same results either way.
- * Synchronises the device.
+ * distance between two tickets of one workgroup).  ef_worker_step_sgd uses the
+ * persistent kernel only after on = 1.  The server always runs one workgroup
+ * per tile.  Same results either way.  Synchronises the device.
  */
 int ef_plan_set_persistent(ef_plan *plan, int on);
 int ef_plan_is_persistent(const ef_plan *plan);

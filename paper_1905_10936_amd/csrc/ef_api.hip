@@ -30,7 +30,7 @@ struct ef_plan {
         uint32_t *d_static;         // [2*ntiles] capacity
         int32_t *d_late;            // [min(B, 2*ntiles)] capacity
     } role[2];
-    int32_t lim_persistent, lim_direct, lim_server, lim_server_persistent;   // automatic limits
+    int32_t lim_persistent, lim_direct, lim_server;   // automatic limits
     int32_t user_fuse_limit;        // >= 0: set through ef_plan_tune, overrides the automatic limits
     // device allocations owned by the plan
     int64_t *d_offs;
@@ -42,8 +42,7 @@ struct ef_plan {
     int worker_grid;                // workgroups of the persistent worker kernel
     int persistent;                 // worker: 1 pipelined persistent kernel, 0 one workgroup per tile
     int persistent_auto;            // what plan creation chose for this layout
-    int server_grid;                // workgroups of the persistent server kernel
-    int server_persistent, server_persistent_auto;
+    int persistent_forced;          // 1 after ef_plan_set_persistent(plan, 1): also for the momentum-free worker
     unsigned long long *d_defer_list;
     unsigned long long *d_fin_list;
     int32_t *d_mixed, *d_uniform;   // tile lists
@@ -158,7 +157,7 @@ int refresh_limits(ef_plan *p)
         p->role[0].fuse_limit = p->role[1].fuse_limit = clamp(p->user_fuse_limit);
     } else {
         p->role[0].fuse_limit = clamp(p->persistent ? p->lim_persistent : p->lim_direct);
-        p->role[1].fuse_limit = clamp(p->server_persistent ? p->lim_server_persistent : p->lim_server);
+        p->role[1].fuse_limit = clamp(p->lim_server);
     }
     p->L.fuse_limit = p->role[0].fuse_limit;
     for (auto &r : p->role) {
@@ -256,11 +255,6 @@ int build_device(ef_plan *p)
         p->lim_persistent = (int32_t)((int64_t)p->worker_grid * ef::PIPE_DEPTH / 2);
         p->lim_direct = (int32_t)((int64_t)prop.multiProcessorCount * occ_d / 2);
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
-        int occ_sp = 0;
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_sp, ef::k_server_uniform_persistent, ef::THREADS, 0));
-        if (occ_sp < 1) occ_sp = 1;
-        p->server_grid = prop.multiProcessorCount * occ_sp;
-        p->lim_server_persistent = (int32_t)((int64_t)p->server_grid * ef::PIPE_DEPTH / 2);
     }
     p->user_fuse_limit = -1;
     // The persistent kernel pays off when every workgroup gets many tiles and a block's tiles
@@ -273,15 +267,11 @@ int build_device(ef_plan *p)
             if (n >= 2 && n <= p->lim_persistent && n > largest) largest = n;
         }
         const int64_t tiles_per_wg = (int64_t)p->L.n_uniform * p->max_workers / (p->worker_grid > 0 ? p->worker_grid : 1);
-        p->persistent_auto = (tiles_per_wg >= 64 && largest <= (int64_t)p->worker_grid * ef::TICKET_TILES_WORKER) ? 1 : 0;
-        // The server moves 2.5 times fewer bytes per tile and does more arithmetic on them: it
-        // gains more from the higher occupancy of one workgroup per tile than from the pipeline
-        // (measured 0.65 ms against 0.90 ms on 2^28 elements, 8 workers), so that is its default.
-        p->server_persistent_auto = 0;
+        p->persistent_auto = (tiles_per_wg >= 64 && largest <= (int64_t)p->worker_grid) ? 1 : 0;
     }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
-    p->server_persistent = p->server_persistent_auto;
+    p->persistent_forced = 0;
     p->calls = 0;
     p->epoch = 0;
     p->last_defer_cnt = p->last_fin_cnt = nullptr;
@@ -453,7 +443,7 @@ int ef_plan_set_persistent(ef_plan *plan, int on)
     if (!plan) return EF_ERR_NULL;
     EF_HIP(hipDeviceSynchronize());
     plan->persistent = on < 0 ? plan->persistent_auto : (on ? 1 : 0);
-    plan->server_persistent = on < 0 ? plan->server_persistent_auto : (on ? 1 : 0);
+    plan->persistent_forced = on > 0 ? 1 : 0;
     return refresh_limits(plan);
 }
 
@@ -564,7 +554,10 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
             hipLaunchKernelGGL(ef::k_worker_mixed<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
-    if (plan->L.n_uniform && plan->persistent) {
+    // The momentum-free worker moves 48 KiB per tile instead of 80: one ticket per tile would
+    // make the ticket counter (about 84 tickets per microsecond) its bottleneck, so it runs one
+    // workgroup per tile unless the persistent kernel was asked for explicitly.
+    if (plan->L.n_uniform && plan->persistent && (has_mom || plan->persistent_forced)) {
         int64_t wgs = (int64_t)plan->L.n_uniform * n_workers;
         if (wgs > plan->worker_grid) wgs = plan->worker_grid;
         if (has_mom)
@@ -617,11 +610,7 @@ int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, i
                            plan->max_workers);
         EF_HIP(hipGetLastError());
     }
-    if (L.n_uniform && plan->server_persistent) {
-        const int wgs = L.n_uniform < plan->server_grid ? L.n_uniform : plan->server_grid;
-        hipLaunchKernelGGL(ef::k_server_uniform_persistent, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A);
-        EF_HIP(hipGetLastError());
-    } else if (L.n_uniform) {
+    if (L.n_uniform) {
         hipLaunchKernelGGL(ef::k_server_uniform, dim3((unsigned)L.n_uniform), dim3(ef::THREADS), 0, s, L, c.X, A,
                            plan->max_workers);
         EF_HIP(hipGetLastError());

@@ -60,22 +60,7 @@ constexpr int DEFER_WGS = 64;   // workgroups that serve the run-time lists of t
 #ifndef EF_PIPE_DEPTH
 #define EF_PIPE_DEPTH 3
 #endif
-#ifndef EF_TICKET_TILES_WORKER
-#define EF_TICKET_TILES_WORKER 1
-#endif
-#ifndef EF_TICKET_TILES_SGD
-#define EF_TICKET_TILES_SGD 2
-#endif
-#ifndef EF_TICKET_TILES_SERVER
-#define EF_TICKET_TILES_SERVER 2
-#endif
 constexpr int PIPE_DEPTH = EF_PIPE_DEPTH;     // tiles a persistent workgroup keeps in registers while their scales form
-// Consecutive tiles handed out per ticket of a persistent kernel.  One counter
-// serves about 84 tickets per microsecond, so a kernel whose tile takes less
-// than 12 ns of HBM time chip-wide needs more than one tile per ticket.
-constexpr int TICKET_TILES_WORKER = EF_TICKET_TILES_WORKER;   // Algorithm 4 worker: 80 KiB of traffic per tile
-constexpr int TICKET_TILES_SGD = EF_TICKET_TILES_SGD;         // Algorithm 3 worker: 48 KiB per tile
-constexpr int TICKET_TILES_SERVER = EF_TICKET_TILES_SERVER;   // server: 32 KiB + sign words per tile
 constexpr unsigned long long TAG_BIT = 1ull << 63;
 constexpr int MAX_PER_THREAD = 6;                        // partial words a thread gathers
 constexpr int FUSE_LIMIT_MAX = MAX_PER_THREAD * THREADS; // tiles of the largest one-pass block
@@ -736,14 +721,14 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
     compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker, S);
 }
 
-// Uniform tiles as a persistent kernel (worker and server alike).
+// Uniform tiles of the worker as a persistent kernel.
 //
 // Every workgroup loops: take the next tile, issue its loads, and while they
 // are in flight write out the oldest of the PIPE_DEPTH tiles it holds in
 // registers (their blocks' scales have had PIPE_DEPTH tile-times to form, so
 // the wait is normally over before it starts); then compute the new tile, post
-// its partial sum and keep it in turn.  Tiles are handed out through one ticket
-// counter (TT per ticket), so at any moment the resident workgroups
+// its partial sum and keep it in turn.  Tiles are handed out one by one through
+// a ticket counter, so at any moment the resident workgroups
 // work on one compact, advancing window of the fp32 streams (best DRAM page
 // locality, no dependence on dispatch order).  A workgroup never waits for a
 // block of which it still holds an unposted tile, so a wait only ever depends
@@ -762,12 +747,12 @@ struct HeldTile {
     int b;                      // < 0: slot empty
 };
 
-template <int TT, class Producer>
+template <class Producer>
 __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratch &X, Producer &prod, int n_part,
                                                    TileShared &S)
 {
-    const unsigned nchunks = (unsigned)((L.n_uniform + TT - 1) / TT);
-    const unsigned total = nchunks * (unsigned)n_part;
+    const unsigned per_part = (unsigned)L.n_uniform;
+    const unsigned total = per_part * (unsigned)n_part;
 
     HeldTile held[PIPE_DEPTH];
 #pragma unroll
@@ -778,23 +763,17 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
 
     unsigned tk_next = 0;       // thread 0: the ticket taken ahead of need
     if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);
-    int cur = 0, cur_end = 0, cur_idx = 0;
 
     for (;;) {
         // ---- next tile
-        if (cur >= cur_end) {
-            if (threadIdx.x == 0) S.ticket = tk_next;
-            __syncthreads();
-            const unsigned t = (unsigned)__builtin_amdgcn_readfirstlane((int)S.ticket);
-            __syncthreads();
-            if (t >= total) break;
-            cur_idx = (int)(t / nchunks);
-            cur = (int)(t % nchunks) * TT;
-            cur_end = min(cur + TT, L.n_uniform);
-            if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);   // answer is read at the next chunk
-        }
-        const int32_t tile = L.uniform_tiles[cur++];
-        const int idx = cur_idx;
+        if (threadIdx.x == 0) S.ticket = tk_next;
+        __syncthreads();
+        const unsigned t = (unsigned)__builtin_amdgcn_readfirstlane((int)S.ticket);
+        __syncthreads();
+        if (t >= total) break;
+        if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);   // the answer is read at the next tile
+        const int idx = (int)(t / per_part);
+        const int32_t tile = L.uniform_tiles[t % per_part];
         const int set = X.set_base + idx;
 
         // ---- this tile's loads go out first
@@ -806,11 +785,9 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
         resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
         if (old.b >= 0) {
             // The block of the oldest tile cannot complete while this workgroup sits on a tile of
-            // the same block that is not posted yet (the new one, or the rest of its ticket): then
-            // do not wait, park p and leave the tile to the second pass.
-            bool may_wait = !(old.idx == idx && L.tile_fb[tile] == old.b);
-            for (int c = cur; c < cur_end; ++c)
-                may_wait = may_wait && !(old.idx == idx && L.tile_fb[L.uniform_tiles[c]] == old.b);
+            // the same block that is not posted yet (the new one): then do not wait, park p and
+            // leave the tile to the second pass.
+            const bool may_wait = !(old.idx == idx && L.tile_fb[tile] == old.b);
             finish_uniform(old.p, old.tile, TILE, old.b, peeked, prod.err_tile(old.idx, old.tile), L, X,
                            X.set_base + old.idx, S, may_wait);
         }
@@ -878,7 +855,7 @@ void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
     __shared__ TileShared S;
     WorkerProducer<MOM> prod;
     prod.A = A;
-    persistent_uniform<MOM ? TICKET_TILES_WORKER : TICKET_TILES_SGD>(L, X, prod, n_workers, S);
+    persistent_uniform(L, X, prod, n_workers, S);
 }
 
 // Uniform tiles of all workers, one workgroup per (tile, worker): the same
@@ -999,77 +976,6 @@ __global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X,
     const int kind = compress_uniform(p, L, tile, n_valid, A.signs, A.scales, te, X, set, S, P);
     resolve_posted(P, L, X, set, A.scales, S);
     if (kind == UNI_PENDING) finish_uniform(p, tile, n_valid, b, 0ull, te, L, X, set, S);
-}
-
-// The same server work as a persistent kernel (see persistent_uniform).  The
-// sign words of the first SERVER_CHUNK workers travel with the tile's loads;
-// further workers, if any, are fetched while the tile is produced.
-struct ServerProducer {
-    ServerArgs A;
-    float4 tv[SUBROWS];
-    uint32_t word[SERVER_CHUNK][SUBROWS];
-    float sc[SERVER_CHUNK];
-
-    __device__ __forceinline__ uint64_t *signs(const Layout &, int) const { return A.signs; }
-    __device__ __forceinline__ float *scales(const Layout &, int) const { return A.scales; }
-    __device__ __forceinline__ float *err_tile(int, int32_t tile) const { return A.err + (int64_t)tile * TILE; }
-    __device__ __forceinline__ void load_chunk(const Layout &L, int32_t tile, int i0)
-    {
-        const uint32_t *s32 = reinterpret_cast<const uint32_t *>(A.signs_in);
-        const int64_t in_hw = 2 * A.in_signs_stride;
-        const int64_t hw0 = ((int64_t)tile * TILE + local_base(0)) >> 5;
-        const int32_t b = L.tile_fb[tile];
-#pragma unroll
-        for (int u = 0; u < SERVER_CHUNK; ++u) {
-            const int i = min(i0 + u, A.M - 1);          // past M: a valid address whose value is not used
-            sc[u] = A.scales_in[(int64_t)i * A.in_scales_stride + b];
-#pragma unroll
-            for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * in_hw + hw0 + 8 * k];
-        }
-    }
-    __device__ __forceinline__ void issue(const Layout &L, int, int32_t tile)
-    {
-        load_tile(A.err + (int64_t)tile * TILE, tv, TILE);
-        load_chunk(L, tile, 0);
-    }
-    __device__ __forceinline__ void produce(const Layout &L, int, int32_t tile, float4 (&p)[SUBROWS])
-    {
-        const unsigned sh = (unsigned)(lane_id() & 7) * 4u;
-            float acc[SUBROWS][4];
-#pragma unroll
-        for (int k = 0; k < SUBROWS; ++k)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[k][c] = 0.0f;
-        for (int i0 = 0; i0 < A.M; i0 += SERVER_CHUNK) {
-            if (i0 > 0) load_chunk(L, tile, i0);
-#pragma unroll
-            for (int u = 0; u < SERVER_CHUNK; ++u) {
-                if (i0 + u < A.M) {
-                    const uint32_t sb = __float_as_uint(sc[u]);
-                    const uint32_t flip = ~(uint32_t)((int32_t)sb >> 31), mag = sb & 0x7fffffffu;
-#pragma unroll
-                    for (int k = 0; k < SUBROWS; ++k) add_decoded4(acc[k], word[u][k], sh, flip, mag);
-                }
-            }
-        }
-        const float r = A.r, Mf = A.Mf, Minv = A.Minv;
-#pragma unroll
-        for (int k = 0; k < SUBROWS; ++k) {
-            p[k].x = mean_of(acc[k][0], Mf, Minv) + r * tv[k].x;
-            p[k].y = mean_of(acc[k][1], Mf, Minv) + r * tv[k].y;
-            p[k].z = mean_of(acc[k][2], Mf, Minv) + r * tv[k].z;
-            p[k].w = mean_of(acc[k][3], Mf, Minv) + r * tv[k].w;
-        }
-    }
-};
-
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 3)))
-void k_server_uniform_persistent(Layout L, Scratch X, ServerArgs A)
-{
-    __shared__ TileShared S;
-    ServerProducer prod;
-    prod.A = A;
-    persistent_uniform<TICKET_TILES_SERVER>(L, X, prod, 1, S);
 }
 
 // Server on the mixed tiles (several blocks meet, or the ragged last tile): a
