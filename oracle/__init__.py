@@ -59,6 +59,8 @@ def lib():
                                 ctypes.c_float]
         L.efo_apply_wd.argtypes = [_f32p, _f32p, _u64p, _f32p, ctypes.c_int64, _i64p, ctypes.c_int64,
                                    ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        L.efo_quality.argtypes = [_f32p, ctypes.c_int64, _i64p, ctypes.c_int64,
+                                  ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.efo_step.argtypes = [ctypes.c_int, _f32p, _f32p, _f32p, _f32p, _f32p, ctypes.c_int64,
                                _i64p, ctypes.c_int64, ctypes.c_float, ctypes.c_float,
                                ctypes.c_float, _u64p, _f32p, _u64p, _f32p]
@@ -204,6 +206,15 @@ def apply_wd(x, mt, signs, scales, offsets, eta, mu, lam):
     if mt.size != d or signs.size != sign_words(d) or scales.size != B:
         raise OracleError("sizes do not match block_offsets")
     _chk(lib().efo_apply_wd(_f(x), _f(mt), _u(signs), _f(scales), d, _i(offs), B, eta, mu, lam), "efo_apply_wd")
+
+
+def quality(v, offsets):
+    """(phi(v) of Proposition 1, delta(v) of the non-block compressor of Eq. (1))."""
+    v = _arr(v, np.float32, "v")
+    offs, B = _offs(offsets)
+    phi, delta = ctypes.c_double(), ctypes.c_double()
+    _chk(lib().efo_quality(_f(v), v.size, _i(offs), B, ctypes.byref(phi), ctypes.byref(delta)), "efo_quality")
+    return phi.value, delta.value
 
 
 def step(g, m, e, te, x, offsets, mu, eta_prev, eta):

@@ -11,6 +11,7 @@
  *   - worker / server / parameter update of one step  : Algorithm 4
  *     (Algorithm 3 is the mu = 0 case, Eq. (1) is the B = 1 case)
  *   - parameter update with weight decay outside compression : Appendix A
+ *   - phi(v) of Proposition 1 and delta of the non-block compressor : Section 3.2
  *   - one bit per coordinate for the sign in {-1, +1},
  *     one fp32 scale per block                        : Appendix A, Section 3.2
  *
@@ -37,7 +38,11 @@
  * is pinned to the Algorithm 4 worker at mu = 0 (the reduction Section 4.1
  * states) and to the brute force; the Appendix A update to efo_apply at
  * lambda = 0, to a float64 run of the decay-momentum recursion on dyadic values
- * (zero payload) and to the brute force.  Nothing is unpinned.
+ * (zero payload) and to the brute force.  efo_quality is pinned by the closed
+ * form the paper prints for the constant-magnitude example, by one-hot blocks
+ * (ratio 1/d_b exactly), by B = 1 (phi = delta) and by the approximation
+ * inequality of Definition 1 measured on the oracle's own compressor output.
+ * Nothing is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -321,6 +326,45 @@ int efo_apply_wd(float *x, float *mt, const uint64_t *signs, const float *scales
         }
     free(delta);
     return rc;
+}
+
+/* How well the compressors approximate v (Definition 1):
+ *   phi(v)   = min_b ||v_Gb||_1^2 / (d_b ||v_Gb||_2^2)   for C_B   (Proposition 1)
+ *   delta(v) = ||v||_1^2 / (d ||v||_2^2)                 for the non-block compressor, Eq. (1)
+ * in double, sums in ascending index order.  A block (or vector) of zeros is
+ * reproduced exactly by the compressor and counts as ratio 1.
+ */
+int efo_quality(const float *v, int64_t d, const int64_t *offs, int64_t B,
+                double *phi, double *delta)
+{
+    int64_t b, j;
+    double l1 = 0.0, l2 = 0.0, best = 1.0;
+    int rc = efo_check_offsets(offs, B, d);
+    if (rc)
+        return rc;
+    if (!v || !phi || !delta)
+        return EFO_BAD_ARG;
+    for (b = 0; b < B; ++b) {
+        double a1 = 0.0, a2 = 0.0;
+        for (j = offs[b]; j < offs[b + 1]; ++j) {
+            double a = fabs((double)v[j]);
+            a1 += a;
+            a2 += a * a;
+        }
+        if (a2 > 0.0) {
+            double ratio = a1 * a1 / ((double)(offs[b + 1] - offs[b]) * a2);
+            if (ratio < best)
+                best = ratio;
+        }
+    }
+    for (j = 0; j < d; ++j) {
+        double a = fabs((double)v[j]);
+        l1 += a;
+        l2 += a * a;
+    }
+    *phi = best;
+    *delta = l2 > 0.0 ? l1 * l1 / ((double)d * l2) : 1.0;
+    return EFO_OK;
 }
 
 /* One whole iteration for M workers that share x (they all pull the same

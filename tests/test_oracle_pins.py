@@ -429,6 +429,65 @@ def test_restart_from_snapshot_is_bit_identical():
         assert np.array_equal(a, b)
 
 
+# --------------------------------------------- phi(v) and delta (Section 3.2) ---
+
+@pytest.mark.parametrize("alpha,B,n", _const_mag_cases())
+def test_quality_constant_magnitude_example(alpha, B, n):
+    """Section 3.2 example: phi = 1 and delta = (1+a)(1-a^B) / (B (1-a)(1+a^B))."""
+    rng = np.random.default_rng(11)
+    c = np.array([alpha ** (B - 1 - b) for b in range(B)])
+    v = (np.repeat(c, n) * rng.choice([-1.0, 1.0], size=B * n)).astype(F)
+    phi, delta = oracle.quality(v, np.arange(B + 1) * n)
+    assert phi == pytest.approx(1.0, rel=1e-12)
+    assert delta == pytest.approx((1 + alpha) * (1 - alpha ** B) / (B * (1 - alpha) * (1 + alpha ** B)), rel=1e-9)
+
+
+def test_quality_one_hot_blocks_and_single_block():
+    """A block with one non-zero has ratio 1/d_b (the lower bound of Proposition 1
+    is attained); zero blocks are skipped; with B = 1, phi = delta."""
+    sizes = [5, 1, 40, 7, 3]
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    v = np.zeros(int(offs[-1]), F)
+    v[offs[0] + 2] = -3.0           # d_b = 5
+    v[offs[2] + 39] = 0.25          # d_b = 40: the minimum
+    v[offs[3]:offs[4]] = 2.0        # constant block: ratio 1
+    phi, delta = oracle.quality(v, offs)
+    assert phi == 1.0 / 40
+    l1, l2 = 3.0 + 0.25 + 14.0, 9.0 + 0.0625 + 28.0
+    assert delta == pytest.approx(l1 * l1 / (56 * l2), rel=1e-15)
+    phi1, delta1 = oracle.quality(v, [0, 56])
+    assert phi1 == delta1 == delta
+    assert oracle.quality(np.zeros(9, F), [0, 4, 9]) == (1.0, 1.0)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_quality_is_the_approximation_constant(seed):
+    """Definition 1 with Proposition 1: ||C_B(v) - v||^2 <= (1 - phi(v)) ||v||^2, with equality
+    when every block has the same ratio; per block the identity of the proof gives
+    ||C(v_b) - v_b||^2 = (1 - ratio_b) ||v_b||^2, so phi must equal the smallest measured ratio."""
+    rng = np.random.default_rng(seed)
+    sizes = rng.integers(1, 200, size=30)
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    v = (rng.standard_normal(int(offs[-1])) * np.repeat(10.0 ** rng.uniform(-2, 2, 30), sizes)).astype(F)
+    v[rng.random(v.size) < 0.3] = 0.0
+    phi, delta = oracle.quality(v, offs)
+    signs, scales = oracle.compress(v, offs)
+    cv = oracle.decode(signs, scales, offs).astype(np.float64)
+    v64 = v.astype(np.float64)
+    ratios = []
+    for b in range(30):
+        sl = slice(offs[b], offs[b + 1])
+        n2 = (v64[sl] ** 2).sum()
+        if n2 > 0:
+            ratios.append(1.0 - ((cv[sl] - v64[sl]) ** 2).sum() / n2)
+    assert phi == pytest.approx(min(ratios), rel=1e-5)
+    assert ((cv - v64) ** 2).sum() <= (1 - phi) * (v64 ** 2).sum() * (1 + 1e-6)
+    s1, c1 = oracle.compress(v, [0, v.size])
+    c1v = oracle.decode(s1, c1, [0, v.size]).astype(np.float64)
+    assert delta == pytest.approx(1.0 - ((c1v - v64) ** 2).sum() / (v64 ** 2).sum(), rel=1e-5)
+    assert phi >= 1.0 / sizes.max() and 0 < delta <= 1
+
+
 # ------------------------------------------- Algorithm 3 (no momentum) ---
 
 def test_sgd_worker_is_momentum_worker_at_mu_zero():
