@@ -240,6 +240,23 @@ int ef_server_step_fused(const ef_plan *plan, int M, const void *payloads, float
                          float eta_prev, float eta, void *out_payload, void *stream);
 int ef_apply_fused(const ef_plan *plan, float *params, const void *payload, float eta, void *stream);
 
+/*
+ * How well the compressors approximate each of n_vectors vectors (Section 3.2):
+ *     out[2i]   = phi(v_i)   = min_b ||v_Gb||_1^2 / (d_b ||v_Gb||_2^2)    (Proposition 1: C_B is
+ *                              phi(v)-approximate; blocks of zeros count as ratio 1)
+ *     out[2i+1] = delta(v_i) = ||v||_1^2 / (d ||v||_2^2)                  (the non-block compressor
+ *                              of Eq. (1); 1 for a vector of zeros)
+ * Sums are taken in fp64 in a fixed order, so repeated calls give the same bits.
+ *
+ *   v     in   float[n_vectors][stride], stride >= d and a multiple of 4
+ *   out   out  double[2 * n_vectors], device memory, 8-byte aligned
+ *   n_vectors in [1, max_workers]
+ * The first call on a plan allocates scratch (48 bytes per tile and vector) and synchronises;
+ * like the other calls it must be ordered on the device with every call that shares the plan.
+ */
+int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out,
+                          void *stream);
+
 /* Static text for an error code; for EF_ERR_HIP the text of the last HIP error
  * seen by this thread is appended.  The returned pointer stays valid until the
  * same thread calls ef_strerror again. */

@@ -25,7 +25,7 @@ EF_MAX_WORKERS = 64
 ABI_SYMBOLS = (
     "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
     "ef_sign_words", "ef_worker_step", "ef_worker_step_sgd", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
-    "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused",
+    "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused", "ef_compressor_quality",
 )
 
 
@@ -84,6 +84,8 @@ def lib():
     L.ef_server_step_fused.argtypes = [vp, c_int, vp, vp, f32, f32, vp, vp]
     L.ef_apply_fused.restype = c_int
     L.ef_apply_fused.argtypes = [vp, vp, vp, f32, vp]
+    L.ef_compressor_quality.restype = c_int
+    L.ef_compressor_quality.argtypes = [vp, c_int, vp, i64, vp, vp]
     L.ef_apply_wd.restype = c_int
     L.ef_apply_wd.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, vp]
     L.ef_strerror.restype = ctypes.c_char_p
@@ -314,4 +316,14 @@ def ef_worker_step_sgd(plan, grad, err, eta_prev, eta, packed_signs, scales, str
                                   _ptr(err, torch.float32, "err"), ss, float(eta_prev), float(eta),
                                   _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
                                   _ptr(scales, torch.float32, "scales"), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_compressor_quality(plan, v, out, stream=None):
+    """v: float32 [n][>=d] (or [d]); out: float64 [n][2] receives (phi, delta) per vector."""
+    n = 1 if v.dim() == 1 else v.shape[0]
+    if out.numel() != 2 * n:
+        raise TypeError("out must hold 2 doubles per vector")
+    rc = lib().ef_compressor_quality(plan._h, n, _ptr(v, torch.float32, "v"), _stride(v, plan.d, "v"),
+                                     _ptr(out, torch.float64, "out"), _stream_ptr(stream))
     _check(rc)

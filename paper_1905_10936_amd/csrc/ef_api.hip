@@ -46,6 +46,10 @@ struct ef_plan {
     unsigned long long *d_defer_list;
     unsigned long long *d_fin_list;
     int32_t *d_mixed, *d_uniform;   // tile lists
+    // compressor-quality diagnostics: allocated at the first ef_compressor_quality call
+    int32_t *d_cross;               // blocks that span several tiles
+    int32_t n_cross;
+    double *d_qtile, *d_qpart;      // [max_workers][ntiles][2], [max_workers][2*ntiles][2]
 };
 
 namespace {
@@ -100,6 +104,9 @@ void destroy_device(ef_plan *p)
     }
     if (p->d_mixed) (void)hipFree(p->d_mixed);
     if (p->d_uniform) (void)hipFree(p->d_uniform);
+    if (p->d_cross) (void)hipFree(p->d_cross);
+    if (p->d_qtile) (void)hipFree(p->d_qtile);
+    if (p->d_qpart) (void)hipFree(p->d_qpart);
 }
 
 int64_t tiles_of_block(const ef_plan *p, int64_t b)
@@ -389,6 +396,9 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
         r.fuse_limit = 0;
     }
     p->d_mixed = p->d_uniform = nullptr;
+    p->d_cross = nullptr;
+    p->n_cross = 0;
+    p->d_qtile = p->d_qpart = nullptr;
 
     rc = build_device(p);
     if (rc) {
@@ -657,6 +667,42 @@ int ef_apply_wd(const ef_plan *plan, float *params, float *decay_mom, const uint
     dim3 grid((unsigned)plan->L.ntiles, 1u);
     hipLaunchKernelGGL(ef::k_apply_wd, grid, dim3(ef::THREADS), 0, s, plan->L, params, decay_mom, packed_signs,
                        scales, eta, mu, lambda);
+    EF_HIP(hipGetLastError());
+    return EF_OK;
+}
+
+int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out, void *stream)
+{
+    if (!plan || !v || !out) return EF_ERR_NULL;
+    if (n_vectors < 1 || n_vectors > plan->max_workers) return EF_ERR_ARG;
+    if (stride < plan->L.d || stride % 4) return EF_ERR_ARG;
+    if (!aligned(v, 16) || !aligned(out, 8)) return EF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!plan->d_qtile) {       // first call on this plan: scratch and the list of crossing blocks
+        std::vector<int32_t> cross;
+        for (int64_t b = 0; b < plan->L.B; ++b)
+            if (tiles_of_block(plan, b) >= 2) cross.push_back((int32_t)b);
+        const size_t nt = (size_t)plan->L.ntiles, nv = (size_t)plan->max_workers;
+        EF_HIP(hipMalloc(&plan->d_cross, sizeof(int32_t) * (cross.size() + 1)));
+        if (!cross.empty())
+            EF_HIP(hipMemcpy(plan->d_cross, cross.data(), sizeof(int32_t) * cross.size(), hipMemcpyHostToDevice));
+        plan->n_cross = (int32_t)cross.size();
+        EF_HIP(hipMalloc(&plan->d_qpart, sizeof(double) * 4 * nt * nv));
+        EF_HIP(hipMalloc(&plan->d_qtile, sizeof(double) * 2 * nt * nv));
+    }
+    ef::QualityArgs Q;
+    Q.v = v;
+    Q.stride = stride;
+    Q.tile_sums = plan->d_qtile;
+    Q.part_sums = plan->d_qpart;
+    Q.out = out;
+    hipLaunchKernelGGL(ef::k_quality_init, dim3(1), dim3(ef::THREADS), 0, s, out, n_vectors);
+    EF_HIP(hipGetLastError());
+    hipLaunchKernelGGL(ef::k_quality_tiles, dim3((unsigned)plan->L.ntiles, (unsigned)n_vectors), dim3(ef::THREADS), 0,
+                       s, plan->L, Q);
+    EF_HIP(hipGetLastError());
+    hipLaunchKernelGGL(ef::k_quality_blocks, dim3((unsigned)plan->n_cross + 1u, (unsigned)n_vectors),
+                       dim3(ef::THREADS), 0, s, plan->L, Q, (const int32_t *)plan->d_cross, (int)plan->n_cross);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
