@@ -63,9 +63,9 @@ typedef struct ef_plan ef_plan; /* opaque */
 /*
  * Build the per-layout plan: a device copy of the partition, the tile -> block
  * table the kernels use to find which blocks a tile touches, and the scratch
- * memory of the cross-tile block reductions (fp64 partial sums and arrival
- * counters for max_workers workers and the server).  Blocks follow Section 3.2
- * ("each parameter tensor/matrix/vector as a block" is the usual choice).
+ * memory of the cross-tile block reductions (fp64 partial sums per tile and one
+ * hand-off word per block, for max_workers workers and the server).  Blocks
+ * follow Section 3.2 (one block per parameter tensor is the usual choice).
  *
  *   out                 HOST  receives the plan; caller releases it with ef_plan_destroy
  *   block_offsets_host  HOST  int64[B+1], copied; need not outlive the call
