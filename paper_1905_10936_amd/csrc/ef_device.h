@@ -924,7 +924,10 @@ constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight to
 // for its block's scale.  The sign words of SERVER_CHUNK workers are loaded
 // together (one 32-bit word per worker and sub-row holds this lane's 4 bits),
 // the block's M scales come through scalar loads.
-__global__ __launch_bounds__(THREADS) void k_server_uniform(Layout L, Scratch X, ServerArgs A, int set)
+// Six workgroups per CU (80 VGPRs): measured 0.58 ms against 0.63 ms at five and 0.73 ms at eight
+// (where a third of the tile spills) on 2^28 elements and 8 workers.
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(6, 8)))
+void k_server_uniform(Layout L, Scratch X, ServerArgs A, int set)
 {
     __shared__ TileShared S;
     const int32_t tile = L.uniform_tiles[blockIdx.x];
