@@ -67,7 +67,12 @@ def _sample_blocks(w, rng, n_random, max_elems):
     return sorted(out)
 
 
-def _run_sampled(w, steps, blocks, workers=None, check_props=True):
+def _run_sampled(w, steps, blocks, workers=None, check_props=True, variant="sgdm", etas=None):
+    """variant: "sgdm" Algorithm 4 through the unfused calls; "sgd" the momentum-free worker
+    (Algorithm 3); "fused" one message per worker (Section 4.2); "wd" the parameter update with
+    weight decay (Appendix A).  etas: stepsize per step (default: the workload's constant one)."""
+    assert variant in ("sgdm", "sgd", "fused", "wd")
+    assert not (check_props and (variant == "sgd" or etas))
     dev = torch.device("cuda")
     d, B, M = w.d, w.B, w.M
     W = (d + 63) // 64
@@ -88,9 +93,23 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True):
     ss = torch.zeros(W, dtype=torch.int64, device=dev)
     sc = torch.zeros(B, dtype=torch.float32, device=dev)
     bsel = torch.as_tensor(blocks, device=dev)
+    if variant == "fused":
+        pb, so = ef.ef_payload_bytes(plan), ef.ef_payload_scales_offset(plan)
+        wmsg = torch.zeros((M, pb), dtype=torch.uint8, device=dev)
+        smsg = torch.zeros(pb, dtype=torch.uint8, device=dev)
+        # the unfused arrays become views of the messages: sign words first, scales at the stated offset
+        ws = wmsg[:, :so].view(torch.int64)
+        wc = wmsg[:, so:so + 4 * B].view(torch.float32)
+        ss = smsg[:so].view(torch.int64)
+        sc = smsg[so:so + 4 * B].view(torch.float32)
+    if variant == "wd":
+        lam = 5e-4
+        mt = torch.zeros(d, dtype=torch.float32, device=dev)
+        x.copy_(torch.randn(d, generator=torch.Generator(device=dev).manual_seed(7), device=dev))
     eta_prev = 0.0
     loose = 0
     for t in range(steps):
+        eta = etas[t] if etas else w.eta
         print("[%s] step %d: generating gradients" % (w.name, t), flush=True)
         for i in range(M):
             w.grad(t, i, device=dev, out=g[i])
@@ -105,8 +124,13 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True):
                 mag += e[0].double().abs()
         ws.fill_(0x5555555555555555)
         wc.fill_(-7.0)
-        print("[%s] step %d: worker step on the GPU" % (w.name, t), flush=True)
-        ef.ef_worker_step(plan, g_rows, m_rows, e_rows, w.mu, eta_prev, w.eta, ws, wc)
+        print("[%s/%s] step %d: worker step on the GPU" % (w.name, variant, t), flush=True)
+        if variant == "sgd":
+            ef.ef_worker_step_sgd(plan, g_rows, e_rows, eta_prev, eta, ws, wc)
+        elif variant == "fused":
+            ef.ef_worker_step_fused(plan, g_rows, m_rows, e_rows, w.mu, eta_prev, eta, wmsg)
+        else:
+            ef.ef_worker_step(plan, g_rows, m_rows, e_rows, w.mu, eta_prev, eta, ws, wc)
         torch.cuda.synchronize()
         print("[%s] step %d: oracle on %d sampled elements x %d workers" % (w.name, t, int(sub_offs[-1]), len(workers)),
               flush=True)
@@ -115,8 +139,11 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True):
         m_out, e_out = _cat(m, offs, blocks), _cat(e, offs, blocks)
         for i in workers:
             mi, ei = np.ascontiguousarray(m_s[i]), np.ascontiguousarray(e_s[i])
-            s_ref, c_ref = oracle.worker_step(np.ascontiguousarray(g_s[i]), mi, ei, sub_offs, F(w.mu), F(eta_prev),
-                                              F(w.eta))
+            if variant == "sgd":
+                s_ref, c_ref = oracle.worker_step_sgd(np.ascontiguousarray(g_s[i]), ei, sub_offs, F(eta_prev), F(eta))
+            else:
+                s_ref, c_ref = oracle.worker_step(np.ascontiguousarray(g_s[i]), mi, ei, sub_offs, F(w.mu),
+                                                  F(eta_prev), F(eta))
             tag = "%s step %d worker %d" % (w.name, t, i)
             ref_bits = np.unpackbits(s_ref.view(np.uint8), bitorder="little")[:wbits.shape[-1]]
             assert np.array_equal(wbits[i], ref_bits), "%s: %d sign bits differ" % (tag, (wbits[i] != ref_bits).sum())
@@ -157,11 +184,14 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True):
         ss.fill_(0x5555555555555555)
         sc.fill_(-7.0)
         print("[%s] step %d: server step" % (w.name, t), flush=True)
-        ef.ef_server_step(plan, M, ws, wc, te, eta_prev, w.eta, ss, sc)
+        if variant == "fused":
+            ef.ef_server_step_fused(plan, M, wmsg, te, eta_prev, eta, smsg)
+        else:
+            ef.ef_server_step(plan, M, ws, wc, te, eta_prev, eta, ss, sc)
         torch.cuda.synchronize()
         te_ref = np.ascontiguousarray(te_s)
         ss_ref, sc_ref = oracle.server_step(_pack(wbits), np.ascontiguousarray(wc_s), te_ref, sub_offs, F(eta_prev),
-                                            F(w.eta))
+                                            F(eta))
         sbits = _bits(ss, offs, blocks)
         ref_bits = np.unpackbits(ss_ref.view(np.uint8), bitorder="little")[:sbits.shape[-1]]
         tag = "%s step %d server" % (w.name, t)
@@ -171,12 +201,23 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True):
         loose += int((~same).sum())
         check_vector(_cat(te, offs, blocks), te_ref, sc_ref, same, sub_offs, tag + " residual")
         # ---- apply
-        ef.ef_apply(plan, x, ss, sc, w.eta)
-        torch.cuda.synchronize()
         x_ref = np.ascontiguousarray(x_s)
-        oracle.apply(x_ref, _pack(sbits), np.ascontiguousarray(sc_s), sub_offs, F(w.eta))
+        if variant == "wd":
+            mt_ref = np.ascontiguousarray(_cat(mt, offs, blocks))
+            ef.ef_apply_wd(plan, x, mt, ss, sc, eta, w.mu, lam)
+            oracle.apply_wd(x_ref, mt_ref, _pack(sbits), np.ascontiguousarray(sc_s), sub_offs, F(eta), F(w.mu), F(lam))
+            torch.cuda.synchronize()
+            assert np.array_equal(_cat(mt, offs, blocks).view(np.uint32), mt_ref.view(np.uint32)), \
+                tag + ": decay momentum differs"
+        else:
+            if variant == "fused":
+                ef.ef_apply_fused(plan, x, smsg, eta)
+            else:
+                ef.ef_apply(plan, x, ss, sc, eta)
+            torch.cuda.synchronize()
+            oracle.apply(x_ref, _pack(sbits), np.ascontiguousarray(sc_s), sub_offs, F(eta))
         assert np.array_equal(_cat(x, offs, blocks).view(np.uint32), x_ref.view(np.uint32)), tag + ": apply differs"
-        eta_prev = w.eta
+        eta_prev = eta
     return loose
 
 
@@ -216,3 +257,21 @@ def test_transformer_like_sampled():
     w = wl.get("transformer_like")
     blocks = [0] + list(range(1, 13)) + [w.B - 1]
     _run_sampled(w, w.steps, blocks, workers=[0, 15], check_props=False)
+
+
+def test_flat_2p28_momentum_free_worker_sampled():
+    """The benchmark workload through the Algorithm 3 worker, with a stepsize that rises and falls."""
+    w = wl.get("flat_2p28")
+    _run_sampled(w, 3, [0, 128, 255], check_props=False, variant="sgd", etas=[0.05, 0.2, 0.1])
+
+
+def test_flat_2p28_fused_messages_sampled():
+    """The benchmark workload with one contiguous message per worker (Section 4.2)."""
+    w = wl.get("flat_2p28")
+    _run_sampled(w, 2, [0, 77, 255], check_props=False, variant="fused")
+
+
+def test_resnet50_like_weight_decay_full():
+    """Configuration 2 with the Appendix A parameter update, all blocks, random initial parameters."""
+    w = wl.get("resnet50_like")
+    _run_sampled(w, 2, list(range(w.B)), check_props=False, variant="wd")
