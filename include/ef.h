@@ -103,8 +103,7 @@ int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit 
  * and keep several tiles in registers while their scales form; on = 0 one
  * workgroup per tile that waits in place for its block's scale; on < 0 the
  * choice plan creation made for this layout (persistent when every workgroup
- * gets at least 64 tiles and the largest one-pass block is small next to the
- * distance between two tickets of one workgroup).  ef_worker_step_sgd uses the
+ * gets at least 64 tiles).  ef_worker_step_sgd uses the
  * persistent kernel only after on = 1.  The server always runs one workgroup
  * per tile.  Same results either way.  Synchronises the device.
  */

@@ -264,17 +264,11 @@ int build_device(ef_plan *p)
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
     }
     p->user_fuse_limit = -1;
-    // The persistent kernel pays off when every workgroup gets many tiles and a block's tiles
-    // are fewer than the distance between two tickets of one workgroup (else it keeps running
-    // into tiles of a block it still holds and parks them); otherwise one workgroup per tile.
+    // The persistent kernel pays off when every workgroup gets many tiles; otherwise one
+    // workgroup per tile (nothing to pipeline, and no ticket traffic).
     {
-        int64_t largest = 0;
-        for (int64_t b = 0; b < B; ++b) {
-            const int64_t n = tiles_of_block(p, b);
-            if (n >= 2 && n <= p->lim_persistent && n > largest) largest = n;
-        }
         const int64_t tiles_per_wg = (int64_t)p->L.n_uniform * p->max_workers / (p->worker_grid > 0 ? p->worker_grid : 1);
-        p->persistent_auto = (tiles_per_wg >= 64 && largest <= (int64_t)p->worker_grid) ? 1 : 0;
+        p->persistent_auto = tiles_per_wg >= 64 ? 1 : 0;
     }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
