@@ -736,8 +736,8 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, W
 // one block had more than (resident workgroups x PIPE_DEPTH) uniform tiles,
 // which fuse_limit rules out, and it is bounded by spin_limit in any case.
 //
-// What is streamed differs per role and comes from a producer:
-//   issue(L, idx, tile)        start the tile's loads (idx: worker, or 0 for the server)
+// What is streamed comes from a producer (Algorithm 4 or Algorithm 3 worker):
+//   issue(L, idx, tile)        start the tile's loads (idx: which worker)
 //   produce(L, idx, tile, p)   the corrected values p of Algorithm 4 (and the role's other stores)
 //   signs(L, idx), scales(L, idx), err_tile(idx, tile)   where that participant's outputs go
 struct HeldTile {
