@@ -238,7 +238,7 @@ def main():
     if not args.no_cpu and variant in ("sgdm", "wd"):
         # bounded sample: a prefix of blocks sized for roughly 10-30 s of single-thread work
         avg_block = d / B
-        n_blocks = args.cpu_blocks or int(max(1, min(B, round(2.4e7 / avg_block))))
+        n_blocks = args.cpu_blocks or int(max(1, min(B, round(5e7 / avg_block))))
         cpu_steps = 2
         g0 = grads[0]
         cpu_val, ds, first = cpu_baseline(w, g0, n_blocks, cpu_steps)

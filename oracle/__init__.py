@@ -16,6 +16,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ef_oracle.c")
 _LIB = os.path.join(_HERE, "libef_oracle.so")
+# tests/test_pins_catch_mistakes.py points this at a copy of the source with a planted mistake
+# to show that the pins notice it; nothing else sets it.
+if os.environ.get("EF_ORACLE_SRC"):
+    _SRC = os.path.abspath(os.environ["EF_ORACLE_SRC"])
+    _LIB = os.path.splitext(_SRC)[0] + ".so"
 
 # -ffp-contract=off: every fp32 operation of Algorithm 4 rounds once, no FMA.
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c99", "-shared",
