@@ -211,6 +211,16 @@ def odd_tiles(M=8, steps=10):
     return Workload("odd_tiles_257x255", 7, [255 * 4096] * 257, M=M, steps=steps, dist=("normal", 1.0))
 
 
+def beyond_2p31(M=2, steps=2):
+    """d a little above 2^31 elements, so that element, word and tile arithmetic must be 64-bit:
+    2047 blocks of 2^20, one block that straddles element 2^31 and ends off the tile grid, 3000
+    tiny blocks behind it, one medium block at the end (ragged last tile)."""
+    rng = np.random.Generator(np.random.Philox(BASE_SEED + 8))
+    tiny = np.clip(np.floor(np.exp(rng.uniform(0.0, np.log(65.0), 3000))), 1, 64).astype(np.int64)
+    sizes = [1 << 20] * 2047 + [(1 << 20) + 3 * 4096 + 5] + [int(v) for v in tiny] + [10_000]
+    return Workload("beyond_2p31", 8, sizes, M=M, steps=steps, dist=("normal", 1.0))
+
+
 WORKLOADS = {
     "resnet20_like": resnet20,
     "resnet50_like": resnet50,
@@ -219,6 +229,7 @@ WORKLOADS = {
     "transformer_like": transformer,
     "one_block_2p28": one_block,
     "odd_tiles": odd_tiles,
+    "beyond_2p31": beyond_2p31,
 }
 
 

@@ -275,3 +275,13 @@ def test_resnet50_like_weight_decay_full():
     """Configuration 2 with the Appendix A parameter update, all blocks, random initial parameters."""
     w = wl.get("resnet50_like")
     _run_sampled(w, 2, list(range(w.B)), check_props=False, variant="wd")
+
+
+def test_beyond_2p31_elements_sampled():
+    """More than 2^31 elements per worker (8.6 GB per fp32 row): every index past 2^31 has to be
+    formed in 64 bits.  Sampled: the first block, the block that straddles element 2^31, the tiny
+    blocks and the ragged last block behind it."""
+    w = wl.get("beyond_2p31")
+    assert w.d > (1 << 31)
+    blocks = [0, 2046, 2047] + list(range(2048, w.B))
+    _run_sampled(w, w.steps, blocks, check_props=False)
