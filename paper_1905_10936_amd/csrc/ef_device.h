@@ -1309,10 +1309,15 @@ __global__ __launch_bounds__(THREADS) void k_quality_tiles(Layout L, QualityArgs
         }
         return;
     }
-    // several blocks meet in this tile: segmented sums through LDS
+    // several blocks meet in this tile: segmented sums through LDS; the smallest ratio of the
+    // segments that close here is collected in LDS first, one global atomic per tile
+    __shared__ unsigned long long tile_min;
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) *reinterpret_cast<float4 *>(&S.val[local_base(k)]) = a[k];
-    if (threadIdx.x == 0) S.n_long = 0;
+    if (threadIdx.x == 0) {
+        S.n_long = 0;
+        tile_min = (unsigned long long)__double_as_longlong(1.0);
+    }
     __syncthreads();
     const int nseg = lb - fb + 1;
     const bool head_open = L.offs[fb] < tile_start;
@@ -1337,7 +1342,7 @@ __global__ __launch_bounds__(THREADS) void k_quality_tiles(Layout L, QualityArgs
             seg_sum[sg == 0 ? 0 : 1][0] = s1;
             seg_sum[sg == 0 ? 0 : 1][1] = s2;
         } else {
-            ratio_min(phi_bits, s1, s2, be - bs);
+            ratio_min(&tile_min, s1, s2, be - bs);
         }
     }
     __syncthreads();
@@ -1362,12 +1367,13 @@ __global__ __launch_bounds__(THREADS) void k_quality_tiles(Layout L, QualityArgs
                 seg_sum[sg == 0 ? 0 : 1][0] = s1;
                 seg_sum[sg == 0 ? 0 : 1][1] = s2;
             } else {
-                ratio_min(phi_bits, s1, s2, be - bs);
+                ratio_min(&tile_min, s1, s2, be - bs);
             }
         }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
+        if (tile_min != (unsigned long long)__double_as_longlong(1.0)) atomicMin(phi_bits, tile_min);
         if (head_open) {
             ps[0] = seg_sum[0][0];
             ps[1] = seg_sum[0][1];
