@@ -79,6 +79,9 @@ def main():
                     help="sgdm: Algorithm 4 (the default, the metric's configuration); sgd: Algorithm 3 worker "
                          "without a momentum buffer; fused: one message per worker (Section 4.2); wd: parameter "
                          "update with weight decay (Appendix A)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a captured HIP graph of the step (one graph per resident gradient set) "
+                         "instead of eager calls; per-call times then come from an untimed eager pass")
     ap.add_argument("--calib", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB elementwise kernel (known size) for counter calibration")
     args = ap.parse_args()
@@ -177,11 +180,34 @@ def main():
 
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(events[k])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    if args.graph:
+        # per-call breakdown from an eager pass, then the timed region replays captured graphs
+        for k in range(args.steps):
+            step(events[k])
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graphs = []
+        for s_ in range(n_sets):
+            state["t"] = s_
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                step()
+            graphs.append(gr)
+        torch.cuda.synchronize()
+        for k in range(max(args.warmup, 1)):
+            graphs[k % n_sets].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graphs[k % n_sets].replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(events[k])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
     # untimed diagnostic: one more worker and server call, asking each how many tiles left the one-pass route
@@ -212,7 +238,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": dict(w.describe(), variant=variant, grad_sets_in_hbm=n_sets, elements_counted="(M+1)*d per step",
+        "config": dict(w.describe(), variant=variant, launch="hip graph replay" if args.graph else "eager calls",
+                       grad_sets_in_hbm=n_sets, elements_counted="(M+1)*d per step",
                        d_per_step_Gelem_s=round(d / (ms_per_step * 1e-3) / 1e9, 3)),
         "roofline": {
             "bound": "hbm",

@@ -20,9 +20,11 @@
  *   stream).  Calls enqueue work and return without synchronising.  All calls
  *   that share one plan must be ordered on the device (same stream, or ordered
  *   by events): the plan owns scratch memory that the kernels of a call use.
- *   Every call passes its kernels a call number and per-worker tags that change
- *   from call to call, so a captured HIP graph of these calls must not be
- *   replayed: replaying would reuse the numbers of the captured call.
+ *   What differs between two calls (call number, tags of the scratch) is kept
+ *   in device memory and advanced by the last kernel of each call, and no call
+ *   records a memset: ef_worker_step*, ef_server_step*, ef_apply* may be
+ *   captured into a HIP graph and the graph replayed; replays and eager calls
+ *   on one plan may be mixed as long as they are ordered on the device.
  * Block partition {G_1..G_B} (Section 3.2).  Block b is the contiguous index
  *   range [block_offsets[b], block_offsets[b+1]) of the flat d-vector;
  *   block_offsets[0] = 0, strictly increasing (every d_b >= 1, since d_b is a

@@ -11,14 +11,11 @@
 
 struct ef_plan {
     ef::Layout L;
-    ef::Scratch X;
+    ef::ScratchRef X;
     int max_workers;
     int device;
     int spin_limit;
-    unsigned int calls;             // calls issued so far; its parity picks the list counters
-    unsigned int epoch;             // number of the last call, skipping 0; carried by the ready words
-    unsigned int *last_defer_cnt, *last_fin_cnt;   // list counters of the most recent call
-    std::vector<uint8_t> set_tag;   // tag the last call that used a set gave its partial words
+    ef::CallState *d_state;         // calls made so far and the tags of the scratch sets: advanced on the device
     std::vector<int64_t> offs_host;
     std::vector<int32_t> fb_host, lb_host;
     // What depends on the one-pass limit, which differs between the worker kernels and the
@@ -96,6 +93,7 @@ void destroy_device(ef_plan *p)
     if (p->d_part) (void)hipFree(p->d_part);
     if (p->d_ready) (void)hipFree(p->d_ready);
     if (p->d_list_cnt) (void)hipFree(p->d_list_cnt);
+    if (p->d_state) (void)hipFree(p->d_state);
     if (p->d_defer_list) (void)hipFree(p->d_defer_list);
     if (p->d_fin_list) (void)hipFree(p->d_fin_list);
     for (auto &r : p->role) {
@@ -235,7 +233,8 @@ int build_device(ef_plan *p)
         p->L.uniform_tiles = p->d_uniform;
     }
     EF_HIP(hipMemset(p->d_list_cnt, 0, sizeof(unsigned int) * 6));
-    p->set_tag.assign(nsets, 0);                 // the zeroed partial words carry tag 0
+    EF_HIP(hipMalloc(&p->d_state, sizeof(ef::CallState)));
+    EF_HIP(hipMemset(p->d_state, 0, sizeof(ef::CallState)));     // the zeroed partial words carry tag 0
     p->L.offs = p->d_offs;
     p->L.tile_fb = p->d_tile_fb;
     p->L.tile_lb = p->d_tile_lb;
@@ -243,6 +242,8 @@ int build_device(ef_plan *p)
     p->X.ready = p->d_ready;
     p->X.defer_list = p->d_defer_list;
     p->X.fin_list = p->d_fin_list;
+    p->X.list_cnt = p->d_list_cnt;
+    p->X.state = p->d_state;
     // A block finishes in one pass if its tiles fit twice over into the
     // workgroups resident at once (see ef_device.h).
     {
@@ -273,51 +274,29 @@ int build_device(ef_plan *p)
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
     p->persistent_forced = 0;
-    p->calls = 0;
-    p->epoch = 0;
-    p->last_defer_cnt = p->last_fin_cnt = nullptr;
     int rc = refresh_limits(p);
     if (rc) return rc;
     EF_HIP(hipDeviceSynchronize());
     return EF_OK;
 }
 
-// Scratch view of one call over the sets [set_base, set_base + nsets): flips the
-// tag of every set it uses and picks the list counters of this call's parity.
+// Scratch argument of one call over the sets [set_base, set_base + nsets).  Everything that
+// differs between two calls of the same kind is read by the kernels from device memory.
 struct CallScratch {
-    ef::Scratch X;
-    unsigned int *next_defer_cnt, *next_fin_cnt, *next_ticket;
+    ef::ScratchRef X;
 };
 
-CallScratch next_call(const ef_plan *plan_c, int set_base, int nsets)
+CallScratch next_call(const ef_plan *plan, int set_base, int nsets)
 {
-    ef_plan *plan = const_cast<ef_plan *>(plan_c);   // calls on one plan are ordered by contract
+    (void)nsets;
     CallScratch c;
     c.X = plan->X;
-    c.X.tags = 0;
-    for (int i = 0; i < nsets; ++i) {
-        plan->set_tag[set_base + i] ^= 1u;
-        c.X.tags |= (unsigned long long)plan->set_tag[set_base + i] << i;
-    }
     c.X.set_base = set_base;
     c.X.spin_limit = plan->spin_limit;
-    const unsigned cur = plan->calls & 1u, nxt = cur ^ 1u;
-    plan->calls += 1;
-    plan->epoch += 1;
-    if (plan->epoch == 0) plan->epoch = 1;       // 0 marks "no scale posted"
-    c.X.epoch = plan->epoch;
-    c.X.defer_cnt = plan->d_list_cnt + cur;
-    c.X.fin_cnt = plan->d_list_cnt + 2 + cur;
-    plan->last_defer_cnt = c.X.defer_cnt;
-    plan->last_fin_cnt = c.X.fin_cnt;
-    c.X.ticket = plan->d_list_cnt + 4 + cur;
-    c.next_defer_cnt = plan->d_list_cnt + nxt;
-    c.next_fin_cnt = plan->d_list_cnt + 2 + nxt;
-    c.next_ticket = plan->d_list_cnt + 4 + nxt;
     return c;
 }
 
-// The two short kernels after the main one: missing scales, then parked residuals.
+// The kernels after the main one: missing scales, parked residuals, and the step to the next call.
 ef::Layout role_layout(const ef_plan *plan, int role)
 {
     ef::Layout L = plan->L;
@@ -334,8 +313,10 @@ int launch_second_pass(const ef_plan *plan, int role, const CallScratch &c, int 
                        (const int32_t *)r.d_late, (int)r.n_late, nsets, scales, scales_stride);
     EF_HIP(hipGetLastError());
     hipLaunchKernelGGL(ef::k_residual_parked, dim3(r.n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s, L,
-                       c.X, (const uint32_t *)r.d_static, (int)r.n_static, nsets, c.next_defer_cnt, c.next_fin_cnt, c.next_ticket, err, err_stride,
+                       c.X, (const uint32_t *)r.d_static, (int)r.n_static, nsets, err, err_stride,
                        (const float *)scales, scales_stride);
+    EF_HIP(hipGetLastError());
+    hipLaunchKernelGGL(ef::k_advance, dim3(1), dim3(64), 0, s, plan->d_state, c.X.set_base, nsets);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
@@ -381,6 +362,7 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_part = nullptr;
     p->d_ready = nullptr;
     p->d_list_cnt = nullptr;
+    p->d_state = nullptr;
     p->d_defer_list = nullptr;
     p->d_fin_list = nullptr;
     for (auto &r : p->role) {
@@ -433,9 +415,12 @@ int ef_plan_last_fallbacks(ef_plan *plan, unsigned int *parked_tiles, unsigned i
     if (!plan) return EF_ERR_NULL;
     EF_HIP(hipDeviceSynchronize());
     unsigned int a = 0, b = 0;
-    if (plan->last_defer_cnt) {
-        EF_HIP(hipMemcpy(&a, plan->last_defer_cnt, sizeof a, hipMemcpyDeviceToHost));
-        EF_HIP(hipMemcpy(&b, plan->last_fin_cnt, sizeof b, hipMemcpyDeviceToHost));
+    ef::CallState st;
+    EF_HIP(hipMemcpy(&st, plan->d_state, sizeof st, hipMemcpyDeviceToHost));
+    if (st.calls > 0) {         // the most recent call used the counters of parity (calls - 1) & 1
+        const unsigned last = (st.calls - 1u) & 1u;
+        EF_HIP(hipMemcpy(&a, plan->d_list_cnt + last, sizeof a, hipMemcpyDeviceToHost));
+        EF_HIP(hipMemcpy(&b, plan->d_list_cnt + 2 + last, sizeof b, hipMemcpyDeviceToHost));
     }
     if (parked_tiles) *parked_tiles = a;
     if (late_blocks) *late_blocks = b;

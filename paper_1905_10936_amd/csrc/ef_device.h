@@ -79,7 +79,30 @@ struct Layout {
     const int32_t *uniform_tiles; // [n_uniform] ascending
 };
 
-// Scratch of one call.  A "set" is one worker, or the server.
+// What changes from call to call lives in device memory, so that the kernel
+// arguments of a call are the same every time (a captured HIP graph of the
+// calls can be replayed): the number of calls made on the plan and the tag each
+// scratch set's partial words carry since the last call that used the set.
+// The last kernel of a call (k_advance) moves it on.
+struct CallState {
+    unsigned int calls;
+    unsigned int server_tag;            // bit 0
+    unsigned long long worker_tags;     // bit i: worker i
+};
+
+// Kernel argument: the plan's scratch.  A "set" is one worker, or the server.
+struct ScratchRef {
+    unsigned long long *part;
+    unsigned long long *ready;
+    unsigned long long *defer_list;
+    unsigned long long *fin_list;
+    unsigned int *list_cnt;             // [6]: defer_cnt[2], fin_cnt[2], ticket[2]; a call uses those of its parity
+    const CallState *state;
+    int set_base;                       // first set this call uses (0 for workers, max_workers for the server)
+    int spin_limit;
+};
+
+// Scratch of one call, formed by every kernel from ScratchRef and CallState (open_call).
 struct Scratch {
     unsigned long long *part;   // [nsets][2*ntiles] tagged fp64 partial sums of open segments
     unsigned long long *ready;  // [nsets][B] (epoch << 32) | scale bits, posted by the block's gatherer
@@ -92,7 +115,36 @@ struct Scratch {
     unsigned int epoch;         // this call's number on the plan (never 0), carried by the ready words
     int set_base;               // first set this call uses (0 for workers, max_workers for the server)
     int spin_limit;             // polls before a waiting workgroup gives up and parks p
+    unsigned int *next_cnt;     // the three list counters of the next call (zeroed by this call's last kernel)
 };
+
+__device__ __forceinline__ unsigned uniform_u32(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
+
+__device__ __forceinline__ Scratch open_call(const ScratchRef &R)
+{
+    Scratch X;
+    const unsigned calls = uniform_u32(R.state->calls);
+    const unsigned cur = calls & 1u;
+    X.part = R.part;
+    X.ready = R.ready;
+    X.defer_list = R.defer_list;
+    X.fin_list = R.fin_list;
+    X.defer_cnt = R.list_cnt + cur;
+    X.fin_cnt = R.list_cnt + 2 + cur;
+    X.ticket = R.list_cnt + 4 + cur;
+    X.next_cnt = R.list_cnt + (cur ^ 1u);
+    // this call's tags are the stored ones flipped
+    if (R.set_base == 0) {
+        const unsigned long long t = R.state->worker_tags;
+        X.tags = ~(((unsigned long long)uniform_u32((unsigned)(t >> 32)) << 32) | uniform_u32((unsigned)t));
+    } else {
+        X.tags = (unsigned long long)(uniform_u32(R.state->server_tag) ^ 1u);
+    }
+    X.epoch = calls % 0xffffffffu + 1u;     // never 0: 0 marks "no scale posted"
+    X.set_base = R.set_base;
+    X.spin_limit = R.spin_limit;
+    return X;
+}
 
 struct WorkerArgs {
     const float *grad; int64_t grad_stride;
@@ -701,8 +753,9 @@ __device__ __forceinline__ void worker_values(const float4 (&g)[SUBROWS], float4
 // Mixed tiles of all workers, one workgroup per (tile, worker).  Runs before
 // the uniform-tile kernel of the same call.
 template <bool MOM>
-__global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, Scratch X, WorkerArgs A)
+__global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, ScratchRef R, WorkerArgs A)
 {
+    const Scratch X = open_call(R);
     __shared__ TileShared S;
     const int32_t tile = L.mixed_tiles[blockIdx.x];
     const int worker = blockIdx.y;
@@ -850,8 +903,9 @@ struct WorkerProducer {
 
 template <bool MOM>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
-void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
+void k_worker_uniform(Layout L, ScratchRef R, WorkerArgs A, int n_workers)
 {
+    const Scratch X = open_call(R);
     __shared__ TileShared S;
     WorkerProducer<MOM> prod;
     prod.A = A;
@@ -868,8 +922,9 @@ void k_worker_uniform(Layout L, Scratch X, WorkerArgs A, int n_workers)
 // transformer-like layout, no change elsewhere).
 template <bool MOM>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k_worker_uniform_direct(Layout L, Scratch X, WorkerArgs A)
+void k_worker_uniform_direct(Layout L, ScratchRef R, WorkerArgs A)
 {
+    const Scratch X = open_call(R);
     __shared__ TileShared S;
     const int32_t tile = L.uniform_tiles[blockIdx.x];
     const int worker = blockIdx.y;
@@ -927,8 +982,9 @@ constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight to
 // Six workgroups per CU (80 VGPRs): measured 0.58 ms against 0.63 ms at five and 0.73 ms at eight
 // (where a third of the tile spills) on 2^28 elements and 8 workers.
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(6, 8)))
-void k_server_uniform(Layout L, Scratch X, ServerArgs A, int set)
+void k_server_uniform(Layout L, ScratchRef R, ServerArgs A, int set)
 {
+    const Scratch X = open_call(R);
     __shared__ TileShared S;
     const int32_t tile = L.uniform_tiles[blockIdx.x];
     constexpr int n_valid = TILE;
@@ -987,8 +1043,9 @@ void k_server_uniform(Layout L, Scratch X, ServerArgs A, int set)
 
 // Server on the mixed tiles (several blocks meet, or the ragged last tile): a
 // per-element segment index in LDS selects each worker's scale.  Never waits.
-__global__ __launch_bounds__(THREADS) void k_server_mixed(Layout L, Scratch X, ServerArgs A, int set)
+__global__ __launch_bounds__(THREADS) void k_server_mixed(Layout L, ScratchRef R, ServerArgs A, int set)
 {
+    const Scratch X = open_call(R);
     __shared__ TileShared S;
     const int32_t tile = L.mixed_tiles[blockIdx.x];
     const int n_valid = tile_valid(L, tile);
@@ -1095,12 +1152,13 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
 
 // Scales the first kernels of a call did not write: those of the blocks on the
 // per-layout list (crossing blocks without a uniform tile, blocks larger than
-// fuse_limit: workgroups 0 .. n_late*nsets-1) and those whose last arriver gave
+// fuse_limit: workgroups 0 .. n_late*nsets-1) and those whose gatherer gave
 // up gathering (list filled at run time: the last DEFER_WGS workgroups).
-__global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X, const int32_t *late_blocks,
+__global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, ScratchRef R, const int32_t *late_blocks,
                                                              int n_late, int nsets, float *scales,
                                                              int64_t scales_stride)
 {
+    const Scratch X = open_call(R);
     __shared__ double red[NWAVES];
     const int n_static = n_late * nsets;
     if ((int)blockIdx.x < n_static) {
@@ -1126,16 +1184,15 @@ __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, Scratch X
 // fuse_limit: workgroups 0 .. n_items*nsets-1) and the tiles whose wait ran out
 // (list filled at run time: the last DEFER_WGS workgroups).  Also clears the
 // list counters the next call will use.
-__global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X, const uint32_t *items,
-                                                             int n_items, int nsets, unsigned int *next_defer_cnt,
-                                                             unsigned int *next_fin_cnt, unsigned int *next_ticket,
-                                                             float *err, int64_t err_stride, const float *scales,
-                                                             int64_t scales_stride)
+__global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, ScratchRef R, const uint32_t *items,
+                                                             int n_items, int nsets, float *err, int64_t err_stride,
+                                                             const float *scales, int64_t scales_stride)
 {
+    const Scratch X = open_call(R);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        *next_defer_cnt = 0u;
-        *next_fin_cnt = 0u;
-        *next_ticket = 0u;
+        X.next_cnt[0] = 0u;
+        X.next_cnt[2] = 0u;
+        X.next_cnt[4] = 0u;
     }
     const int n_static = n_items * nsets;
     if ((int)blockIdx.x < n_static) {
@@ -1151,6 +1208,18 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, Scratch X
         const int w = (int)(it >> 33) - X.set_base;
         const int32_t tile = (int32_t)((it >> 1) & 0xffffffffull);
         residual_segment(L, tile, (int)(it & 1ull), err + (int64_t)w * err_stride, scales + (int64_t)w * scales_stride);
+    }
+}
+
+// The call is over: count it and flip the tags of the sets it used (one thread).
+__global__ void k_advance(CallState *state, int set_base, int nsets)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        state->calls = state->calls + 1u;
+        if (set_base == 0)
+            state->worker_tags ^= nsets >= 64 ? ~0ull : ((1ull << nsets) - 1ull);
+        else
+            state->server_tag ^= 1u;
     }
 }
 
