@@ -20,6 +20,9 @@
  *   stream).  Calls enqueue work and return without synchronising.  All calls
  *   that share one plan must be ordered on the device (same stream, or ordered
  *   by events): the plan owns scratch memory that the kernels of a call use.
+ *   Calls on different plans may overlap on the device; every wait inside the
+ *   kernels is bounded, so kernels that compete for the compute units cannot
+ *   hang each other (at worst some tiles take the two-pass route).
  *   What differs between two calls (call number, tags of the scratch) is kept
  *   in device memory and advanced by the last kernel of each call, and no call
  *   records a memset: ef_worker_step*, ef_server_step*, ef_apply* may be

@@ -269,3 +269,37 @@ def test_fallback_counters():
             assert parked >= 2 * (40 + 23) and late == 4     # every full single-block tile, both big blocks x 2 workers
         else:
             assert parked == 0 and late == 0
+
+
+def test_two_plans_on_two_streams_at_once():
+    """Calls on different plans may overlap on the device.  Their kernels compete
+    for the same compute units, and every wait in them is bounded, so at worst
+    some tiles take the two-pass route: the results must be those of the same
+    calls made one after the other."""
+    offs_a = _offs(LAYOUTS["two_big"])
+    offs_b = _offs([6 * 4096] * 40)
+    rng = np.random.default_rng(8)
+    outs = []
+    for overlap in (False, True):
+        sa, sb = GpuState(offs_a, 4, route="direct"), GpuState(offs_b, 8, route="one_pass")
+        rng_run = np.random.default_rng(9)
+        streams = (torch.cuda.Stream(), torch.cuda.Stream())
+        eta_prev = 0.0
+        for t in range(4):
+            for st in (sa, sb):
+                st.set_grads(rng_run.standard_normal((st.M, st.d)).astype(F))
+            torch.cuda.synchronize()
+            for st, stream in ((sa, streams[0]), (sb, streams[1])):
+                with torch.cuda.stream(stream):
+                    ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.9, eta_prev, 0.1, st.ws, st.wc, stream=stream)
+                    ef.ef_server_step(st.plan, st.M, st.ws, st.wc, st.te, eta_prev, 0.1, st.ss, st.sc, stream=stream)
+                    ef.ef_apply(st.plan, st.x, st.ss, st.sc, 0.1, stream=stream)
+                if not overlap:
+                    stream.synchronize()
+            torch.cuda.synchronize()
+            eta_prev = 0.1
+        outs.append([to_np(t).copy() for st in (sa, sb) for t in (st.ws, st.wc, st.ss, st.sc, st.m, st.e, st.te, st.x)])
+        sa.plan.close()
+        sb.plan.close()
+    for u, v in zip(*outs):
+        assert np.array_equal(u.view(np.uint8), v.view(np.uint8))
