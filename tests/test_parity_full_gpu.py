@@ -285,3 +285,47 @@ def test_beyond_2p31_elements_sampled():
     assert w.d > (1 << 31)
     blocks = [0, 2046, 2047] + list(range(2048, w.B))
     _run_sampled(w, w.steps, blocks, check_props=False)
+
+
+@pytest.mark.parametrize("persistent", [True, False])
+def test_blocks_around_the_one_pass_limits(persistent):
+    """Blocks whose tile counts sit on both sides of every default one-pass limit (768, 1024, 1152,
+    1536 tiles), some ending off the tile grid, with the plan's own limits: each block must take the
+    route its size calls for and give the oracle's result either way.  All blocks go through the oracle."""
+    tiles = [767, 768, 769, 1023, 1024, 1025, 1151, 1152, 1153, 1535, 1536, 1537]
+    rng = np.random.default_rng(12)
+    sizes = [t * 4096 + int(rng.integers(-3, 4)) for t in tiles]
+    order = rng.permutation(len(sizes))
+    w = wl.Workload("limit_blocks", 9, [sizes[i] for i in order], M=2, steps=2, dist=("normal", 1.0))
+    dev = torch.device("cuda")
+    plan = ef.ef_plan_create(w.offsets, w.M)
+    plan.set_persistent(persistent)
+    d, B, M = w.d, w.B, w.M
+    W = (d + 63) // 64
+    ds = (d + 3) // 4 * 4
+    g = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+    m = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+    e = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+    ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
+    wc = torch.zeros((M, B), dtype=torch.float32, device=dev)
+    eta_prev = 0.0
+    for t in range(w.steps):
+        for i in range(M):
+            w.grad(t, i, device=dev, out=g[i, :d])
+        g_h, m_h, e_h = (x[:, :d].cpu().numpy() for x in (g, m, e))
+        print("[limit_blocks persistent=%s] step %d on the GPU (limit %d tiles)" % (persistent, t, plan.fuse_limit), flush=True)
+        ef.ef_worker_step(plan, g, m, e, w.mu, eta_prev, w.eta, ws, wc)
+        torch.cuda.synchronize()
+        parked, late = plan.last_fallbacks()
+        assert parked == 0 and late == 0, "run-time fallbacks on an idle GPU: %d tiles, %d blocks" % (parked, late)
+        for i in range(M):
+            print("[limit_blocks] step %d: oracle for worker %d" % (t, i), flush=True)
+            mi, ei = np.ascontiguousarray(m_h[i]), np.ascontiguousarray(e_h[i])
+            s_ref, c_ref = oracle.worker_step(np.ascontiguousarray(g_h[i]), mi, ei, w.offsets, F(w.mu), F(eta_prev), F(w.eta))
+            tag = "limit_blocks persistent=%s step %d worker %d" % (persistent, t, i)
+            assert np.array_equal(ws[i].cpu().numpy().view(np.uint64), s_ref), tag + ": sign words differ"
+            assert np.array_equal(m[i, :d].cpu().numpy().view(np.uint32), mi.view(np.uint32)), tag + ": momentum differs"
+            same = check_scales(wc[i].cpu().numpy(), c_ref, tag)
+            check_vector(e[i, :d].cpu().numpy(), ei, c_ref, same, w.offsets, tag + " residual")
+        eta_prev = w.eta
+    plan.close()
