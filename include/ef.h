@@ -101,6 +101,12 @@ int ef_plan_destroy(ef_plan *plan);
  * kernel gets its own limit: half the tiles its workgroups can hold at once
  * (resident workgroups, times three for the persistent worker kernel), at most
  * 1536 tiles.  A limit set here applies to worker and server alike.
+ *
+ * For the caller's choice of blocks this means: a block of up to about 4.7 M
+ * elements (1152 tiles, the persistent worker kernel's default limit on a GPU
+ * with 256 compute units) costs 20.125 bytes of HBM traffic per element and
+ * worker; a larger block has its corrected gradient written out and read back
+ * once more (28.125 bytes).  Proposition 1 favours finer blocks as well.
  */
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
 int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit in force */
