@@ -1,0 +1,237 @@
+// Worker kernels of libef (Algorithm 4 and Algorithm 3 of arxiv 1905.10936): see ef_tile.h for the tile scheme.
+#pragma once
+#include "ef_tile.h"
+
+namespace ef {
+
+// --------------------------------------------------------- worker kernels ---
+
+// The worker's corrected gradient, one rounding per operation, left to right.
+// MOM (Algorithm 4): m <- mu*m + g and p = mu*m + g + r*e; m is overwritten
+// with the new momentum, e with p.  !MOM (Algorithm 3, no momentum buffer):
+// p = g + r*e; m is not touched.
+template <bool MOM>
+__device__ __forceinline__ void worker_values(const float4 (&g)[SUBROWS], float4 (&m)[SUBROWS], float4 (&e)[SUBROWS],
+                                              float mu, float r)
+{
+    if (!MOM) {
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) {
+            e[k].x = g[k].x + r * e[k].x;
+            e[k].y = g[k].y + r * e[k].y;
+            e[k].z = g[k].z + r * e[k].z;
+            e[k].w = g[k].w + r * e[k].w;
+        }
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k) {
+        m[k].x = mu * m[k].x + g[k].x;
+        m[k].y = mu * m[k].y + g[k].y;
+        m[k].z = mu * m[k].z + g[k].z;
+        m[k].w = mu * m[k].w + g[k].w;
+        e[k].x = (mu * m[k].x + g[k].x) + r * e[k].x;
+        e[k].y = (mu * m[k].y + g[k].y) + r * e[k].y;
+        e[k].z = (mu * m[k].z + g[k].z) + r * e[k].z;
+        e[k].w = (mu * m[k].w + g[k].w) + r * e[k].w;
+    }
+}
+
+// Mixed tiles of all workers, one workgroup per (tile, worker).  Runs before
+// the uniform-tile kernel of the same call.
+template <bool MOM>
+__global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, ScratchRef R, WorkerArgs A)
+{
+    const Scratch X = open_call(R);
+    __shared__ TileShared S;
+    const int32_t tile = L.mixed_tiles[blockIdx.x];
+    const int worker = blockIdx.y;
+    const int n_valid = tile_valid(L, tile);
+    const int64_t tile_start = (int64_t)tile * TILE;
+    const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
+    float *m = MOM ? A.mom + (int64_t)worker * A.state_stride + tile_start : nullptr;
+    float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
+    float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
+    load_tile(g, gv, n_valid);
+    if (MOM) load_tile(m, mv, n_valid);
+    load_tile(e, pv, n_valid);
+    worker_values<MOM>(gv, mv, pv, A.mu, A.r);
+    if (MOM) store_tile(m, mv, n_valid);
+    float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
+    compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker, S);
+}
+
+// Uniform tiles of the worker as a persistent kernel.
+//
+// Every workgroup loops: take the next tile, issue its loads, and while they
+// are in flight write out the oldest of the PIPE_DEPTH tiles it holds in
+// registers (their blocks' scales have had PIPE_DEPTH tile-times to form, so
+// the wait is normally over before it starts); then compute the new tile, post
+// its partial sum and keep it in turn.  Tiles are handed out one by one through
+// a ticket counter, so at any moment the resident workgroups
+// work on one compact, advancing window of the fp32 streams (best DRAM page
+// locality, no dependence on dispatch order).  A workgroup never waits for a
+// block of which it still holds an unposted tile, so a wait only ever depends
+// on workgroups that wait for strictly older blocks; it could starve only if
+// one block had more than (resident workgroups x PIPE_DEPTH) uniform tiles,
+// which fuse_limit rules out, and it is bounded by spin_limit in any case.
+//
+// What is streamed comes from a producer (Algorithm 4 or Algorithm 3 worker):
+//   issue(L, idx, tile)        start the tile's loads (idx: which worker)
+//   produce(L, idx, tile, p)   the corrected values p of Algorithm 4 (and the role's other stores)
+//   signs(L, idx), scales(L, idx), err_tile(idx, tile)   where that participant's outputs go
+struct HeldTile {
+    float4 p[SUBROWS];
+    int32_t tile;
+    int idx;
+    int b;                      // < 0: slot empty
+};
+
+template <class Producer>
+__device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratch &X, Producer &prod, int n_part,
+                                                   TileShared &S)
+{
+    const unsigned per_part = (unsigned)L.n_uniform;
+    const unsigned total = per_part * (unsigned)n_part;
+
+    HeldTile held[PIPE_DEPTH];
+#pragma unroll
+    for (int q = 0; q < PIPE_DEPTH; ++q) held[q].b = -1;
+    Posted posted;
+    clear_posted(posted);
+    int posted_idx = 0;
+
+    unsigned tk_next = 0;       // thread 0: the ticket taken ahead of need
+    if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);
+
+    for (;;) {
+        // ---- next tile
+        if (threadIdx.x == 0) S.ticket = tk_next;
+        __syncthreads();
+        const unsigned t = (unsigned)__builtin_amdgcn_readfirstlane((int)S.ticket);
+        __syncthreads();
+        if (t >= total) break;
+        if (threadIdx.x == 0) tk_next = atomicAdd(X.ticket, 1u);   // the answer is read at the next tile
+        const int idx = (int)(t / per_part);
+        const int32_t tile = L.uniform_tiles[t % per_part];
+        const int set = X.set_base + idx;
+
+        // ---- this tile's loads go out first
+        prod.issue(L, idx, tile);
+
+        // ---- while they fly: follow up on the previous tile's post, write out the oldest tile held
+        HeldTile &old = held[0];
+        const unsigned long long peeked = peek_ready(old.b, L, X, X.set_base + (old.b >= 0 ? old.idx : 0));
+        resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
+        if (old.b >= 0) {
+            // The block of the oldest tile cannot complete while this workgroup sits on a tile of
+            // the same block that is not posted yet (the new one): then do not wait, park p and
+            // leave the tile to the second pass.
+            const bool may_wait = !(old.idx == idx && L.tile_fb[tile] == old.b);
+            finish_uniform(old.p, old.tile, TILE, old.b, peeked, prod.err_tile(old.idx, old.tile), L, X,
+                           X.set_base + old.idx, S, may_wait);
+        }
+#pragma unroll
+        for (int q = 0; q + 1 < PIPE_DEPTH; ++q) held[q] = held[q + 1];
+
+        // ---- the new tile
+        float4 pv[SUBROWS];
+        prod.produce(L, idx, tile, pv);
+        HeldTile &slot = held[PIPE_DEPTH - 1];
+        const int kind = compress_uniform(pv, L, tile, TILE, prod.signs(L, idx), prod.scales(L, idx),
+                                          prod.err_tile(idx, tile), X, set, S, posted);
+        posted_idx = idx;
+        slot.b = -1;
+        if (kind == UNI_PENDING) {
+#pragma unroll
+            for (int k = 0; k < SUBROWS; ++k) slot.p[k] = pv[k];
+            slot.tile = tile;
+            slot.idx = idx;
+            slot.b = L.tile_fb[tile];
+        }
+    }
+
+    // ---- drain
+    resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
+#pragma unroll
+    for (int q = 0; q < PIPE_DEPTH; ++q) {
+        if (held[q].b >= 0)
+            finish_uniform(held[q].p, held[q].tile, TILE, held[q].b, 0ull, prod.err_tile(held[q].idx, held[q].tile), L,
+                           X, X.set_base + held[q].idx, S);
+    }
+}
+
+template <bool MOM>
+struct WorkerProducer {
+    WorkerArgs A;
+    float4 gv[SUBROWS], mv[SUBROWS], ev[SUBROWS];
+
+    __device__ __forceinline__ uint64_t *signs(const Layout &L, int idx) const { return A.signs + (int64_t)idx * A.signs_stride; }
+    __device__ __forceinline__ float *scales(const Layout &L, int idx) const { return A.scales + (int64_t)idx * A.scales_stride; }
+    __device__ __forceinline__ float *err_tile(int idx, int32_t tile) const
+    {
+        return A.err + (int64_t)idx * A.state_stride + (int64_t)tile * TILE;
+    }
+    __device__ __forceinline__ void issue(const Layout &, int idx, int32_t tile)
+    {
+        const int64_t tile_start = (int64_t)tile * TILE;
+        load_tile(A.grad + (int64_t)idx * A.grad_stride + tile_start, gv, TILE);
+        if (MOM) load_tile(A.mom + (int64_t)idx * A.state_stride + tile_start, mv, TILE);
+        load_tile(A.err + (int64_t)idx * A.state_stride + tile_start, ev, TILE);
+    }
+    __device__ __forceinline__ void produce(const Layout &, int idx, int32_t tile, float4 (&p)[SUBROWS])
+    {
+        worker_values<MOM>(gv, mv, ev, A.mu, A.r);
+        if (MOM) store_tile(A.mom + (int64_t)idx * A.state_stride + (int64_t)tile * TILE, mv, TILE);
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) p[k] = ev[k];
+    }
+};
+
+template <bool MOM>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void k_worker_uniform(Layout L, ScratchRef R, WorkerArgs A, int n_workers)
+{
+    const Scratch X = open_call(R);
+    __shared__ TileShared S;
+    WorkerProducer<MOM> prod;
+    prod.A = A;
+    persistent_uniform(L, X, prod, n_workers, S);
+}
+
+// Uniform tiles of all workers, one workgroup per (tile, worker): the same
+// steps without the pipeline; the workgroup waits in place for its block's
+// scale.  Relies on workgroups being dispatched in grid order (fuse_limit keeps
+// a block's tiles well inside what is resident at once) and on spin_limit.
+// Eight workgroups per CU (64 VGPRs, a few spilled): the one-pass limit is half
+// of what is resident, and 2048 resident workgroups let blocks of up to 1024
+// tiles (4 Mi elements) finish in one pass (measured: 27.1 -> 24.4 ms on the
+// transformer-like layout, no change elsewhere).
+template <bool MOM>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k_worker_uniform_direct(Layout L, ScratchRef R, WorkerArgs A)
+{
+    const Scratch X = open_call(R);
+    __shared__ TileShared S;
+    const int32_t tile = L.uniform_tiles[blockIdx.x];
+    const int worker = blockIdx.y;
+    constexpr int n_valid = TILE;
+    const int64_t tile_start = (int64_t)tile * TILE;
+    const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
+    float *m = MOM ? A.mom + (int64_t)worker * A.state_stride + tile_start : nullptr;
+    float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
+    Posted P;
+    float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
+    load_tile(g, gv, n_valid);
+    if (MOM) load_tile(m, mv, n_valid);
+    load_tile(e, pv, n_valid);
+    worker_values<MOM>(gv, mv, pv, A.mu, A.r);
+    if (MOM) store_tile(m, mv, n_valid);
+    float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
+    const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker,
+                                      S, P);
+    resolve_posted(P, L, X, worker, scales_out, S);
+    if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, L.tile_fb[tile], 0ull, e, L, X, worker, S);
+}
+
+}  // namespace ef
