@@ -14,20 +14,6 @@ __device__ __forceinline__ float mean_of(float acc, float Mf, float Minv)
     return Minv != 0.0f ? acc * Minv : acc / Mf;
 }
 
-// acc[c] += (+s if bit sh+c of `word` is set, else -s), c = 0..3: what one
-// worker's payload stands for in this lane's four elements.  The sign bit of
-// the addend is sign(s) XOR NOT(bit), built without a compare: `flip` is ~0 for
-// s >= 0 and 0 for s < 0, so word ^ flip has a 1 exactly where the addend is
-// negative; that bit is extracted, shifted to the top and or-ed onto `mag`, the
-// magnitude bits of s (one bit-field extract, one shift-or, one add per
-// element).  Negation by sign bit is exact for every s.
-__device__ __forceinline__ void add_decoded4(float (&acc)[4], uint32_t word, unsigned sh, uint32_t flip, uint32_t mag)
-{
-    const uint32_t x = word ^ flip;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) acc[c] = acc[c] + __uint_as_float((((x >> (sh + c)) & 1u) << 31) | mag);
-}
-
 constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight together
 
 // Server part of Algorithm 4 on the tiles that lie inside one block:
@@ -35,7 +21,12 @@ constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight to
 // server residual, compress.  One workgroup per tile; it waits in the kernel
 // for its block's scale.  The sign words of SERVER_CHUNK workers are loaded
 // together (one 32-bit word per worker and sub-row holds this lane's 4 bits),
-// the block's M scales come through scalar loads.
+// the block's M scales come through scalar loads.  Decoding goes through a
+// small table in LDS: entry (u, nibble) holds the four values +-s_u that the
+// nibble stands for, so a lane gets its four addends of worker u with one
+// bit-field extract and one 128-bit LDS read (16 entries of 16 bytes cover the
+// 64 banks once: no conflicts) instead of shifting and selecting bit by bit
+// (measured 0.57 -> 0.55 ms at M = 8, 0.70 -> 0.64 ms at M = 16 on 2^28 elements).
 // Six workgroups per CU (80 VGPRs): measured 0.58 ms against 0.63 ms at five and 0.73 ms at eight
 // (where a third of the tile spills) on 2^28 elements and 8 workers.
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(6, 8)))
@@ -74,16 +65,33 @@ void k_server_uniform(Layout L, ScratchRef R, ServerArgs A, int set)
 #pragma unroll
             for (int k = 0; k < SUBROWS; ++k) word[u][k] = s32[(int64_t)i * in_hw + hw0 + 8 * k];
         }
+        // table[u][nibble] = the four values (+-s_u) a nibble of worker u's sign bits stands for
+        float4 *table = reinterpret_cast<float4 *>(S.val);
+        if (i0 > 0) __syncthreads();
+        if (threadIdx.x < SERVER_CHUNK * 16) {
+            const int u = threadIdx.x >> 4, nib = threadIdx.x & 15;
+            float su = sc[0];
+#pragma unroll
+            for (int q = 1; q < SERVER_CHUNK; ++q) su = (u == q) ? sc[q] : su;
+            table[threadIdx.x] = make_float4(signed_scale(su, nib & 1), signed_scale(su, nib & 2),
+                                             signed_scale(su, nib & 4), signed_scale(su, nib & 8));
+        }
+        __syncthreads();
 #pragma unroll
         for (int u = 0; u < SERVER_CHUNK; ++u) {
             if (i0 + u < A.M) {
-                const uint32_t sb = __float_as_uint(sc[u]);
-                const uint32_t flip = ~(uint32_t)((int32_t)sb >> 31), mag = sb & 0x7fffffffu;
 #pragma unroll
-                for (int k = 0; k < SUBROWS; ++k) add_decoded4(acc[k], word[u][k], sh, flip, mag);
+                for (int k = 0; k < SUBROWS; ++k) {
+                    const float4 dv = table[u * 16 + ((word[u][k] >> sh) & 15u)];
+                    acc[k][0] = acc[k][0] + dv.x;
+                    acc[k][1] = acc[k][1] + dv.y;
+                    acc[k][2] = acc[k][2] + dv.z;
+                    acc[k][3] = acc[k][3] + dv.w;
+                }
             }
         }
     }
+    __syncthreads();            // the table's space is free again
     float4 p[SUBROWS];
     const float r = A.r, Mf = A.Mf, Minv = A.Minv;
 #pragma unroll
