@@ -239,11 +239,38 @@ __device__ __forceinline__ int tile_valid(const Layout &L, int32_t tile)
     return left >= TILE ? TILE : (int)left;
 }
 
-// Butterfly sum over the 64 lanes: every lane ends with the same bits.
+// Data-parallel-primitive moves inside a row of 16 lanes: the value of the lane
+// whose index differs in bit 0 / bit 1, and of the mirror lane within 8 / 16
+// lanes.  Applied in this order to an associative, commutative operation they
+// leave its result over the whole row in every lane of the row (after the
+// first two steps a group of four lanes agrees, and the mirrors pair up whole
+// groups), with no LDS traffic.
+#define EF_DPP_XOR1 0xB1            // quad_perm [1,0,3,2]
+#define EF_DPP_XOR2 0x4E            // quad_perm [2,3,0,1]
+#define EF_DPP_HALF_MIRROR 0x141    // lane i <- lane 7-i of its group of 8
+#define EF_DPP_MIRROR 0x140         // lane i <- lane 15-i of its row
+template <int CTRL>
+__device__ __forceinline__ unsigned row_move(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ double row_move(double v)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const unsigned lo = row_move<CTRL>((unsigned)b), hi = row_move<CTRL>((unsigned)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// Sum over the 64 lanes in a fixed order: every lane ends with the same bits.
 __device__ __forceinline__ double wave_sum(double v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    v += row_move<EF_DPP_XOR1>(v);
+    v += row_move<EF_DPP_XOR2>(v);
+    v += row_move<EF_DPP_HALF_MIRROR>(v);
+    v += row_move<EF_DPP_MIRROR>(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
     return v;
 }
 
@@ -294,11 +321,15 @@ __device__ __forceinline__ void store_signs(const float4 (&p)[SUBROWS], int n_va
         }
         unsigned lo = (l16 < 8) ? (nib << sh) : 0u;
         unsigned hi = (l16 >= 8) ? (nib << sh) : 0u;
-#pragma unroll
-        for (int off = 1; off <= 8; off <<= 1) {
-            lo |= (unsigned)__shfl_xor((int)lo, off);
-            hi |= (unsigned)__shfl_xor((int)hi, off);
-        }
+        // OR over the 16 lanes of the word
+        lo |= row_move<EF_DPP_XOR1>(lo);
+        hi |= row_move<EF_DPP_XOR1>(hi);
+        lo |= row_move<EF_DPP_XOR2>(lo);
+        hi |= row_move<EF_DPP_XOR2>(hi);
+        lo |= row_move<EF_DPP_HALF_MIRROR>(lo);
+        hi |= row_move<EF_DPP_HALF_MIRROR>(hi);
+        lo |= row_move<EF_DPP_MIRROR>(lo);
+        hi |= row_move<EF_DPP_MIRROR>(hi);
         if (l16 == k) { mylo = lo; myhi = hi; }
     }
     if (l16 < SUBROWS) {
