@@ -99,11 +99,12 @@ int ef_plan_destroy(ef_plan *plan);
  * through two passes, spin_limit = 0 makes every wait give up at once (used by
  * tests to exercise the fallback).  Synchronises the device.  By default each
  * kernel gets its own limit: half the tiles its workgroups can hold at once
- * (resident workgroups, times three for the persistent worker kernel), at most
- * 1536 tiles.  A limit set here applies to worker and server alike.
+ * (resident workgroups; times six for the persistent worker kernel, which
+ * keeps three tiles in registers and three in LDS), at most 4096 tiles.  A
+ * limit set here applies to worker and server alike.
  *
- * For the caller's choice of blocks this means: a block of up to about 4.7 M
- * elements (1152 tiles, the persistent worker kernel's default limit on a GPU
+ * For the caller's choice of blocks this means: a block of up to about 9.4 M
+ * elements (2304 tiles, the persistent worker kernel's default limit on a GPU
  * with 256 compute units) costs 20.125 bytes of HBM traffic per element and
  * worker; a larger block has its corrected gradient written out and read back
  * once more (28.125 bytes).  Proposition 1 favours finer blocks as well.
@@ -117,7 +118,8 @@ int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit 
  * and keep several tiles in registers while their scales form; on = 0 one
  * workgroup per tile that waits in place for its block's scale; on < 0 the
  * choice plan creation made for this layout (persistent when every workgroup
- * gets at least 64 tiles).  ef_worker_step_sgd uses the
+ * gets at least 64 tiles, or at least 16 and the layout has blocks that only
+ * the persistent kernel finishes in one pass).  ef_worker_step_sgd uses the
  * persistent kernel only after on = 1.  The server always runs one workgroup
  * per tile.  Same results either way.  Synchronises the device.
  */

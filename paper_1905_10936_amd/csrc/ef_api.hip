@@ -255,21 +255,28 @@ int build_device(ef_plan *p)
         if (occ_w < 1) occ_w = 1;
         p->worker_grid = prop.multiProcessorCount * occ_w;
         // one-pass blocks must fit twice over into the tiles a kernel's workgroups hold at once:
-        // grid x PIPE_DEPTH for the persistent kernels, the resident workgroups for the kernels that
+        // grid x (PIPE_DEPTH + STAGE_DEPTH) for the persistent kernel, the resident workgroups for the kernels that
         // run one workgroup per tile (dispatched in grid order).  Larger limits were measured slower:
         // a block that fills most of the machine makes its first tiles wait for its last.
         int occ_d = 0;
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, ef::k_worker_uniform_direct<true>, ef::THREADS, 0));
-        p->lim_persistent = (int32_t)((int64_t)p->worker_grid * ef::PIPE_DEPTH / 2);
+        p->lim_persistent = (int32_t)((int64_t)p->worker_grid * (ef::PIPE_DEPTH + ef::STAGE_DEPTH) / 2);
         p->lim_direct = (int32_t)((int64_t)prop.multiProcessorCount * occ_d / 2);
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
     }
     p->user_fuse_limit = -1;
-    // The persistent kernel pays off when every workgroup gets many tiles; otherwise one
-    // workgroup per tile (nothing to pipeline, and no ticket traffic).
+    // The persistent kernel pays off when every workgroup gets many tiles, and when it lets blocks
+    // finish in one pass that are too large for the other kernel; otherwise one workgroup per
+    // tile (nothing to pipeline, and no ticket traffic).
     {
         const int64_t tiles_per_wg = (int64_t)p->L.n_uniform * p->max_workers / (p->worker_grid > 0 ? p->worker_grid : 1);
-        p->persistent_auto = tiles_per_wg >= 64 ? 1 : 0;
+        const int64_t lim_hi = p->lim_persistent < ef::FUSE_LIMIT_MAX ? p->lim_persistent : ef::FUSE_LIMIT_MAX;
+        bool larger_blocks = false;
+        for (int64_t b = 0; b < B && !larger_blocks; ++b) {
+            const int64_t n = tiles_of_block(p, b);
+            larger_blocks = n > p->lim_direct && n <= lim_hi && has_uniform_tile(p, b);
+        }
+        p->persistent_auto = (tiles_per_wg >= 64 || (larger_blocks && tiles_per_wg >= 16)) ? 1 : 0;
     }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
@@ -549,12 +556,11 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
     if (plan->L.n_uniform && plan->persistent && (has_mom || plan->persistent_forced)) {
         int64_t wgs = (int64_t)plan->L.n_uniform * n_workers;
         if (wgs > plan->worker_grid) wgs = plan->worker_grid;
+        const dim3 grid((unsigned)wgs), block(ef::THREADS);
         if (has_mom)
-            hipLaunchKernelGGL(ef::k_worker_uniform<true>, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A,
-                               n_workers);
+            hipLaunchKernelGGL(ef::k_worker_uniform<true>, grid, block, 0, s, L, c.X, A, n_workers);
         else
-            hipLaunchKernelGGL(ef::k_worker_uniform<false>, dim3((unsigned)wgs), dim3(ef::THREADS), 0, s, L, c.X, A,
-                               n_workers);
+            hipLaunchKernelGGL(ef::k_worker_uniform<false>, grid, block, 0, s, L, c.X, A, n_workers);
         EF_HIP(hipGetLastError());
     } else if (plan->L.n_uniform) {
         const dim3 grid((unsigned)plan->L.n_uniform, (unsigned)n_workers);

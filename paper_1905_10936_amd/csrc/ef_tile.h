@@ -62,8 +62,7 @@ constexpr int DEFER_WGS = 64;   // workgroups that serve the run-time lists of t
 #endif
 constexpr int PIPE_DEPTH = EF_PIPE_DEPTH;     // tiles a persistent workgroup keeps in registers while their scales form
 constexpr unsigned long long TAG_BIT = 1ull << 63;
-constexpr int MAX_PER_THREAD = 6;                        // partial words a thread gathers
-constexpr int FUSE_LIMIT_MAX = MAX_PER_THREAD * THREADS; // tiles of the largest one-pass block
+constexpr int FUSE_LIMIT_MAX = 4096;                     // most tiles a one-pass block may be given through ef_plan_tune
 
 struct Layout {
     int64_t d;                  // elements
@@ -353,14 +352,18 @@ __device__ __forceinline__ double abs_sum(const float4 (&p)[SUBROWS], int n_vali
     return acc;
 }
 
-struct TileShared {
-    float val[TILE];            // |p| per element, then the element's scale (closed segments)
+// LDS of a workgroup: what every kernel needs for reductions and broadcasts ...
+struct SyncShared {
     double red[NWAVES];
+    int flag[2];
+    unsigned ticket;
+};
+// ... and what the kernels that cut a tile into segments need on top of it.
+struct TileShared : SyncShared {
+    float val[TILE];            // |p| per element, then the element's scale (closed segments)
     double open_sum[2];
     int long_list[MAX_LONG];
     int n_long;
-    int flag[2];
-    unsigned ticket;
 };
 
 // ------------------------------------------------- per-set scratch views ---
@@ -460,21 +463,27 @@ __device__ __forceinline__ double sum_block_partials(const Layout &L, int64_t b,
 // Wait (bounded) until every tile of block b has posted this call's partial,
 // then form the block's scale.  Called by every thread of the workgroup with
 // the same arguments; returns the same answer to all of them.
-__device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const Scratch &X, int set, TileShared &S,
+constexpr int GATHER_KEEP = 4;      // partial words per thread whose values are kept while polling
+
+__device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const Scratch &X, int set, SyncShared &S,
                                              float *s)
 {
-    const BlockSpan sp = block_span(L, b);          // sp.n <= fuse_limit <= FUSE_LIMIT_MAX
+    const BlockSpan sp = block_span(L, b);
     const unsigned long long *part = set_part(X, L, set);
     const unsigned long long tag = set_tag(X, set);
-    double v[MAX_PER_THREAD];
+    // Thread t is in charge of tiles t, t + 256, ...  All of them are polled in every round, so
+    // that the loads of a round overlap.  The values of the first GATHER_KEEP (blocks of up to
+    // 1024 tiles: all) are kept as they arrive; words beyond that are only checked for this
+    // call's tag and read once more when everything has arrived.
+    double v[GATHER_KEEP];
     unsigned have = 0;
 #pragma unroll
-    for (int q = 0; q < MAX_PER_THREAD; ++q) v[q] = 0.0;
-    bool ok = false;
+    for (int q = 0; q < GATHER_KEEP; ++q) v[q] = 0.0;
+    bool complete = false;
     for (int it = 0; it < X.spin_limit; ++it) {
         int all = 1;
 #pragma unroll
-        for (int q = 0; q < MAX_PER_THREAD; ++q) {
+        for (int q = 0; q < GATHER_KEEP; ++q) {
             const int i = (int)threadIdx.x + q * THREADS;
             if (i < sp.n && !((have >> q) & 1u)) {
                 const unsigned long long w =
@@ -487,16 +496,26 @@ __device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const S
                 }
             }
         }
+        for (int i = (int)threadIdx.x + GATHER_KEEP * THREADS; i < sp.n; i += THREADS) {
+            const unsigned long long w =
+                __hip_atomic_load(part + part_index(sp.t0 + i, sp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((w >> 63) != tag) all = 0;
+        }
         if (__syncthreads_and(all)) {
-            ok = true;
+            complete = true;
             break;
         }
         __builtin_amdgcn_s_sleep(8);
     }
-    if (!ok) return false;
-    double acc = 0.0;
+    if (!complete) return false;
+    double acc = 0.0;               // same order as sum_block_partials: thread t adds tiles t, t + 256, ... ascending
 #pragma unroll
-    for (int q = 0; q < MAX_PER_THREAD; ++q) acc += v[q];   // absent words were left at +0
+    for (int q = 0; q < GATHER_KEEP; ++q) acc += v[q];   // absent words were left at +0
+    for (int i = (int)threadIdx.x + GATHER_KEEP * THREADS; i < sp.n; i += THREADS) {
+        const unsigned long long w =
+            __hip_atomic_load(part + part_index(sp.t0 + i, sp), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        acc += __longlong_as_double((long long)(w & ~TAG_BIT));
+    }
     const double total = block_sum(acc, S.red);
     *s = (float)(total / (double)(sp.be - sp.bs));
     return true;
@@ -507,7 +526,7 @@ __device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const S
 // other tile of the block was handed out earlier), writes it out and posts it
 // for the block's other tiles.  Called by every thread of that workgroup.
 __device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const Scratch &X, int set,
-                                             float *scales_out, TileShared &S)
+                                             float *scales_out, SyncShared &S)
 {
     float s;
     const bool ok = gather_scale(b, L, X, set, S, &s);
@@ -527,7 +546,7 @@ __device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const S
 // Follow up on what a uniform tile posted: if it is its block's last whole
 // tile, finish that block.  Called by every thread of the workgroup.
 __device__ __forceinline__ void resolve_posted(const Posted &P, const Layout &L, const Scratch &X, int set,
-                                               float *scales_out, TileShared &S)
+                                               float *scales_out, SyncShared &S)
 {
     if (P.gather >= 0) finish_block(P.gather, L, X, set, scales_out, S);
 }
@@ -545,7 +564,7 @@ __device__ __forceinline__ unsigned long long peek_ready(int b, const Layout &L,
 // `peeked` is thread 0's earlier look at the word (see peek_ready).  Called by
 // every thread of the workgroup; same answer to all of them.
 __device__ __forceinline__ bool wait_ready(int64_t b, unsigned long long peeked, const Layout &L, const Scratch &X,
-                                           int set, TileShared &S, float *s)
+                                           int set, SyncShared &S, float *s)
 {
     if (threadIdx.x == 0) {
         const unsigned long long *word = set_ready(X, L, set) + b;
@@ -676,7 +695,7 @@ enum { UNI_DONE = 0, UNI_PARKED = 1, UNI_PENDING = 2 };
 
 __device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
                                                 uint64_t *signs, float *scales_out, float *err_tile,
-                                                const Scratch &X, int set, TileShared &S, Posted &P)
+                                                const Scratch &X, int set, SyncShared &S, Posted &P)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t b = L.tile_fb[tile];
@@ -706,7 +725,7 @@ __device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layo
 // the wait runs out, p is parked and the segment deferred.
 __device__ __forceinline__ void finish_uniform(float4 (&p)[SUBROWS], int32_t tile, int n_valid, int b,
                                                unsigned long long peeked, float *err_tile, const Layout &L,
-                                               const Scratch &X, int set, TileShared &S, bool may_wait = true)
+                                               const Scratch &X, int set, SyncShared &S, bool may_wait = true)
 {
     float s = 0.f;
     const bool ok = may_wait && wait_ready(b, peeked, L, X, set, S, &s);

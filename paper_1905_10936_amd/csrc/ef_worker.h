@@ -64,17 +64,21 @@ __global__ __launch_bounds__(THREADS) void k_worker_mixed(Layout L, ScratchRef R
 // Uniform tiles of the worker as a persistent kernel.
 //
 // Every workgroup loops: take the next tile, issue its loads, and while they
-// are in flight write out the oldest of the PIPE_DEPTH tiles it holds in
-// registers (their blocks' scales have had PIPE_DEPTH tile-times to form, so
-// the wait is normally over before it starts); then compute the new tile, post
-// its partial sum and keep it in turn.  Tiles are handed out one by one through
-// a ticket counter, so at any moment the resident workgroups
+// are in flight write out the oldest of the tiles it holds: the last
+// PIPE_DEPTH in registers and, behind them, STAGE_DEPTH more in LDS (a tile
+// leaving the registers is not written out yet but moved to LDS and written
+// out STAGE_DEPTH tiles later; one LDS round trip per element doubles the
+// number of tiles in flight, hence the size of the blocks that finish in one
+// pass).  By then its block's scale has had six tile-times to form, so the
+// wait is normally over before it starts.  Then the workgroup computes the new
+// tile, posts its partial sum and keeps it in turn.  Tiles are handed out one
+// by one through a ticket counter, so at any moment the resident workgroups
 // work on one compact, advancing window of the fp32 streams (best DRAM page
 // locality, no dependence on dispatch order).  A workgroup never waits for a
 // block of which it still holds an unposted tile, so a wait only ever depends
 // on workgroups that wait for strictly older blocks; it could starve only if
-// one block had more than (resident workgroups x PIPE_DEPTH) uniform tiles,
-// which fuse_limit rules out, and it is bounded by spin_limit in any case.
+// one block had more than (resident workgroups x 6) uniform tiles, which
+// fuse_limit rules out, and it is bounded by spin_limit in any case.
 //
 // What is streamed comes from a producer (Algorithm 4 or Algorithm 3 worker):
 //   issue(L, idx, tile)        start the tile's loads (idx: which worker)
@@ -87,9 +91,31 @@ struct HeldTile {
     int b;                      // < 0: slot empty
 };
 
+// A tile that has left the registers for the workgroup's LDS: every lane keeps
+// its own 16 values at its own addresses, so no barrier is needed.
+struct StagedTile {
+    int32_t tile;
+    int idx;
+    int b;                      // < 0: slot empty
+    int slot;                   // which third of the stage buffer holds its p
+};
+
+__device__ __forceinline__ void stage_store(float *stage, int slot, const float4 (&p)[SUBROWS])
+{
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k) *reinterpret_cast<float4 *>(stage + slot * TILE + local_base(k)) = p[k];
+}
+__device__ __forceinline__ void stage_load(const float *stage, int slot, float4 (&p)[SUBROWS])
+{
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k) p[k] = *reinterpret_cast<const float4 *>(stage + slot * TILE + local_base(k));
+}
+
+constexpr int STAGE_DEPTH = 3;      // tiles a workgroup keeps in LDS behind the PIPE_DEPTH it keeps in registers
+
 template <class Producer>
 __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratch &X, Producer &prod, int n_part,
-                                                   TileShared &S)
+                                                   SyncShared &S, float *stage)
 {
     const unsigned per_part = (unsigned)L.n_uniform;
     const unsigned total = per_part * (unsigned)n_part;
@@ -97,6 +123,14 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
     HeldTile held[PIPE_DEPTH];
 #pragma unroll
     for (int q = 0; q < PIPE_DEPTH; ++q) held[q].b = -1;
+    StagedTile staged[STAGE_DEPTH];
+#pragma unroll
+    for (int q = 0; q < STAGE_DEPTH; ++q) {
+        staged[q].b = -1;
+        staged[q].slot = q;
+        staged[q].tile = 0;
+        staged[q].idx = 0;
+    }
     Posted posted;
     clear_posted(posted);
     int posted_idx = 0;
@@ -120,16 +154,32 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
         prod.issue(L, idx, tile);
 
         // ---- while they fly: follow up on the previous tile's post, write out the oldest tile held
-        HeldTile &old = held[0];
-        const unsigned long long peeked = peek_ready(old.b, L, X, X.set_base + (old.b >= 0 ? old.idx : 0));
+        const int old_b = staged[0].b;
+        const int old_idx = staged[0].idx;
+        const int32_t old_tile = staged[0].tile;
+        const unsigned long long peeked = peek_ready(old_b, L, X, X.set_base + (old_b >= 0 ? old_idx : 0));
         resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
-        if (old.b >= 0) {
+        if (old_b >= 0) {
             // The block of the oldest tile cannot complete while this workgroup sits on a tile of
             // the same block that is not posted yet (the new one): then do not wait, park p and
             // leave the tile to the second pass.
-            const bool may_wait = !(old.idx == idx && L.tile_fb[tile] == old.b);
-            finish_uniform(old.p, old.tile, TILE, old.b, peeked, prod.err_tile(old.idx, old.tile), L, X,
-                           X.set_base + old.idx, S, may_wait);
+            const bool may_wait = !(old_idx == idx && L.tile_fb[tile] == old_b);
+            float4 pv_old[SUBROWS];
+            stage_load(stage, staged[0].slot, pv_old);
+            finish_uniform(pv_old, old_tile, TILE, old_b, peeked, prod.err_tile(old_idx, old_tile), L, X,
+                           X.set_base + old_idx, S, may_wait);
+        }
+        {
+            // the oldest register tile takes the LDS slot that has just become free
+            const int free_slot = staged[0].slot;
+#pragma unroll
+            for (int q = 0; q + 1 < STAGE_DEPTH; ++q) staged[q] = staged[q + 1];
+            StagedTile &in = staged[STAGE_DEPTH - 1];
+            in.slot = free_slot;
+            in.b = held[0].b;
+            in.tile = held[0].tile;
+            in.idx = held[0].idx;
+            if (held[0].b >= 0) stage_store(stage, free_slot, held[0].p);
         }
 #pragma unroll
         for (int q = 0; q + 1 < PIPE_DEPTH; ++q) held[q] = held[q + 1];
@@ -151,8 +201,17 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
         }
     }
 
-    // ---- drain
+    // ---- drain, oldest first
     resolve_posted(posted, L, X, X.set_base + posted_idx, prod.scales(L, posted_idx), S);
+#pragma unroll
+    for (int q = 0; q < STAGE_DEPTH; ++q) {
+        if (staged[q].b >= 0) {
+            float4 pv_old[SUBROWS];
+            stage_load(stage, staged[q].slot, pv_old);
+            finish_uniform(pv_old, staged[q].tile, TILE, staged[q].b, 0ull, prod.err_tile(staged[q].idx, staged[q].tile),
+                           L, X, X.set_base + staged[q].idx, S);
+        }
+    }
 #pragma unroll
     for (int q = 0; q < PIPE_DEPTH; ++q) {
         if (held[q].b >= 0)
@@ -193,10 +252,11 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void k_worker_uniform(Layout L, ScratchRef R, WorkerArgs A, int n_workers)
 {
     const Scratch X = open_call(R);
-    __shared__ TileShared S;
+    __shared__ SyncShared S;
+    __shared__ float stage[STAGE_DEPTH * TILE];     // 48 KiB: three workgroups per CU, as the registers allow
     WorkerProducer<MOM> prod;
     prod.A = A;
-    persistent_uniform(L, X, prod, n_workers, S);
+    persistent_uniform(L, X, prod, n_workers, S, stage);
 }
 
 // Uniform tiles of all workers, one workgroup per (tile, worker): the same
@@ -212,7 +272,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void k_worker_uniform_direct(Layout L, ScratchRef R, WorkerArgs A)
 {
     const Scratch X = open_call(R);
-    __shared__ TileShared S;
+    __shared__ SyncShared S;
     const int32_t tile = L.uniform_tiles[blockIdx.x];
     const int worker = blockIdx.y;
     constexpr int n_valid = TILE;

@@ -289,10 +289,11 @@ def test_beyond_2p31_elements_sampled():
 
 @pytest.mark.parametrize("persistent", [True, False])
 def test_blocks_around_the_one_pass_limits(persistent):
-    """Blocks whose tile counts sit on both sides of every default one-pass limit (768, 1024, 1152,
-    1536 tiles), some ending off the tile grid, with the plan's own limits: each block must take the
+    """Blocks whose tile counts sit on both sides of every default one-pass limit (768 and 1024 tiles
+    for the kernels with one workgroup per tile, 2304 for the persistent one) and of earlier ones
+    (1152), some ending off the tile grid, with the plan's own limits: each block must take the
     route its size calls for and give the oracle's result either way.  All blocks go through the oracle."""
-    tiles = [767, 768, 769, 1023, 1024, 1025, 1151, 1152, 1153, 1535, 1536, 1537]
+    tiles = [767, 768, 769, 1023, 1024, 1025, 1151, 1152, 1153, 2303, 2304, 2305]
     rng = np.random.default_rng(12)
     sizes = [t * 4096 + int(rng.integers(-3, 4)) for t in tiles]
     order = rng.permutation(len(sizes))
