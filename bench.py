@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--fuse-limit", type=int, default=-1, help="override the plan's one-pass block limit")
     ap.add_argument("--spin-limit", type=int, default=-1, help="override the plan's wait budget")
     ap.add_argument("--persistent", type=int, default=-1, help="1/0: force the persistent worker kernel on/off")
+    ap.add_argument("--lazy", action="store_true",
+                    help="deferred residual correction for blocks beyond the one-pass limit (ef_plan_set_lazy)")
     ap.add_argument("--variant", default="sgdm", choices=["sgdm", "sgd", "fused", "wd"],
                     help="sgdm: Algorithm 4 (the default, the metric's configuration); sgd: Algorithm 3 worker "
                          "without a momentum buffer; fused: one message per worker (Section 4.2); wd: parameter "
@@ -103,6 +105,8 @@ def main():
         plan.tune(args.fuse_limit, args.spin_limit)
     if args.persistent >= 0:
         plan.set_persistent(args.persistent)
+    if args.lazy:
+        plan.set_lazy(True)
 
     # gradient sets resident in HBM, cycled over the steps
     n_sets = args.grad_sets or max(1, min(args.steps + args.warmup, int(64e9 // (4.0 * d * M)), 4))
@@ -239,6 +243,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": dict(w.describe(), variant=variant, launch="hip graph replay" if args.graph else "eager calls",
+                       deferred_residual_correction=bool(plan.lazy),
                        grad_sets_in_hbm=n_sets, elements_counted="(M+1)*d per step",
                        d_per_step_Gelem_s=round(d / (ms_per_step * 1e-3) / 1e9, 3)),
         "roofline": {

@@ -127,6 +127,45 @@ int ef_plan_set_persistent(ef_plan *plan, int on);
 int ef_plan_is_persistent(const ef_plan *plan);
 
 /*
+ * Deferred residual correction, off by default.  Algorithm 4 ends a worker's
+ * (and the server's) step with e <- p - Delta.  For a block of more than
+ * fuse_limit tiles the scale of Delta is known only after the first kernel
+ * has passed over the whole block, so that kernel leaves p in the residual
+ * buffer and a second one reads it back and writes e (8 more bytes of HBM
+ * traffic per element).  With on = 1 that second pass is not run: the buffer
+ * keeps p over the whole tiles of such blocks, the plan remembers the block's
+ * scale, and the next ef_worker_step* / ef_server_step on that buffer forms
+ * e = p - Delta as it loads the data: the same fp32 subtraction on the same
+ * operands, so payloads, momentum and parameters of every step are bit-equal
+ * to the default mode's.  What changes for the caller:
+ *   - between calls the residual buffers are opaque where large blocks lie;
+ *     ef_flush writes the true e into them (before reading, checkpointing, or
+ *     handing a buffer to another plan or to another worker index);
+ *   - worker i's buffer must stay worker i's (the remembered scales are kept
+ *     per worker index and for the server), and the plan must see every step
+ *     of it;
+ *   - ef_plan_tune (fuse_limit), ef_plan_set_persistent and ef_plan_set_lazy
+ *     return EF_ERR_ARG while any buffer is waiting for its correction, since
+ *     they change which blocks count as large: call ef_flush first.
+ * Blocks of at most fuse_limit tiles, and the parts of large blocks that
+ * share a tile with another block, are corrected in the call as before.
+ * ef_plan_set_lazy synchronises the device.
+ */
+int ef_plan_set_lazy(ef_plan *plan, int on);
+int ef_plan_is_lazy(const ef_plan *plan);
+
+/*
+ * Makes the deferred corrections now: err (device, [n_workers][state_stride],
+ * may be NULL) and server_err (device, [d], may be NULL) are the buffers the
+ * plan's last worker / server calls wrote; afterwards they hold e of
+ * Algorithm 4 everywhere and the next call takes them as they are.  Buffers
+ * with nothing pending are left untouched, so the call is harmless in the
+ * default mode.  Enqueues on `stream`; EF_ERR_ARG for n_workers outside
+ * [1, max_workers] or a bad stride, EF_ERR_ALIGN for a pointer off 16 bytes.
+ */
+int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_stride, float *server_err, void *stream);
+
+/*
  * How often the most recent ef_worker_step / ef_server_step on this plan left
  * the one-pass route at run time: tiles whose wait for the block scale was not
  * taken or ran out (p parked, finished by the second pass) and blocks whose

@@ -23,7 +23,7 @@ EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1
 EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
-    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_flush", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
     "ef_sign_words", "ef_worker_step", "ef_worker_step_sgd", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
     "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused", "ef_compressor_quality",
 )
@@ -60,6 +60,12 @@ def lib():
     L.ef_plan_set_persistent.argtypes = [vp, c_int]
     L.ef_plan_is_persistent.restype = c_int
     L.ef_plan_is_persistent.argtypes = [vp]
+    L.ef_plan_set_lazy.restype = c_int
+    L.ef_plan_set_lazy.argtypes = [vp, c_int]
+    L.ef_plan_is_lazy.restype = c_int
+    L.ef_plan_is_lazy.argtypes = [vp]
+    L.ef_flush.restype = c_int
+    L.ef_flush.argtypes = [vp, c_int, vp, i64, vp, vp]
     L.ef_plan_last_fallbacks.restype = c_int
     L.ef_plan_last_fallbacks.argtypes = [vp, ctypes.POINTER(ctypes.c_uint), ctypes.POINTER(ctypes.c_uint)]
     L.ef_plan_fuse_limit.restype = c_int
@@ -160,6 +166,14 @@ class Plan:
     def persistent(self):
         return bool(lib().ef_plan_is_persistent(self._h))
 
+    def set_lazy(self, on):
+        """Deferred residual correction for blocks larger than fuse_limit (see ef_plan_set_lazy)."""
+        _check(lib().ef_plan_set_lazy(self._h, int(bool(on))))
+
+    @property
+    def lazy(self):
+        return bool(lib().ef_plan_is_lazy(self._h))
+
     def last_fallbacks(self):
         """(parked_tiles, late_blocks) of the most recent worker/server call."""
         a, b = ctypes.c_uint(0), ctypes.c_uint(0)
@@ -196,6 +210,29 @@ def ef_plan_set_persistent(plan, on):
 
 def ef_plan_is_persistent(plan):
     return plan.persistent
+
+
+def ef_plan_set_lazy(plan, on):
+    plan.set_lazy(on)
+
+
+def ef_plan_is_lazy(plan):
+    return plan.lazy
+
+
+def ef_flush(plan, err=None, server_err=None, stream=None):
+    """Writes the deferred corrections into err ([n][>=d] or [d], or None) and server_err ([d], or None)."""
+    n, ss, ep = 1, plan.d, None
+    if err is not None:
+        n = 1 if err.dim() == 1 else err.shape[0]
+        ss = _stride(err, plan.d, "err")
+        ep = _ptr(err, torch.float32, "err")
+    sp = None
+    if server_err is not None:
+        if server_err.numel() != plan.d:
+            raise TypeError("server_err must hold d entries")
+        sp = _ptr(server_err, torch.float32, "server_err")
+    _check(lib().ef_flush(plan._h, n, ep, ss, sp, _stream_ptr(stream)))
 
 
 def ef_plan_last_fallbacks(plan):

@@ -26,7 +26,15 @@ struct ef_plan {
         uint32_t n_late;            // blocks whose scale the first kernels never write
         uint32_t *d_static;         // [2*ntiles] capacity
         int32_t *d_late;            // [min(B, 2*ntiles)] capacity
+        // deferred correction: position of every block in d_late if it is larger than fuse_limit, else -1;
+        // the whole tiles of those blocks (left out of d_static while the mode is on)
+        int32_t *d_late_index;      // [B]
+        int32_t *d_lazy_tiles;      // [ntiles] capacity
+        uint32_t n_lazy_tiles;
     } role[2];
+    int lazy;                       // deferred correction on (ef_plan_set_lazy)
+    float *d_lazy_scales;           // [nsets][lazy_stride]
+    int lazy_stride;
     int32_t lim_persistent, lim_direct, lim_server;   // automatic limits
     int32_t user_fuse_limit;        // >= 0: set through ef_plan_tune, overrides the automatic limits
     // device allocations owned by the plan
@@ -94,11 +102,14 @@ void destroy_device(ef_plan *p)
     if (p->d_ready) (void)hipFree(p->d_ready);
     if (p->d_list_cnt) (void)hipFree(p->d_list_cnt);
     if (p->d_state) (void)hipFree(p->d_state);
+    if (p->d_lazy_scales) (void)hipFree(p->d_lazy_scales);
     if (p->d_defer_list) (void)hipFree(p->d_defer_list);
     if (p->d_fin_list) (void)hipFree(p->d_fin_list);
     for (auto &r : p->role) {
         if (r.d_static) (void)hipFree(r.d_static);
         if (r.d_late) (void)hipFree(r.d_late);
+        if (r.d_late_index) (void)hipFree(r.d_late_index);
+        if (r.d_lazy_tiles) (void)hipFree(r.d_lazy_tiles);
     }
     if (p->d_mixed) (void)hipFree(p->d_mixed);
     if (p->d_uniform) (void)hipFree(p->d_uniform);
@@ -126,12 +137,15 @@ bool has_uniform_tile(const ef_plan *p, int64_t b)
 int upload_static_list(ef_plan *p, ef_plan::Role &r)
 {
     std::vector<uint32_t> items;
-    std::vector<int32_t> late;
+    std::vector<int32_t> late, late_index((size_t)p->L.B, -1), lazy_tiles;
     const int64_t *o = p->offs_host.data();
     for (int64_t b = 0; b < p->L.B; ++b) {
         const int64_t n = tiles_of_block(p, b);
         if (n < 2) continue;
-        if (n > r.fuse_limit || !has_uniform_tile(p, b)) late.push_back((int32_t)b);
+        if (n > r.fuse_limit || !has_uniform_tile(p, b)) {
+            if (n > r.fuse_limit && has_uniform_tile(p, b)) late_index[(size_t)b] = (int32_t)late.size();
+            late.push_back((int32_t)b);
+        }
     }
     for (int32_t t = 0; t < p->L.ntiles; ++t) {
         const int64_t start = (int64_t)t * ef::TILE, end = start + ef::TILE;
@@ -140,7 +154,10 @@ int upload_static_list(ef_plan *p, ef_plan::Role &r)
         if (fb == lb) {
             // a full tile parks p only for blocks beyond fuse_limit, the ragged last tile always
             const bool open = (o[fb] < start) || (o[fb + 1] > end);
-            if (open && (!full || tiles_of_block(p, fb) > r.fuse_limit)) items.push_back(((uint32_t)t << 1) | 0u);
+            if (open && full && tiles_of_block(p, fb) > r.fuse_limit && p->lazy)
+                lazy_tiles.push_back(t);        // deferred: corrected when the buffer is next loaded
+            else if (open && (!full || tiles_of_block(p, fb) > r.fuse_limit))
+                items.push_back(((uint32_t)t << 1) | 0u);
         } else {
             if (o[fb] < start) items.push_back(((uint32_t)t << 1) | 0u);
             if (o[lb + 1] > end) items.push_back(((uint32_t)t << 1) | 1u);
@@ -148,6 +165,10 @@ int upload_static_list(ef_plan *p, ef_plan::Role &r)
     }
     r.n_late = (uint32_t)late.size();
     r.n_static = (uint32_t)items.size();
+    r.n_lazy_tiles = (uint32_t)lazy_tiles.size();
+    EF_HIP(hipMemcpy(r.d_late_index, late_index.data(), sizeof(int32_t) * late_index.size(), hipMemcpyHostToDevice));
+    if (!lazy_tiles.empty())
+        EF_HIP(hipMemcpy(r.d_lazy_tiles, lazy_tiles.data(), sizeof(int32_t) * lazy_tiles.size(), hipMemcpyHostToDevice));
     if (!late.empty()) EF_HIP(hipMemcpy(r.d_late, late.data(), sizeof(int32_t) * late.size(), hipMemcpyHostToDevice));
     if (!items.empty())
         EF_HIP(hipMemcpy(r.d_static, items.data(), sizeof(uint32_t) * items.size(), hipMemcpyHostToDevice));
@@ -214,7 +235,12 @@ int build_device(ef_plan *p)
     for (auto &r : p->role) {
         EF_HIP(hipMalloc(&r.d_static, sizeof(uint32_t) * 2 * (size_t)ntiles));
         EF_HIP(hipMalloc(&r.d_late, sizeof(int32_t) * max_cross));
+        EF_HIP(hipMalloc(&r.d_late_index, sizeof(int32_t) * (size_t)B));
+        EF_HIP(hipMalloc(&r.d_lazy_tiles, sizeof(int32_t) * (size_t)ntiles));
     }
+    p->lazy_stride = (int)max_cross;
+    EF_HIP(hipMalloc(&p->d_lazy_scales, sizeof(float) * max_cross * nsets));
+    EF_HIP(hipMemset(p->d_lazy_scales, 0, sizeof(float) * max_cross * nsets));
     {
         std::vector<int32_t> mixed, uniform;
         for (int32_t t = 0; t < ntiles; ++t) {
@@ -244,6 +270,8 @@ int build_device(ef_plan *p)
     p->X.fin_list = p->d_fin_list;
     p->X.list_cnt = p->d_list_cnt;
     p->X.state = p->d_state;
+    p->X.lazy_scales = p->d_lazy_scales;
+    p->X.lazy_stride = p->lazy_stride;
     // A block finishes in one pass if its tiles fit twice over into the
     // workgroups resident at once (see ef_device.h).
     {
@@ -308,6 +336,8 @@ ef::Layout role_layout(const ef_plan *plan, int role)
 {
     ef::Layout L = plan->L;
     L.fuse_limit = plan->role[role].fuse_limit;
+    L.lazy = plan->lazy;
+    L.late_index = plan->role[role].d_late_index;
     return L;
 }
 
@@ -323,7 +353,7 @@ int launch_second_pass(const ef_plan *plan, int role, const CallScratch &c, int 
                        c.X, (const uint32_t *)r.d_static, (int)r.n_static, nsets, err, err_stride,
                        (const float *)scales, scales_stride);
     EF_HIP(hipGetLastError());
-    hipLaunchKernelGGL(ef::k_advance, dim3(1), dim3(64), 0, s, plan->d_state, c.X.set_base, nsets);
+    hipLaunchKernelGGL(ef::k_advance, dim3(1), dim3(64), 0, s, plan->d_state, c.X.set_base, nsets, plan->lazy);
     EF_HIP(hipGetLastError());
     return EF_OK;
 }
@@ -370,12 +400,15 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_ready = nullptr;
     p->d_list_cnt = nullptr;
     p->d_state = nullptr;
+    p->d_lazy_scales = nullptr;
+    p->lazy = 0;
     p->d_defer_list = nullptr;
     p->d_fin_list = nullptr;
     for (auto &r : p->role) {
         r.d_static = nullptr;
         r.d_late = nullptr;
-        r.n_static = r.n_late = 0;
+        r.d_late_index = r.d_lazy_tiles = nullptr;
+        r.n_static = r.n_late = r.n_lazy_tiles = 0;
         r.fuse_limit = 0;
     }
     p->d_mixed = p->d_uniform = nullptr;
@@ -402,12 +435,64 @@ int ef_plan_destroy(ef_plan *plan)
     return EF_OK;
 }
 
+// Residual buffers whose large blocks still hold uncorrected p (deferred correction): the lists
+// that say which blocks those are must not change under them.
+static int residuals_pending(ef_plan *plan, bool *pending)
+{
+    ef::CallState st;
+    EF_HIP(hipDeviceSynchronize());
+    EF_HIP(hipMemcpy(&st, plan->d_state, sizeof st, hipMemcpyDeviceToHost));
+    *pending = st.worker_pending != 0ull || st.server_pending != 0u;
+    return EF_OK;
+}
+
+int ef_plan_set_lazy(ef_plan *plan, int on)
+{
+    if (!plan) return EF_ERR_NULL;
+    bool pending = false;
+    int rc = residuals_pending(plan, &pending);
+    if (rc) return rc;
+    if (pending) return EF_ERR_ARG;
+    plan->lazy = on ? 1 : 0;
+    return refresh_limits(plan);
+}
+
+int ef_plan_is_lazy(const ef_plan *plan) { return plan ? plan->lazy : 0; }
+
+int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_stride, float *server_err, void *stream)
+{
+    if (!plan) return EF_ERR_NULL;
+    if (err && (n_workers < 1 || n_workers > plan->max_workers || state_stride < plan->L.d || state_stride % 4))
+        return EF_ERR_ARG;
+    if ((err && !aligned(err, 16)) || (server_err && !aligned(server_err, 16))) return EF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int role = 0; role < 2; ++role) {
+        float *buf = role == 0 ? err : server_err;
+        if (!buf) continue;
+        const ef_plan::Role &r = plan->role[role];
+        const int nsets = role == 0 ? n_workers : 1;
+        const CallScratch c = next_call(plan, role == 0 ? 0 : plan->max_workers, nsets);
+        if (r.n_lazy_tiles) {
+            hipLaunchKernelGGL(ef::k_flush, dim3(r.n_lazy_tiles, (unsigned)nsets), dim3(ef::THREADS), 0, s,
+                               role_layout(plan, role), c.X, (const int32_t *)r.d_lazy_tiles, (int)r.n_lazy_tiles, buf,
+                               role == 0 ? state_stride : (int64_t)0);
+            EF_HIP(hipGetLastError());
+        }
+        hipLaunchKernelGGL(ef::k_flush_done, dim3(1), dim3(64), 0, s, plan->d_state, c.X.set_base, nsets);
+        EF_HIP(hipGetLastError());
+    }
+    return EF_OK;
+}
+
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
 {
     if (!plan) return EF_ERR_NULL;
-    EF_HIP(hipDeviceSynchronize());
     if (spin_limit >= 0) plan->spin_limit = spin_limit;
     if (fuse_limit >= 0) {
+        bool pending = false;
+        int rc = residuals_pending(plan, &pending);
+        if (rc) return rc;
+        if (pending) return EF_ERR_ARG;
         plan->user_fuse_limit = fuse_limit;
         return refresh_limits(plan);
     }
@@ -437,7 +522,10 @@ int ef_plan_last_fallbacks(ef_plan *plan, unsigned int *parked_tiles, unsigned i
 int ef_plan_set_persistent(ef_plan *plan, int on)
 {
     if (!plan) return EF_ERR_NULL;
-    EF_HIP(hipDeviceSynchronize());
+    bool pending = false;
+    int rc = residuals_pending(plan, &pending);
+    if (rc) return rc;
+    if (pending) return EF_ERR_ARG;
     plan->persistent = on < 0 ? plan->persistent_auto : (on ? 1 : 0);
     plan->persistent_forced = on > 0 ? 1 : 0;
     return refresh_limits(plan);

@@ -63,7 +63,13 @@ __global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, ScratchRe
         const int64_t b = late_blocks[blockIdx.x % n_late];
         const int w = blockIdx.x / n_late;
         const double total = sum_block_partials(L, b, set_part(X, L, X.set_base + w), red);
-        if (threadIdx.x == 0) scales[(int64_t)w * scales_stride + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+        if (threadIdx.x == 0) {
+            const float sc = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+            scales[(int64_t)w * scales_stride + b] = sc;
+            // remembered for the deferred correction of the block's residual
+            if (L.lazy && L.late_index[b] >= 0)
+                X.lazy_scales[(int64_t)(X.set_base + w) * X.lazy_stride + L.late_index[b]] = sc;
+        }
         return;
     }
     const unsigned n = *X.fin_cnt;
@@ -110,14 +116,46 @@ __global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, ScratchRe
 }
 
 // The call is over: count it and flip the tags of the sets it used (one thread).
-__global__ void k_advance(CallState *state, int set_base, int nsets)
+__global__ void k_advance(CallState *state, int set_base, int nsets, int lazy)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const unsigned long long used = nsets >= 64 ? ~0ull : ((1ull << nsets) - 1ull);
         state->calls = state->calls + 1u;
-        if (set_base == 0)
-            state->worker_tags ^= nsets >= 64 ? ~0ull : ((1ull << nsets) - 1ull);
-        else
+        if (set_base == 0) {
+            state->worker_tags ^= used;
+            // with the deferred correction on, the large blocks of these sets now hold p
+            state->worker_pending = lazy ? (state->worker_pending | used) : (state->worker_pending & ~used);
+        } else {
             state->server_tag ^= 1u;
+            state->server_pending = lazy ? 1u : 0u;
+        }
+    }
+}
+
+// Deferred correction made now (ef_flush): e <- p - Delta on the whole tiles of the blocks larger
+// than fuse_limit, for the sets whose buffers still hold p.  One workgroup per (tile, set).
+__global__ __launch_bounds__(THREADS) void k_flush(Layout L, ScratchRef R, const int32_t *tiles, int n_tiles,
+                                                   float *err, int64_t err_stride)
+{
+    const Scratch X = open_call(R);
+    const int32_t tile = tiles[blockIdx.x];
+    const int set = X.set_base + blockIdx.y;
+    float *e = err + (int64_t)blockIdx.y * err_stride + (int64_t)tile * TILE;
+    float4 v[SUBROWS];
+    if (!((X.pending >> blockIdx.y) & 1ull)) return;
+    load_tile(e, v, TILE);
+    correct_loaded_residual(v, L, tile, X, set);
+    store_tile(e, v, TILE);
+}
+
+__global__ void k_flush_done(CallState *state, int set_base, int nsets)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const unsigned long long used = nsets >= 64 ? ~0ull : ((1ull << nsets) - 1ull);
+        if (set_base == 0)
+            state->worker_pending &= ~used;
+        else
+            state->server_pending = 0u;
     }
 }
 

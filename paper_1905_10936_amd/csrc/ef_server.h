@@ -42,6 +42,7 @@ void k_server_uniform(Layout L, ScratchRef R, ServerArgs A, int set)
     Posted P;
     float4 tv[SUBROWS];
     load_tile(te, tv, n_valid);
+    correct_loaded_residual(tv, L, tile, X, set);
 
     float acc[SUBROWS][4];
 #pragma unroll

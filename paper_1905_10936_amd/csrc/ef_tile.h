@@ -76,6 +76,10 @@ struct Layout {
     const int32_t *tile_lb;     // [ntiles] block holding the tile's last valid element
     const int32_t *mixed_tiles;   // [n_mixed] ascending
     const int32_t *uniform_tiles; // [n_uniform] ascending
+    // Deferred correction (see Scratch::lazy_scales): on or off, and for every block its position
+    // among the blocks larger than fuse_limit (-1 for the others).
+    int32_t lazy;
+    const int32_t *late_index;    // [B]
 };
 
 // What changes from call to call lives in device memory, so that the kernel
@@ -87,6 +91,8 @@ struct CallState {
     unsigned int calls;
     unsigned int server_tag;            // bit 0
     unsigned long long worker_tags;     // bit i: worker i
+    unsigned long long worker_pending;  // bit i: worker i's residual buffer holds uncorrected p in its large blocks
+    unsigned int server_pending;        // bit 0: the same for the server residual
 };
 
 // Kernel argument: the plan's scratch.  A "set" is one worker, or the server.
@@ -96,6 +102,8 @@ struct ScratchRef {
     unsigned long long *defer_list;
     unsigned long long *fin_list;
     unsigned int *list_cnt;             // [6]: defer_cnt[2], fin_cnt[2], ticket[2]; a call uses those of its parity
+    float *lazy_scales;                 // [nsets][lazy_stride] last scale of every block larger than fuse_limit
+    int lazy_stride;
     const CallState *state;
     int set_base;                       // first set this call uses (0 for workers, max_workers for the server)
     int spin_limit;
@@ -115,6 +123,14 @@ struct Scratch {
     int set_base;               // first set this call uses (0 for workers, max_workers for the server)
     int spin_limit;             // polls before a waiting workgroup gives up and parks p
     unsigned int *next_cnt;     // the three list counters of the next call (zeroed by this call's last kernel)
+    // Deferred correction.  A block larger than fuse_limit cannot have its residual finished in
+    // the first kernel; instead of a second pass over it (p written, read back, e written: 8 more
+    // bytes per element), the residual buffer keeps p, the block's scale is remembered here, and
+    // the next call that loads the buffer subtracts the decoded value on the fly: the same fp32
+    // operation on the same operands, one call later.  `pending` says for which sets that is due.
+    float *lazy_scales;
+    int lazy_stride;
+    unsigned long long pending;  // bit i: set (set_base + i)
 };
 
 __device__ __forceinline__ unsigned uniform_u32(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
@@ -138,6 +154,14 @@ __device__ __forceinline__ Scratch open_call(const ScratchRef &R)
         X.tags = ~(((unsigned long long)uniform_u32((unsigned)(t >> 32)) << 32) | uniform_u32((unsigned)t));
     } else {
         X.tags = (unsigned long long)(uniform_u32(R.state->server_tag) ^ 1u);
+    }
+    X.lazy_scales = R.lazy_scales;
+    X.lazy_stride = R.lazy_stride;
+    if (R.set_base == 0) {
+        const unsigned long long t = R.state->worker_pending;
+        X.pending = ((unsigned long long)uniform_u32((unsigned)(t >> 32)) << 32) | uniform_u32((unsigned)t);
+    } else {
+        X.pending = (unsigned long long)(uniform_u32(R.state->server_pending) & 1u);
     }
     X.epoch = calls % 0xffffffffu + 1u;     // never 0: 0 marks "no scale posted"
     X.set_base = R.set_base;
@@ -682,6 +706,20 @@ __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layou
     }
     store_tile(err_tile, p, n_valid);
     __syncthreads();            // S.val is free again
+}
+
+// Deferred correction of a uniform tile's residual as loaded (see Scratch::lazy_scales): if the
+// tile's block is larger than fuse_limit and the set's last call left p in the buffer, subtract
+// what that call's payload stood for.  Called by every thread with the same tile and set.
+__device__ __forceinline__ void correct_loaded_residual(float4 (&e)[SUBROWS], const Layout &L, int32_t tile,
+                                                        const Scratch &X, int set)
+{
+    if (!L.lazy || !((X.pending >> (set - X.set_base)) & 1ull)) return;
+    const int32_t li = L.late_index[L.tile_fb[tile]];
+    if (li < 0) return;
+    const float s = X.lazy_scales[(int64_t)set * X.lazy_stride + li];
+#pragma unroll
+    for (int k = 0; k < SUBROWS; ++k) residual4(e[k], s);
 }
 
 // Uniform tile (inside one block b): sign words and the tile's fp64 sum.

@@ -223,6 +223,7 @@ __device__ __forceinline__ void persistent_uniform(const Layout &L, const Scratc
 template <bool MOM>
 struct WorkerProducer {
     WorkerArgs A;
+    const Scratch *X;
     float4 gv[SUBROWS], mv[SUBROWS], ev[SUBROWS];
 
     __device__ __forceinline__ uint64_t *signs(const Layout &L, int idx) const { return A.signs + (int64_t)idx * A.signs_stride; }
@@ -238,8 +239,9 @@ struct WorkerProducer {
         if (MOM) load_tile(A.mom + (int64_t)idx * A.state_stride + tile_start, mv, TILE);
         load_tile(A.err + (int64_t)idx * A.state_stride + tile_start, ev, TILE);
     }
-    __device__ __forceinline__ void produce(const Layout &, int idx, int32_t tile, float4 (&p)[SUBROWS])
+    __device__ __forceinline__ void produce(const Layout &L, int idx, int32_t tile, float4 (&p)[SUBROWS])
     {
+        correct_loaded_residual(ev, L, tile, *X, X->set_base + idx);
         worker_values<MOM>(gv, mv, ev, A.mu, A.r);
         if (MOM) store_tile(A.mom + (int64_t)idx * A.state_stride + (int64_t)tile * TILE, mv, TILE);
 #pragma unroll
@@ -256,6 +258,7 @@ void k_worker_uniform(Layout L, ScratchRef R, WorkerArgs A, int n_workers)
     __shared__ float stage[STAGE_DEPTH * TILE];     // 48 KiB: three workgroups per CU, as the registers allow
     WorkerProducer<MOM> prod;
     prod.A = A;
+    prod.X = &X;
     persistent_uniform(L, X, prod, n_workers, S, stage);
 }
 
@@ -285,6 +288,7 @@ void k_worker_uniform_direct(Layout L, ScratchRef R, WorkerArgs A)
     load_tile(g, gv, n_valid);
     if (MOM) load_tile(m, mv, n_valid);
     load_tile(e, pv, n_valid);
+    correct_loaded_residual(pv, L, tile, X, worker);
     worker_values<MOM>(gv, mv, pv, A.mu, A.r);
     if (MOM) store_tile(m, mv, n_valid);
     float *scales_out = A.scales + (int64_t)worker * A.scales_stride;

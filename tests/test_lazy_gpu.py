@@ -1,0 +1,292 @@
+"""Deferred residual correction (ef_plan_set_lazy): a plan in that mode must
+produce, step after step, the bits of a plan in the default mode fed the same
+gradients: sign words, scales, momentum and parameters equal at every step, and
+the residual buffers equal once ef_flush has run.  The default-mode plan is
+itself checked against the CPU oracle at every step (tests/parity_util.py: sign
+words and momentum bit-exact, scales within 1e-6 relative, residuals and
+parameters bit-exact where the scale is), so the chain oracle == default ==
+deferred holds to that bar.
+
+The layouts put the one-pass limit (fuse_limit) below the size of some blocks,
+so that those blocks' whole tiles take the deferred route; the tests also check
+that the mode really was in effect (the buffer differs from e before the
+flush), that worker counts may change between calls, and that the settings
+which would invalidate pending corrections are refused until ef_flush.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_1905_10936_amd as ef
+from tests.parity_util import F, GpuState, synced_step, to_np
+
+pytestmark = pytest.mark.gpu
+
+TILE = 4096
+
+# sizes in elements; with fuse_limit 3 the blocks of 5+ tiles are "large"
+SIZES = {
+    "ragged_large": [5 * TILE + 17, 3, 1, 700, 12 * TILE - 5, TILE, 3 * TILE, 2 * TILE + 1, 7 * TILE + 2048, 33],
+    "aligned_large": [4 * TILE, 8 * TILE, TILE, 2 * TILE, 6 * TILE],
+    "one_large_block": [9 * TILE + 1234],
+    "tiny_then_large": [1] * 70 + [10 * TILE + 1, 5, 4 * TILE + 4095],
+}
+
+
+def _offs(sizes):
+    return np.concatenate([[0], np.cumsum(np.asarray(sizes, dtype=np.int64))])
+
+
+def _raw_step(st, variant, mu, eta_prev, eta, n=None):
+    n = st.M if n is None else n
+    if st.fused:                 # as tests/parity_util.py poisons the padding bytes of the messages
+        st.wmsg.fill_(0xA5)
+        st.smsg.fill_(0xA5)
+    if variant == "sgd":
+        ef.ef_worker_step_sgd(st.plan, st.g[:n], st.e[:n], eta_prev, eta, st.ws[:n], st.wc[:n])
+    elif st.fused:
+        ef.ef_worker_step_fused(st.plan, st.g[:n], st.m[:n], st.e[:n], mu, eta_prev, eta, st.wmsg[:n])
+    else:
+        ef.ef_worker_step(st.plan, st.g[:n], st.m[:n], st.e[:n], mu, eta_prev, eta, st.ws[:n], st.wc[:n])
+    if st.fused and variant != "sgd":
+        ef.ef_server_step_fused(st.plan, n, st.wmsg[:n], st.te, eta_prev, eta, st.smsg)
+        ef.ef_apply_fused(st.plan, st.x, st.smsg, eta)
+    else:
+        ef.ef_server_step(st.plan, n, st.ws[:n], st.wc[:n], st.te, eta_prev, eta, st.ss, st.sc)
+        ef.ef_apply(st.plan, st.x, st.ss, st.sc, eta)
+    torch.cuda.synchronize()
+
+
+def _same_bits(a, b, what):
+    a, b = to_np(a), to_np(b)
+    a = a.view(np.uint32) if a.dtype == np.float32 else a
+    b = b.view(np.uint32) if b.dtype == np.float32 else b
+    assert np.array_equal(a, b), "%s: %d entries differ" % (what, int((a != b).sum()))
+
+
+def _compare_outputs(lazy, ref, tag, n=None):
+    n = lazy.M if n is None else n
+    if lazy.fused:
+        _same_bits(lazy.wmsg[:n], ref.wmsg[:n], tag + " worker messages")
+        _same_bits(lazy.smsg, ref.smsg, tag + " server message")
+    else:
+        _same_bits(lazy.ws[:n], ref.ws[:n], tag + " worker sign words")
+        _same_bits(lazy.wc[:n], ref.wc[:n], tag + " worker scales")
+        _same_bits(lazy.ss, ref.ss, tag + " server sign words")
+        _same_bits(lazy.sc, ref.sc, tag + " server scales")
+    _same_bits(lazy.m, ref.m, tag + " momentum")
+    _same_bits(lazy.x, ref.x, tag + " parameters")
+
+
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("route", ["one_pass", "direct"])
+@pytest.mark.parametrize("layout", sorted(SIZES))
+def test_deferred_equals_default_and_oracle(layout, route, fused):
+    offs = _offs(SIZES[layout])
+    d = int(offs[-1])
+    M, mu = 3, 0.9
+    rng = np.random.default_rng(4242)
+    x0 = rng.standard_normal(d).astype(F)
+    ref = GpuState(offs, M, x0=x0, route=route, fused=fused, pad=1)
+    lazy = GpuState(offs, M, x0=x0, route=route, fused=fused, pad=1)
+    for st in (ref, lazy):
+        st.plan.tune(fuse_limit=3)
+    lazy.plan.set_lazy(True)
+    assert lazy.plan.lazy and not ref.plan.lazy
+    eta_prev = 0.0
+    for t in range(4):
+        eta = [0.4, 0.4, 0.1, 0.05][t]
+        g = rng.standard_normal((M, d)).astype(F)
+        g[rng.random((M, d)) < 0.05] = 0.0
+        ref.set_grads(g)
+        lazy.set_grads(g)
+        tag = "%s/%s step %d" % (layout, route, t)
+        synced_step(ref, mu, eta_prev, eta, None, tag)          # default mode against the oracle
+        _raw_step(lazy, "sgdm", mu, eta_prev, eta)
+        _compare_outputs(lazy, ref, tag)
+        eta_prev = eta
+    # the mode was in effect: before the flush the buffers hold p, not e, in the large blocks
+    assert not np.array_equal(to_np(lazy.e), to_np(ref.e))
+    assert not np.array_equal(to_np(lazy.te), to_np(ref.te))
+    with pytest.raises(ef.EfError):
+        lazy.plan.tune(fuse_limit=5)
+    with pytest.raises(ef.EfError):
+        lazy.plan.set_persistent(route != "one_pass")
+    with pytest.raises(ef.EfError):
+        lazy.plan.set_lazy(False)
+    ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+    torch.cuda.synchronize()
+    _same_bits(lazy.e, ref.e, layout + " residuals after flush (padding columns included)")
+    _same_bits(lazy.te, ref.te, layout + " server residual after flush")
+    # a second flush changes nothing, and the settings are accepted again
+    ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+    torch.cuda.synchronize()
+    _same_bits(lazy.e, ref.e, layout + " residuals after a second flush")
+    lazy.plan.tune(fuse_limit=3)
+    # and the run goes on from flushed buffers
+    g = rng.standard_normal((M, d)).astype(F)
+    for st in (ref, lazy):
+        st.set_grads(g)
+    synced_step(ref, mu, eta_prev, 0.05, None, layout + " after flush")
+    _raw_step(lazy, "sgdm", mu, eta_prev, 0.05)
+    _compare_outputs(lazy, ref, layout + " after flush")
+    for st in (ref, lazy):
+        st.plan.close()
+
+
+@pytest.mark.parametrize("route", ["one_pass", "direct"])
+def test_deferred_momentum_free_and_changing_worker_count(route):
+    """Algorithm 3 calls, with the number of workers changing from call to call: a worker left out
+    of a call keeps its pending correction until the next call that includes it."""
+    offs = _offs(SIZES["ragged_large"])
+    d = int(offs[-1])
+    M = 4
+    rng = np.random.default_rng(99)
+    x0 = rng.standard_normal(d).astype(F)
+    ref = GpuState(offs, M, x0=x0, route=route)
+    lazy = GpuState(offs, M, x0=x0, route=route)
+    for st in (ref, lazy):
+        st.plan.tune(fuse_limit=3)
+    lazy.plan.set_lazy(True)
+    eta_prev = 0.0
+    for t, n in enumerate([4, 2, 3, 1, 4]):
+        eta = [0.2, 0.2, 0.1, 0.1, 0.05][t]
+        g = rng.standard_normal((M, d)).astype(F)
+        for st in (ref, lazy):
+            st.set_grads(g)
+            _raw_step(st, "sgd", 0.0, eta_prev, eta, n)
+        _compare_outputs(lazy, ref, "%s call %d with %d workers" % (route, t, n), n)
+        eta_prev = eta
+    ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+    torch.cuda.synchronize()
+    _same_bits(lazy.e, ref.e, "residuals after flush")
+    _same_bits(lazy.te, ref.te, "server residual after flush")
+    for st in (ref, lazy):
+        st.plan.close()
+
+
+def test_deferred_mode_without_large_blocks_changes_nothing():
+    offs = _offs(SIZES["ragged_large"])
+    d = int(offs[-1])
+    M = 2
+    rng = np.random.default_rng(5)
+    ref = GpuState(offs, M)
+    lazy = GpuState(offs, M)
+    lazy.plan.set_lazy(True)                 # default limit: no block of this layout is large
+    for t in range(2):
+        g = rng.standard_normal((M, d)).astype(F)
+        for st in (ref, lazy):
+            st.set_grads(g)
+            _raw_step(st, "sgdm", 0.9, 0.1 * t, 0.1)
+        _compare_outputs(lazy, ref, "step %d" % t)
+        _same_bits(lazy.e, ref.e, "residuals, no flush needed")
+        _same_bits(lazy.te, ref.te, "server residual, no flush needed")
+    for st in (ref, lazy):
+        st.plan.close()
+
+
+def test_flush_argument_checks():
+    offs = _offs([3 * TILE])
+    plan = ef.ef_plan_create(offs, 2)
+    e = torch.zeros((3, 3 * TILE), dtype=torch.float32, device="cuda")
+    with pytest.raises(ef.EfError):
+        ef.ef_flush(plan, e)                 # more rows than max_workers
+    ef.ef_flush(plan, e[:2])
+    ef.ef_flush(plan)                        # nothing to do
+    with pytest.raises(ef.EfError):
+        ef.ef_flush(plan, e[:2, 1:].contiguous().view(-1)[1:3 * TILE + 1])   # off 16 bytes
+    torch.cuda.synchronize()
+    plan.close()
+
+
+@pytest.mark.parametrize("route", ["one_pass", "direct"])
+def test_deferred_mode_in_a_replayed_graph(route):
+    """A captured iteration in the deferred mode, replayed: which buffers wait for a correction is
+    device state, so every replay corrects what the replay before it left."""
+    offs = _offs(SIZES["ragged_large"])
+    d = int(offs[-1])
+    M, mu, eta = 3, 0.9, 0.1
+    rng = np.random.default_rng(31)
+    x0 = rng.standard_normal(d).astype(F)
+    a = GpuState(offs, M, x0=x0, route=route)        # deferred mode, replayed from a graph
+    b = GpuState(offs, M, x0=x0, route=route)        # default mode, eager calls
+    for st in (a, b):
+        st.plan.tune(fuse_limit=3)
+    a.plan.set_lazy(True)
+    g0 = rng.standard_normal((M, d)).astype(F)
+    for st in (a, b):
+        st.set_grads(g0)
+        _raw_step(st, "sgdm", mu, 0.0, eta)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        ef.ef_worker_step(a.plan, a.g, a.m, a.e, mu, eta, eta, a.ws, a.wc)
+        ef.ef_server_step(a.plan, M, a.ws, a.wc, a.te, eta, eta, a.ss, a.sc)
+        ef.ef_apply(a.plan, a.x, a.ss, a.sc, eta)
+    torch.cuda.synchronize()
+    for k in range(4):
+        g = rng.standard_normal((M, d)).astype(F)
+        a.set_grads(g)
+        b.set_grads(g)
+        torch.cuda.synchronize()
+        graph.replay()
+        _raw_step(b, "sgdm", mu, eta, eta)
+        _compare_outputs(a, b, "%s replay %d" % (route, k))
+    ef.ef_flush(a.plan, a.e, a.te)
+    torch.cuda.synchronize()
+    _same_bits(a.e, b.e, "residuals after flush")
+    _same_bits(a.te, b.te, "server residual after flush")
+    # the default-mode side is what the oracle computes
+    g = rng.standard_normal((M, d)).astype(F)
+    b.set_grads(g)
+    synced_step(b, mu, eta, eta, None, "after the replays")
+    for st in (a, b):
+        st.plan.close()
+
+
+def test_deferred_full_size_one_block():
+    """The bench configuration of the layout that gains most (one block of 2^28 elements, 8 workers,
+    default limits and kernels): deferred and default mode side by side on the same gradients.
+    The default mode at this size is checked against the oracle in tests/test_parity_full_gpu.py."""
+    import ef_workloads as wl
+    w = wl.get("one_block_2p28")
+    dev = torch.device("cuda")
+    d, B, M = w.d, w.B, w.M
+    W = (d + 63) // 64
+    g = torch.zeros((M, d), dtype=torch.float32, device=dev)
+
+    class Side:
+        def __init__(self, lazy):
+            self.plan = ef.ef_plan_create(w.offsets, M)
+            self.plan.set_lazy(lazy)
+            self.m = torch.zeros((M, d), dtype=torch.float32, device=dev)
+            self.e = torch.zeros((M, d), dtype=torch.float32, device=dev)
+            self.te = torch.zeros(d, dtype=torch.float32, device=dev)
+            self.x = torch.zeros(d, dtype=torch.float32, device=dev)
+            self.ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
+            self.wc = torch.zeros((M, B), dtype=torch.float32, device=dev)
+            self.ss = torch.zeros(W, dtype=torch.int64, device=dev)
+            self.sc = torch.zeros(B, dtype=torch.float32, device=dev)
+
+    ref, lazy = Side(False), Side(True)
+    eta_prev = 0.0
+    for t in range(3):
+        print("[one_block_2p28 deferred] step %d" % t, flush=True)
+        for i in range(M):
+            w.grad(t, i, device=dev, out=g[i])
+        for s in (ref, lazy):
+            ef.ef_worker_step(s.plan, g, s.m, s.e, w.mu, eta_prev, w.eta, s.ws, s.wc)
+            ef.ef_server_step(s.plan, M, s.ws, s.wc, s.te, eta_prev, w.eta, s.ss, s.sc)
+            ef.ef_apply(s.plan, s.x, s.ss, s.sc, w.eta)
+        torch.cuda.synchronize()
+        for name in ("ws", "wc", "ss", "sc", "m", "x"):
+            assert torch.equal(getattr(lazy, name), getattr(ref, name)), "step %d: %s differs" % (t, name)
+        eta_prev = w.eta
+    assert not torch.equal(lazy.e, ref.e) and not torch.equal(lazy.te, ref.te)
+    ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+    torch.cuda.synchronize()
+    assert torch.equal(lazy.e.view(torch.int32), ref.e.view(torch.int32)), "residuals after flush"
+    assert torch.equal(lazy.te.view(torch.int32), ref.te.view(torch.int32)), "server residual after flush"
+    for s in (ref, lazy):
+        s.plan.close()
