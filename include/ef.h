@@ -149,6 +149,11 @@ int ef_plan_is_persistent(const ef_plan *plan);
  *     they change which blocks count as large: call ef_flush first.
  * Blocks of at most fuse_limit tiles, and the parts of large blocks that
  * share a tile with another block, are corrected in the call as before.
+ * Unless ef_plan_tune has set a limit, the mode lowers fuse_limit to 0 for the
+ * server and for the persistent worker kernel, so that every block of two or
+ * more tiles takes the deferred route and no workgroup waits for a scale
+ * (measured faster: 7.8 instead of 8.0 ms per step on 2^28 elements in 256
+ * blocks with 8 workers).
  * ef_plan_set_lazy synchronises the device.
  */
 int ef_plan_set_lazy(ef_plan *plan, int on);

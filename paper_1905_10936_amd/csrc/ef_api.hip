@@ -181,6 +181,12 @@ int refresh_limits(ef_plan *p)
     auto clamp = [](int64_t v) { return (int32_t)(v < 0 ? 0 : (v > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : v)); };
     if (p->user_fuse_limit >= 0) {
         p->role[0].fuse_limit = p->role[1].fuse_limit = clamp(p->user_fuse_limit);
+    } else if (p->lazy) {
+        // With the correction deferred nothing is gained by waiting for a block's scale inside the
+        // first kernel: every block of two or more tiles takes the deferred route (measured faster
+        // than the one-pass route for the server and the persistent worker kernel).
+        p->role[0].fuse_limit = p->persistent ? 0 : clamp(p->lim_direct);
+        p->role[1].fuse_limit = 0;
     } else {
         p->role[0].fuse_limit = clamp(p->persistent ? p->lim_persistent : p->lim_direct);
         p->role[1].fuse_limit = clamp(p->lim_server);

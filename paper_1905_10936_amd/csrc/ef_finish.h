@@ -144,7 +144,7 @@ __global__ __launch_bounds__(THREADS) void k_flush(Layout L, ScratchRef R, const
     float4 v[SUBROWS];
     if (!((X.pending >> blockIdx.y) & 1ull)) return;
     load_tile(e, v, TILE);
-    correct_loaded_residual(v, L, tile, X, set);
+    correct_loaded_residual(v, loaded_correction(L, tile, X, set));
     store_tile(e, v, TILE);
 }
 

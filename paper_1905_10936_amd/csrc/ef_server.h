@@ -41,8 +41,9 @@ void k_server_uniform(Layout L, ScratchRef R, ServerArgs A, int set)
     float *te = A.err + tile_start;
     Posted P;
     float4 tv[SUBROWS];
+    const LoadedCorrection corr = loaded_correction(L, tile, X, set);
     load_tile(te, tv, n_valid);
-    correct_loaded_residual(tv, L, tile, X, set);
+    correct_loaded_residual(tv, corr);
 
     float acc[SUBROWS][4];
 #pragma unroll

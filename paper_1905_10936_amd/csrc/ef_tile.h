@@ -709,17 +709,31 @@ __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layou
 }
 
 // Deferred correction of a uniform tile's residual as loaded (see Scratch::lazy_scales): if the
-// tile's block is larger than fuse_limit and the set's last call left p in the buffer, subtract
-// what that call's payload stood for.  Called by every thread with the same tile and set.
-__device__ __forceinline__ void correct_loaded_residual(float4 (&e)[SUBROWS], const Layout &L, int32_t tile,
-                                                        const Scratch &X, int set)
+// tile's block is larger than fuse_limit and the set's last call left p in the buffer, what that
+// call's payload stood for is subtracted.  The scale is looked up before the tile's loads are
+// issued (two dependent scalar loads that then overlap with them) and applied once they are in.
+// Called by every thread with the same tile and set.
+struct LoadedCorrection {
+    float s;
+    bool on;
+};
+__device__ __forceinline__ LoadedCorrection loaded_correction(const Layout &L, int32_t tile, const Scratch &X, int set)
 {
-    if (!L.lazy || !((X.pending >> (set - X.set_base)) & 1ull)) return;
+    LoadedCorrection c;
+    c.s = 0.f;
+    c.on = false;
+    if (!L.lazy || !((X.pending >> (set - X.set_base)) & 1ull)) return c;
     const int32_t li = L.late_index[L.tile_fb[tile]];
-    if (li < 0) return;
-    const float s = X.lazy_scales[(int64_t)set * X.lazy_stride + li];
+    if (li < 0) return c;
+    c.s = X.lazy_scales[(int64_t)set * X.lazy_stride + li];
+    c.on = true;
+    return c;
+}
+__device__ __forceinline__ void correct_loaded_residual(float4 (&e)[SUBROWS], const LoadedCorrection &c)
+{
+    if (!c.on) return;
 #pragma unroll
-    for (int k = 0; k < SUBROWS; ++k) residual4(e[k], s);
+    for (int k = 0; k < SUBROWS; ++k) residual4(e[k], c.s);
 }
 
 // Uniform tile (inside one block b): sign words and the tile's fp64 sum.

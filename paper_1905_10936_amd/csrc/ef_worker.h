@@ -225,6 +225,7 @@ struct WorkerProducer {
     WorkerArgs A;
     const Scratch *X;
     float4 gv[SUBROWS], mv[SUBROWS], ev[SUBROWS];
+    LoadedCorrection corr;
 
     __device__ __forceinline__ uint64_t *signs(const Layout &L, int idx) const { return A.signs + (int64_t)idx * A.signs_stride; }
     __device__ __forceinline__ float *scales(const Layout &L, int idx) const { return A.scales + (int64_t)idx * A.scales_stride; }
@@ -232,16 +233,17 @@ struct WorkerProducer {
     {
         return A.err + (int64_t)idx * A.state_stride + (int64_t)tile * TILE;
     }
-    __device__ __forceinline__ void issue(const Layout &, int idx, int32_t tile)
+    __device__ __forceinline__ void issue(const Layout &L, int idx, int32_t tile)
     {
         const int64_t tile_start = (int64_t)tile * TILE;
+        corr = loaded_correction(L, tile, *X, X->set_base + idx);
         load_tile(A.grad + (int64_t)idx * A.grad_stride + tile_start, gv, TILE);
         if (MOM) load_tile(A.mom + (int64_t)idx * A.state_stride + tile_start, mv, TILE);
         load_tile(A.err + (int64_t)idx * A.state_stride + tile_start, ev, TILE);
     }
     __device__ __forceinline__ void produce(const Layout &L, int idx, int32_t tile, float4 (&p)[SUBROWS])
     {
-        correct_loaded_residual(ev, L, tile, *X, X->set_base + idx);
+        correct_loaded_residual(ev, corr);
         worker_values<MOM>(gv, mv, ev, A.mu, A.r);
         if (MOM) store_tile(A.mom + (int64_t)idx * A.state_stride + (int64_t)tile * TILE, mv, TILE);
 #pragma unroll
@@ -285,10 +287,11 @@ void k_worker_uniform_direct(Layout L, ScratchRef R, WorkerArgs A)
     float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
     Posted P;
     float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
+    const LoadedCorrection corr = loaded_correction(L, tile, X, worker);
     load_tile(g, gv, n_valid);
     if (MOM) load_tile(m, mv, n_valid);
     load_tile(e, pv, n_valid);
-    correct_loaded_residual(pv, L, tile, X, worker);
+    correct_loaded_residual(pv, corr);
     worker_values<MOM>(gv, mv, pv, A.mu, A.r);
     if (MOM) store_tile(m, mv, n_valid);
     float *scales_out = A.scales + (int64_t)worker * A.scales_stride;

@@ -165,22 +165,37 @@ def test_deferred_momentum_free_and_changing_worker_count(route):
         st.plan.close()
 
 
-def test_deferred_mode_without_large_blocks_changes_nothing():
+@pytest.mark.parametrize("route", ["one_pass", "direct"])
+def test_deferred_mode_with_its_own_limits(route):
+    """Without a limit set by the caller the deferred mode picks its own (no waiting for scales
+    where that was measured faster); results stay those of the default mode."""
     offs = _offs(SIZES["ragged_large"])
     d = int(offs[-1])
     M = 2
     rng = np.random.default_rng(5)
-    ref = GpuState(offs, M)
-    lazy = GpuState(offs, M)
-    lazy.plan.set_lazy(True)                 # default limit: no block of this layout is large
+    ref = GpuState(offs, M, route=route)
+    lazy = GpuState(offs, M, route=route)
+    lazy.plan.set_lazy(True)
+    for t in range(3):
+        g = rng.standard_normal((M, d)).astype(F)
+        for st in (ref, lazy):
+            st.set_grads(g)
+            _raw_step(st, "sgdm", 0.9, 0.1 if t else 0.0, 0.1)
+        _compare_outputs(lazy, ref, "step %d" % t)
+    assert not np.array_equal(to_np(lazy.te), to_np(ref.te))
+    ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+    torch.cuda.synchronize()
+    _same_bits(lazy.e, ref.e, "residuals after flush")
+    _same_bits(lazy.te, ref.te, "server residual after flush")
+    lazy.plan.set_lazy(False)                # nothing pending any more
     for t in range(2):
         g = rng.standard_normal((M, d)).astype(F)
         for st in (ref, lazy):
             st.set_grads(g)
-            _raw_step(st, "sgdm", 0.9, 0.1 * t, 0.1)
-        _compare_outputs(lazy, ref, "step %d" % t)
-        _same_bits(lazy.e, ref.e, "residuals, no flush needed")
-        _same_bits(lazy.te, ref.te, "server residual, no flush needed")
+            _raw_step(st, "sgdm", 0.9, 0.1, 0.1)
+        _compare_outputs(lazy, ref, "default mode again, step %d" % t)
+        _same_bits(lazy.e, ref.e, "residuals in the default mode")
+        _same_bits(lazy.te, ref.te, "server residual in the default mode")
     for st in (ref, lazy):
         st.plan.close()
 
