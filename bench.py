@@ -228,6 +228,14 @@ def main():
     step_bytes = bw + bs + ba
     achieved = bw / (t_worker * 1e-3) / 1e9
 
+    # untimed: the practical ceiling of the worker's access pattern on this machine (a bare stream of
+    # the same reads and writes over the same buffers; the state is not needed any more)
+    ceiling = None
+    if variant != "sgd" and M * ds >= 4096:
+        torch.cuda.synchronize()
+        p_ms, p_bytes = ef.ef_stream_probe(grads[0].view(-1), mom.view(-1), err.view(-1), repeats=3)
+        ceiling = p_bytes / (p_ms * 1e-3) / 1e9
+
     value = (M + 1) * d / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "EF-compress step Gelem/s (worker+server, M workers) and % of HBM roofline",
@@ -258,6 +266,11 @@ def main():
             "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if variant == "sgdm" else None,
             "algorithmic_bytes_per_launch": bw,
             "ms_per_launch": round(t_worker, 4),
+            "practical_ceiling": None if ceiling is None else {
+                "achieved": round(ceiling, 1), "unit": "GB/s", "frac_of_peak": round(ceiling / HBM_PEAK_GBS, 4),
+                "worker_vs_ceiling": round(achieved / ceiling, 4),
+                "what": "ef_stream_probe: bare 3-read/2-write fp32 stream over the same buffers, same tiles and "
+                        "ticket order, no compression (measured in this run, untimed part)"},
         },
         "per_call_ms": {"ef_worker_step": round(t_worker, 4), "ef_server_step": round(t_server, 4),
                         "ef_apply": round(t_apply, 4)},

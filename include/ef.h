@@ -316,6 +316,23 @@ int ef_apply_fused(const ef_plan *plan, float *params, const void *payload, floa
 int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out,
                           void *stream);
 
+/*
+ * Measurement aid, not part of Algorithm 4: streams the worker step's memory
+ * traffic with nothing else in it.  For every whole 4096-element tile of
+ * g, m, e (device, >= n_elements floats each, 16-byte aligned, distinct) it
+ * reads all three and writes m and e, 20 bytes per element, with the worker
+ * kernel's loads, stores, tile shape and ticket order, but no compression and
+ * no waiting; m and e hold garbage afterwards.  Runs one warm-up pass and
+ * `repeats` (1..1000) timed passes on `stream`, waits for them, and stores
+ * the mean time of a pass in *ms_per_pass (host): 20 * (n_elements rounded
+ * down to whole tiles) bytes / that time is the practical ceiling of this
+ * access pattern on the machine, to set beside ef_worker_step's rate.
+ * Allocates a counter and two events for the duration of the call.
+ * EF_ERR_ARG for fewer than 4096 elements or repeats out of range.
+ */
+int ef_stream_probe(const float *g, float *m, float *e, int64_t n_elements, int repeats, float *ms_per_pass,
+                    void *stream);
+
 /* Static text for an error code; for EF_ERR_HIP the text of the last HIP error
  * seen by this thread is appended.  The returned pointer stays valid until the
  * same thread calls ef_strerror again. */

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = [os.path.join(HERE, "csrc", "ef_api.hip")]
 DEPS = SRC + [os.path.join(HERE, "csrc", h) for h in
-              ("ef_device.h", "ef_tile.h", "ef_worker.h", "ef_server.h", "ef_finish.h", "ef_quality.h")] + \
+              ("ef_device.h", "ef_tile.h", "ef_worker.h", "ef_server.h", "ef_finish.h", "ef_quality.h", "ef_probe.h")] + \
     [os.path.join(ROOT, "include", "ef.h")]
 LIB = os.path.join(HERE, "libef.so")
 

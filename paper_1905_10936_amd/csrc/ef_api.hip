@@ -2,6 +2,7 @@
 // behind the C ABI declared in include/ef.h.
 #include "ef.h"
 #include "ef_device.h"
+#include "ef_probe.h"
 
 #include <cmath>
 #include <cstdio>
@@ -488,6 +489,49 @@ int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_strid
         EF_HIP(hipGetLastError());
     }
     return EF_OK;
+}
+
+int ef_stream_probe(const float *g, float *m, float *e, int64_t n_elements, int repeats, float *ms_per_pass, void *stream)
+{
+    if (!g || !m || !e || !ms_per_pass) return EF_ERR_NULL;
+    if (n_elements < ef::TILE || n_elements / ef::TILE > 0x7fffffffll || repeats < 1 || repeats > 1000) return EF_ERR_ARG;
+    if (!aligned(g, 16) || !aligned(m, 16) || !aligned(e, 16)) return EF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned n_tiles = (unsigned)(n_elements / ef::TILE);
+    hipDeviceProp_t prop;
+    int dev = 0, occ = 0;
+    EF_HIP(hipGetDevice(&dev));
+    EF_HIP(hipGetDeviceProperties(&prop, dev));
+    EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, ef::k_probe_stream, ef::THREADS, 0));
+    if (occ < 1) occ = 1;
+    unsigned grid = (unsigned)prop.multiProcessorCount * (unsigned)occ;
+    if (grid > n_tiles) grid = n_tiles;
+    unsigned int *ticket = nullptr;
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    int rc = EF_OK;
+    float ms = 0.f;
+    auto pass = [&]() {
+        hipLaunchKernelGGL(ef::k_probe_reset, dim3(1), dim3(64), 0, s, ticket);
+        hipLaunchKernelGGL(ef::k_probe_stream, dim3(grid), dim3(ef::THREADS), 0, s, g, m, e, n_tiles, ticket);
+    };
+    if (hipMalloc(&ticket, sizeof(unsigned int)) != hipSuccess || hipEventCreate(&t0) != hipSuccess ||
+        hipEventCreate(&t1) != hipSuccess) {
+        rc = EF_ERR_HIP;
+    } else {
+        pass();                                     // warm-up
+        bool ok = hipEventRecord(t0, s) == hipSuccess;
+        for (int r = 0; r < repeats; ++r) pass();
+        ok = ok && hipEventRecord(t1, s) == hipSuccess && hipEventSynchronize(t1) == hipSuccess &&
+             hipEventElapsedTime(&ms, t0, t1) == hipSuccess && hipGetLastError() == hipSuccess;
+        if (ok)
+            *ms_per_pass = ms / (float)repeats;
+        else
+            rc = EF_ERR_HIP;
+    }
+    if (t0) (void)hipEventDestroy(t0);
+    if (t1) (void)hipEventDestroy(t1);
+    if (ticket) (void)hipFree(ticket);
+    return rc;
 }
 
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
