@@ -260,23 +260,27 @@ def test_deferred_mode_in_a_replayed_graph(route):
         st.plan.close()
 
 
-def test_deferred_full_size_one_block():
-    """The bench configuration of the layout that gains most (one block of 2^28 elements, 8 workers,
-    default limits and kernels): deferred and default mode side by side on the same gradients.
-    The default mode at this size is checked against the oracle in tests/test_parity_full_gpu.py."""
+@pytest.mark.parametrize("workload,steps", [("one_block_2p28", 3), ("skewed_blocks", 3), ("transformer_like", 2)])
+def test_deferred_full_size(workload, steps):
+    """Bench configurations (full size, default limits and kernels) of the layouts with blocks beyond
+    the one-pass limit: one block of 2^28 elements; a million tiny blocks around four of 8 Mi; the
+    transformer-like layout with its 51 M-element embedding and 16 workers.  Deferred and default
+    mode side by side on the same gradients.  The default mode at these sizes is checked against the
+    oracle in tests/test_parity_full_gpu.py."""
     import ef_workloads as wl
-    w = wl.get("one_block_2p28")
+    w = wl.get(workload)
     dev = torch.device("cuda")
     d, B, M = w.d, w.B, w.M
     W = (d + 63) // 64
-    g = torch.zeros((M, d), dtype=torch.float32, device=dev)
+    ds = (d + 3) // 4 * 4            # row stride: the ABI wants a multiple of 4 elements
+    g = torch.zeros((M, ds), dtype=torch.float32, device=dev)
 
     class Side:
         def __init__(self, lazy):
             self.plan = ef.ef_plan_create(w.offsets, M)
             self.plan.set_lazy(lazy)
-            self.m = torch.zeros((M, d), dtype=torch.float32, device=dev)
-            self.e = torch.zeros((M, d), dtype=torch.float32, device=dev)
+            self.m = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+            self.e = torch.zeros((M, ds), dtype=torch.float32, device=dev)
             self.te = torch.zeros(d, dtype=torch.float32, device=dev)
             self.x = torch.zeros(d, dtype=torch.float32, device=dev)
             self.ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
@@ -286,10 +290,10 @@ def test_deferred_full_size_one_block():
 
     ref, lazy = Side(False), Side(True)
     eta_prev = 0.0
-    for t in range(3):
-        print("[one_block_2p28 deferred] step %d" % t, flush=True)
+    for t in range(steps):
+        print("[%s deferred] step %d" % (workload, t), flush=True)
         for i in range(M):
-            w.grad(t, i, device=dev, out=g[i])
+            w.grad(t, i, device=dev, out=g[i, :d])
         for s in (ref, lazy):
             ef.ef_worker_step(s.plan, g, s.m, s.e, w.mu, eta_prev, w.eta, s.ws, s.wc)
             ef.ef_server_step(s.plan, M, s.ws, s.wc, s.te, eta_prev, w.eta, s.ss, s.sc)
