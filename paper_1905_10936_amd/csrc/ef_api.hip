@@ -2,7 +2,6 @@
 // behind the C ABI declared in include/ef.h.
 #include "ef.h"
 #include "ef_device.h"
-#include "ef_probe.h"
 
 #include <cmath>
 #include <cstdio>
@@ -280,7 +279,7 @@ int build_device(ef_plan *p)
     p->X.lazy_scales = p->d_lazy_scales;
     p->X.lazy_stride = p->lazy_stride;
     // A block finishes in one pass if its tiles fit twice over into the
-    // workgroups resident at once (see ef_device.h).
+    // workgroups resident at once (see ef_tile.h).
     {
         hipDeviceProp_t prop;
         EF_HIP(hipGetDeviceProperties(&prop, p->device));

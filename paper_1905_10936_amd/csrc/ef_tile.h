@@ -44,6 +44,13 @@
 // than fuse_limit and any tile whose (bounded) wait ran out, get p parked in
 // the residual buffer; a small kernel then computes the scales still missing
 // and another subtracts the decoded value where p was parked.
+//
+// Deferred correction (optional)
+// ------------------------------
+// With Layout::lazy set, the whole tiles of blocks larger than fuse_limit are
+// left out of that last kernel: the buffer keeps p, the block's scale is kept
+// in Scratch::lazy_scales, a bit per set in CallState says so, and the next
+// call subtracts the decoded value as it loads the tile (loaded_correction).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
