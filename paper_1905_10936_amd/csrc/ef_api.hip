@@ -31,7 +31,7 @@ struct ef_plan {
         int32_t *d_late_index;      // [B]
         int32_t *d_lazy_tiles;      // [ntiles] capacity
         uint32_t n_lazy_tiles;
-    } role[2];
+    } role[3];                      // worker, server, worker calls that run one workgroup per tile whatever `persistent` says
     int lazy;                       // deferred correction on (ef_plan_set_lazy)
     float *d_lazy_scales;           // [nsets][lazy_stride]
     int lazy_stride;
@@ -180,16 +180,19 @@ int refresh_limits(ef_plan *p)
 {
     auto clamp = [](int64_t v) { return (int32_t)(v < 0 ? 0 : (v > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : v)); };
     if (p->user_fuse_limit >= 0) {
-        p->role[0].fuse_limit = p->role[1].fuse_limit = clamp(p->user_fuse_limit);
+        p->role[0].fuse_limit = p->role[1].fuse_limit = p->role[2].fuse_limit = clamp(p->user_fuse_limit);
     } else if (p->lazy) {
         // With the correction deferred nothing is gained by waiting for a block's scale inside the
         // first kernel: every block of two or more tiles takes the deferred route (measured faster
         // than the one-pass route for the server and the persistent worker kernel).
         p->role[0].fuse_limit = p->persistent ? 0 : clamp(p->lim_direct);
         p->role[1].fuse_limit = 0;
+        // the buffers a call leaves behind must fit the lists of whichever worker call comes next
+        p->role[2].fuse_limit = p->role[0].fuse_limit;
     } else {
         p->role[0].fuse_limit = clamp(p->persistent ? p->lim_persistent : p->lim_direct);
         p->role[1].fuse_limit = clamp(p->lim_server);
+        p->role[2].fuse_limit = clamp(p->lim_direct);
     }
     p->L.fuse_limit = p->role[0].fuse_limit;
     for (auto &r : p->role) {
@@ -678,7 +681,13 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
     A.scales_stride = scales_stride;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const CallScratch c = next_call(plan, 0, n_workers);
-    const ef::Layout L = role_layout(plan, 0);
+    // The momentum-free worker moves 48 KiB per tile instead of 80: one ticket per tile would
+    // make the ticket counter (about 84 tickets per microsecond) its bottleneck, so it runs one
+    // workgroup per tile unless the persistent kernel was asked for explicitly.  That kernel has
+    // its own one-pass limit, hence its own lists (role 2).
+    const bool ticketed = plan->L.n_uniform && plan->persistent && (has_mom || plan->persistent_forced);
+    const int role = ticketed || !plan->persistent ? 0 : 2;
+    const ef::Layout L = role_layout(plan, role);
     if (plan->L.n_mixed) {
         const dim3 grid((unsigned)plan->L.n_mixed, (unsigned)n_workers);
         if (has_mom)
@@ -687,10 +696,7 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
             hipLaunchKernelGGL(ef::k_worker_mixed<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
-    // The momentum-free worker moves 48 KiB per tile instead of 80: one ticket per tile would
-    // make the ticket counter (about 84 tickets per microsecond) its bottleneck, so it runs one
-    // workgroup per tile unless the persistent kernel was asked for explicitly.
-    if (plan->L.n_uniform && plan->persistent && (has_mom || plan->persistent_forced)) {
+    if (ticketed) {
         int64_t wgs = (int64_t)plan->L.n_uniform * n_workers;
         if (wgs > plan->worker_grid) wgs = plan->worker_grid;
         const dim3 grid((unsigned)wgs), block(ef::THREADS);
@@ -707,7 +713,7 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
             hipLaunchKernelGGL(ef::k_worker_uniform_direct<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
-    return launch_second_pass(plan, 0, c, n_workers, err, state_stride, scales, scales_stride, s);
+    return launch_second_pass(plan, role, c, n_workers, err, state_stride, scales, scales_stride, s);
 }
 
 int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, int64_t in_signs_stride,

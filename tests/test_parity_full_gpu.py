@@ -287,12 +287,15 @@ def test_beyond_2p31_elements_sampled():
     _run_sampled(w, w.steps, blocks, check_props=False)
 
 
-@pytest.mark.parametrize("persistent", [True, False])
-def test_blocks_around_the_one_pass_limits(persistent):
+@pytest.mark.parametrize("persistent,variant", [(True, "sgdm"), (False, "sgdm"), (None, "sgd"), (True, "sgd"),
+                                                (False, "sgd")])
+def test_blocks_around_the_one_pass_limits(persistent, variant):
     """Blocks whose tile counts sit on both sides of every default one-pass limit (768 and 1024 tiles
     for the kernels with one workgroup per tile, 2304 for the persistent one) and of earlier ones
     (1152), some ending off the tile grid, with the plan's own limits: each block must take the
-    route its size calls for and give the oracle's result either way.  All blocks go through the oracle."""
+    route its size calls for and give the oracle's result either way.  All blocks go through the oracle.
+    persistent None: the plan's own choice (the persistent kernel for this layout), under which the
+    momentum-free worker still runs one workgroup per tile and needs that kernel's limit."""
     tiles = [767, 768, 769, 1023, 1024, 1025, 1151, 1152, 1153, 2303, 2304, 2305]
     rng = np.random.default_rng(12)
     sizes = [t * 4096 + int(rng.integers(-3, 4)) for t in tiles]
@@ -300,7 +303,10 @@ def test_blocks_around_the_one_pass_limits(persistent):
     w = wl.Workload("limit_blocks", 9, [sizes[i] for i in order], M=2, steps=2, dist=("normal", 1.0))
     dev = torch.device("cuda")
     plan = ef.ef_plan_create(w.offsets, w.M)
-    plan.set_persistent(persistent)
+    if persistent is None:
+        assert plan.persistent
+    else:
+        plan.set_persistent(persistent)
     d, B, M = w.d, w.B, w.M
     W = (d + 63) // 64
     ds = (d + 3) // 4 * 4
@@ -315,15 +321,22 @@ def test_blocks_around_the_one_pass_limits(persistent):
             w.grad(t, i, device=dev, out=g[i, :d])
         g_h, m_h, e_h = (x[:, :d].cpu().numpy() for x in (g, m, e))
         print("[limit_blocks persistent=%s] step %d on the GPU (limit %d tiles)" % (persistent, t, plan.fuse_limit), flush=True)
-        ef.ef_worker_step(plan, g, m, e, w.mu, eta_prev, w.eta, ws, wc)
+        if variant == "sgd":
+            ef.ef_worker_step_sgd(plan, g, e, eta_prev, w.eta, ws, wc)
+        else:
+            ef.ef_worker_step(plan, g, m, e, w.mu, eta_prev, w.eta, ws, wc)
         torch.cuda.synchronize()
         parked, late = plan.last_fallbacks()
         assert parked == 0 and late == 0, "run-time fallbacks on an idle GPU: %d tiles, %d blocks" % (parked, late)
         for i in range(M):
             print("[limit_blocks] step %d: oracle for worker %d" % (t, i), flush=True)
             mi, ei = np.ascontiguousarray(m_h[i]), np.ascontiguousarray(e_h[i])
-            s_ref, c_ref = oracle.worker_step(np.ascontiguousarray(g_h[i]), mi, ei, w.offsets, F(w.mu), F(eta_prev), F(w.eta))
-            tag = "limit_blocks persistent=%s step %d worker %d" % (persistent, t, i)
+            if variant == "sgd":
+                s_ref, c_ref = oracle.worker_step_sgd(np.ascontiguousarray(g_h[i]), ei, w.offsets, F(eta_prev), F(w.eta))
+            else:
+                s_ref, c_ref = oracle.worker_step(np.ascontiguousarray(g_h[i]), mi, ei, w.offsets, F(w.mu), F(eta_prev),
+                                                  F(w.eta))
+            tag = "limit_blocks persistent=%s %s step %d worker %d" % (persistent, variant, t, i)
             assert np.array_equal(ws[i].cpu().numpy().view(np.uint64), s_ref), tag + ": sign words differ"
             assert np.array_equal(m[i, :d].cpu().numpy().view(np.uint32), mi.view(np.uint32)), tag + ": momentum differs"
             same = check_scales(wc[i].cpu().numpy(), c_ref, tag)
