@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE, scaled by a torch add kernel of known size run
 # in the same process): see profiles/ef_step_flat_2p28.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43295888559}
+MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43296748949}
 
 
 def algorithmic_bytes(d, B, M, variant="sgdm"):
