@@ -143,7 +143,9 @@ int ef_plan_is_persistent(const ef_plan *plan);
  *     handing a buffer to another plan or to another worker index);
  *   - worker i's buffer must stay worker i's (the remembered scales are kept
  *     per worker index and for the server), and the plan must see every step
- *     of it;
+ *     of it: while corrections are waiting, a worker, server or flush call
+ *     with another err / server_err pointer or stride than the call that
+ *     left them returns EF_ERR_ARG;
  *   - ef_plan_tune (fuse_limit), ef_plan_set_persistent and ef_plan_set_lazy
  *     return EF_ERR_ARG while any buffer is waiting for its correction, since
  *     they change which blocks count as large: call ef_flush first.

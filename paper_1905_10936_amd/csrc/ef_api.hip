@@ -33,6 +33,12 @@ struct ef_plan {
         uint32_t n_lazy_tiles;
     } role[3];                      // worker, server, worker calls that run one workgroup per tile whatever `persistent` says
     int lazy;                       // deferred correction on (ef_plan_set_lazy)
+    // Host-side guard of the deferred mode: the residual buffers (workers, server) the last calls
+    // left waiting for their correction, so that a call with other buffers is refused.  The
+    // device-side CallState is what the kernels go by; this only catches misuse at the boundary.
+    mutable const float *lazy_buf[2];
+    mutable int64_t lazy_stride_seen;
+    mutable int lazy_sets_seen;     // most workers any call since the last full flush has used
     float *d_lazy_scales;           // [nsets][lazy_stride]
     int lazy_stride;
     int32_t lim_persistent, lim_direct, lim_server;   // automatic limits
@@ -411,6 +417,9 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_state = nullptr;
     p->d_lazy_scales = nullptr;
     p->lazy = 0;
+    p->lazy_buf[0] = p->lazy_buf[1] = nullptr;
+    p->lazy_stride_seen = 0;
+    p->lazy_sets_seen = 0;
     p->d_defer_list = nullptr;
     p->d_fin_list = nullptr;
     for (auto &r : p->role) {
@@ -463,6 +472,8 @@ int ef_plan_set_lazy(ef_plan *plan, int on)
     if (rc) return rc;
     if (pending) return EF_ERR_ARG;
     plan->lazy = on ? 1 : 0;
+    plan->lazy_buf[0] = plan->lazy_buf[1] = nullptr;
+    plan->lazy_sets_seen = 0;
     return refresh_limits(plan);
 }
 
@@ -474,10 +485,19 @@ int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_strid
     if (err && (n_workers < 1 || n_workers > plan->max_workers || state_stride < plan->L.d || state_stride % 4))
         return EF_ERR_ARG;
     if ((err && !aligned(err, 16)) || (server_err && !aligned(server_err, 16))) return EF_ERR_ALIGN;
+    // other buffers than the ones that wait for their correction: refuse rather than corrupt them
+    if (err && plan->lazy_buf[0] && (plan->lazy_buf[0] != err || plan->lazy_stride_seen != state_stride)) return EF_ERR_ARG;
+    if (server_err && plan->lazy_buf[1] && plan->lazy_buf[1] != server_err) return EF_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     for (int role = 0; role < 2; ++role) {
         float *buf = role == 0 ? err : server_err;
         if (!buf) continue;
+        if (role == 1) {
+            plan->lazy_buf[1] = nullptr;
+        } else if (n_workers >= plan->lazy_sets_seen) {
+            plan->lazy_buf[0] = nullptr;
+            plan->lazy_sets_seen = 0;
+        }
         const ef_plan::Role &r = plan->role[role];
         const int nsets = role == 0 ? n_workers : 1;
         const CallScratch c = next_call(plan, role == 0 ? 0 : plan->max_workers, nsets);
@@ -680,6 +700,12 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
     A.signs_stride = signs_stride;
     A.scales_stride = scales_stride;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->lazy) {
+        if (plan->lazy_buf[0] && (plan->lazy_buf[0] != err || plan->lazy_stride_seen != state_stride)) return EF_ERR_ARG;
+        plan->lazy_buf[0] = err;
+        plan->lazy_stride_seen = state_stride;
+        if (n_workers > plan->lazy_sets_seen) plan->lazy_sets_seen = n_workers;
+    }
     const CallScratch c = next_call(plan, 0, n_workers);
     // The momentum-free worker moves 48 KiB per tile instead of 80: one ticket per tile would
     // make the ticket counter (about 84 tickets per microsecond) its bottleneck, so it runs one
@@ -740,6 +766,10 @@ int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, i
     A.signs = out_signs;
     A.scales = out_scales;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->lazy) {
+        if (plan->lazy_buf[1] && plan->lazy_buf[1] != server_err) return EF_ERR_ARG;
+        plan->lazy_buf[1] = server_err;
+    }
     const CallScratch c = next_call(plan, plan->max_workers, 1);
     const ef::Layout L = role_layout(plan, 1);
     // mixed tiles first: they never wait, and the uniform tiles' gathers need their partials

@@ -309,3 +309,37 @@ def test_deferred_full_size(workload, steps):
     assert torch.equal(lazy.te.view(torch.int32), ref.te.view(torch.int32)), "server residual after flush"
     for s in (ref, lazy):
         s.plan.close()
+
+
+def test_deferred_mode_refuses_other_buffers():
+    """While corrections are waiting the plan accepts only the buffers that wait for them."""
+    offs = _offs(SIZES["aligned_large"])
+    d = int(offs[-1])
+    M = 2
+    st = GpuState(offs, M)
+    st.plan.tune(fuse_limit=3)
+    st.plan.set_lazy(True)
+    st.set_grads(np.random.default_rng(3).standard_normal((M, d)).astype(F))
+    _raw_step(st, "sgdm", 0.9, 0.0, 0.1)
+    other_e, other_te = st.e.clone(), st.te.clone()
+    with pytest.raises(ef.EfError):
+        ef.ef_worker_step(st.plan, st.g, st.m, other_e, 0.9, 0.1, 0.1, st.ws, st.wc)
+    with pytest.raises(ef.EfError):
+        ef.ef_worker_step(st.plan, st.g[1:], st.m[1:], st.e[1:], 0.9, 0.1, 0.1, st.ws[1:], st.wc[1:])   # worker 1 as worker 0
+    with pytest.raises(ef.EfError):
+        ef.ef_server_step(st.plan, M, st.ws, st.wc, other_te, 0.1, 0.1, st.ss, st.sc)
+    with pytest.raises(ef.EfError):
+        ef.ef_flush(st.plan, other_e, None)
+    with pytest.raises(ef.EfError):
+        ef.ef_flush(st.plan, None, other_te)
+    ef.ef_flush(st.plan, st.e[:1], None)             # worker 0 only: worker 1 still waits
+    with pytest.raises(ef.EfError):
+        ef.ef_worker_step(st.plan, st.g, st.m, other_e, 0.9, 0.1, 0.1, st.ws, st.wc)
+    ef.ef_flush(st.plan, st.e, st.te)
+    torch.cuda.synchronize()
+    other_e.copy_(st.e)
+    other_te.copy_(st.te)
+    ef.ef_worker_step(st.plan, st.g, st.m, other_e, 0.9, 0.1, 0.1, st.ws, st.wc)     # nothing waits: any buffer will do
+    ef.ef_server_step(st.plan, M, st.ws, st.wc, other_te, 0.1, 0.1, st.ss, st.sc)
+    torch.cuda.synchronize()
+    st.plan.close()
