@@ -343,3 +343,46 @@ def test_deferred_mode_refuses_other_buffers():
     ef.ef_server_step(st.plan, M, st.ws, st.wc, other_te, 0.1, 0.1, st.ss, st.sc)
     torch.cuda.synchronize()
     st.plan.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_deferred_equals_default_on_random_layouts(seed):
+    """Random partitions (the generator of tests/test_random_layouts_gpu.py), random one-pass limit,
+    worker count changing from step to step, flushes at random steps."""
+    from tests.test_random_layouts_gpu import _random_sizes
+    rng = np.random.default_rng(5000 + seed)
+    offs = _offs(_random_sizes(rng))
+    d = int(offs[-1])
+    M = int(rng.integers(1, 6))
+    route = ["one_pass", "direct"][seed % 2]
+    fused = bool(rng.integers(0, 2))
+    pad = int(rng.integers(0, 3))
+    ref = GpuState(offs, M, route=route, fused=fused, pad=pad)
+    lazy = GpuState(offs, M, route=route, fused=fused, pad=pad)
+    if rng.integers(0, 3) > 0:
+        lim = int(rng.integers(0, 8))
+        ref.plan.tune(fuse_limit=lim)
+        lazy.plan.tune(fuse_limit=lim)
+    lazy.plan.set_lazy(True)
+    variant = "sgd" if (seed % 3 == 0 and not fused) else "sgdm"
+    eta_prev = 0.0
+    for t in range(5):
+        eta = float(rng.choice([0.4, 0.1, 0.05]))
+        n = int(rng.integers(1, M + 1))
+        g = (rng.standard_normal((M, d)) * 10.0 ** rng.uniform(-3, 1)).astype(F)
+        g[rng.random((M, d)) < 0.1] = 0.0
+        for st in (ref, lazy):
+            st.set_grads(g)
+            _raw_step(st, variant, 0.9, eta_prev, eta, n)
+        _compare_outputs(lazy, ref, "seed %d step %d" % (seed, t), n)
+        if rng.integers(0, 4) == 0:
+            ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+            torch.cuda.synchronize()
+            _same_bits(lazy.e, ref.e, "seed %d: residuals after a flush at step %d" % (seed, t))
+        eta_prev = eta
+    ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+    torch.cuda.synchronize()
+    _same_bits(lazy.e, ref.e, "seed %d: residuals" % seed)
+    _same_bits(lazy.te, ref.te, "seed %d: server residual" % seed)
+    for st in (ref, lazy):
+        st.plan.close()
