@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE, scaled by a torch add kernel of known size run
 # in the same process): see profiles/ef_step_flat_2p28.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43296748949}
+MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43296770554}
 
 
 def algorithmic_bytes(d, B, M, variant="sgdm"):
@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--persistent", type=int, default=-1, help="1/0: force the persistent worker kernel on/off")
     ap.add_argument("--lazy", action="store_true",
                     help="deferred residual correction for blocks beyond the one-pass limit (ef_plan_set_lazy)")
+    ap.add_argument("--no-deferred", action="store_true",
+                    help="skip the extra leg that times the same steps in the deferred-correction mode")
     ap.add_argument("--variant", default="sgdm", choices=["sgdm", "sgd", "fused", "wd"],
                     help="sgdm: Algorithm 4 (the default, the metric's configuration); sgd: Algorithm 3 worker "
                          "without a momentum buffer; fused: one message per worker (Section 4.2); wd: parameter "
@@ -231,7 +233,7 @@ def main():
 
     # beside the headline (not part of `value`): the same steps with the deferred residual correction on
     deferred = None
-    if not args.lazy and not args.graph:
+    if not args.lazy and not args.graph and not args.no_deferred:
         plan.set_lazy(True)
         for k in range(max(args.warmup, 1)):
             step()
