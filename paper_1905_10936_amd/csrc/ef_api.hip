@@ -242,8 +242,9 @@ int build_device(ef_plan *p)
     EF_HIP(hipMemset(p->d_part, 0, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
     // a block that crosses a tile boundary owns at least one of the 2*ntiles open segments
     const size_t max_cross = (size_t)(2 * (int64_t)ntiles < B ? 2 * (int64_t)ntiles : B);
-    EF_HIP(hipMalloc(&p->d_ready, sizeof(unsigned long long) * (size_t)B * nsets));
-    EF_HIP(hipMemset(p->d_ready, 0, sizeof(unsigned long long) * (size_t)B * nsets));
+    // one 128-byte line per tile and set: a block's ready word sits in the line of its gatherer tile
+    EF_HIP(hipMalloc(&p->d_ready, sizeof(unsigned long long) * ef::READY_STRIDE * (size_t)ntiles * nsets));
+    EF_HIP(hipMemset(p->d_ready, 0, sizeof(unsigned long long) * ef::READY_STRIDE * (size_t)ntiles * nsets));
     EF_HIP(hipMalloc(&p->d_list_cnt, sizeof(unsigned int) * 6));
     EF_HIP(hipMalloc(&p->d_defer_list, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
     EF_HIP(hipMalloc(&p->d_fin_list, sizeof(unsigned long long) * max_cross * nsets));
