@@ -117,11 +117,15 @@ int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit 
  * on = 1 a persistent kernel whose workgroups take tiles from a ticket counter
  * and keep several tiles in registers while their scales form; on = 0 one
  * workgroup per tile that waits in place for its block's scale; on < 0 the
- * choice plan creation made for this layout (persistent when every workgroup
- * gets at least 64 tiles, or at least 16 and the layout has blocks that only
- * the persistent kernel finishes in one pass).  ef_worker_step_sgd uses the
- * persistent kernel only after on = 1.  The server always runs one workgroup
- * per tile.  Same results either way.  Synchronises the device.
+ * choice plan creation made for this layout: the persistent kernel if every
+ * workgroup gets at least 16 tiles and the layout's blocks are cheaper on it
+ * by the measured cost per tile of either kernel (one workgroup per tile is
+ * the faster on blocks of up to 256 tiles, the persistent kernel on larger
+ * ones, and it finishes blocks of 1025 to 2304 tiles in one pass that the
+ * other sends through the second pass).  ef_worker_step_sgd, and every worker
+ * call in the deferred mode (ef_plan_set_lazy), use the persistent kernel only
+ * after on = 1.  The server always runs one workgroup per tile.  Same results
+ * either way.  Synchronises the device.
  */
 int ef_plan_set_persistent(ef_plan *plan, int on);
 int ef_plan_is_persistent(const ef_plan *plan);
@@ -151,15 +155,29 @@ int ef_plan_is_persistent(const ef_plan *plan);
  *     they change which blocks count as large: call ef_flush first.
  * Blocks of at most fuse_limit tiles, and the parts of large blocks that
  * share a tile with another block, are corrected in the call as before.
- * Unless ef_plan_tune has set a limit, the mode lowers fuse_limit to 0 for the
- * server and for the persistent worker kernel, so that every block of two or
- * more tiles takes the deferred route and no workgroup waits for a scale
- * (measured faster: 7.8 instead of 8.0 ms per step on 2^28 elements in 256
- * blocks with 8 workers).
+ * Unless ef_plan_tune has set a limit, the mode picks its own: 0 for the
+ * server (no workgroup waits for a scale) and 64 tiles for the worker, which
+ * then runs one workgroup per tile unless ef_plan_set_persistent(plan, 1) asks
+ * for the persistent kernel (limit 0).  Measured on 2^28 elements in 256
+ * blocks with 8 workers: 7.5 instead of 8.0 ms per step.
  * ef_plan_set_lazy synchronises the device.
  */
 int ef_plan_set_lazy(ef_plan *plan, int on);
 int ef_plan_is_lazy(const ef_plan *plan);
+
+/*
+ * Writing out in step.  In the worker kernel that runs one workgroup per tile,
+ * the whole tiles of a block larger than fuse_limit have nothing to wait for;
+ * they are made to wait (bounded by spin_limit, and with nothing depending on
+ * the outcome) for their neighbours, in groups of `tiles` consecutive tiles,
+ * and then write together: workgroups that write at the same moment were
+ * measured to stream faster than workgroups that each write when done (worker
+ * call on 2^28 elements, 8 workers, deferred mode: 7.6 ms without, 6.9 ms in
+ * groups of 16, 6.7 ms in groups of 32).  tiles = 0 or 1 turns it off;
+ * at most 256; default 16.  Results do not depend on it.  Synchronises the
+ * device.
+ */
+int ef_plan_set_sync_group(ef_plan *plan, int tiles);
 
 /*
  * Makes the deferred corrections now: err (device, [n_workers][state_stride],

@@ -23,7 +23,7 @@ EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1
 EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
-    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_flush", "ef_stream_probe", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_plan_set_sync_group", "ef_flush", "ef_stream_probe", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
     "ef_sign_words", "ef_worker_step", "ef_worker_step_sgd", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
     "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused", "ef_compressor_quality",
 )
@@ -62,6 +62,8 @@ def lib():
     L.ef_plan_is_persistent.argtypes = [vp]
     L.ef_plan_set_lazy.restype = c_int
     L.ef_plan_set_lazy.argtypes = [vp, c_int]
+    L.ef_plan_set_sync_group.restype = c_int
+    L.ef_plan_set_sync_group.argtypes = [vp, c_int]
     L.ef_plan_is_lazy.restype = c_int
     L.ef_plan_is_lazy.argtypes = [vp]
     L.ef_stream_probe.restype = c_int
@@ -172,6 +174,10 @@ class Plan:
         """Deferred residual correction for blocks larger than fuse_limit (see ef_plan_set_lazy)."""
         _check(lib().ef_plan_set_lazy(self._h, int(bool(on))))
 
+    def set_sync_group(self, tiles):
+        """Tiles of a large block that are written out in step (0 or 1: off)."""
+        _check(lib().ef_plan_set_sync_group(self._h, int(tiles)))
+
     @property
     def lazy(self):
         return bool(lib().ef_plan_is_lazy(self._h))
@@ -216,6 +222,10 @@ def ef_plan_is_persistent(plan):
 
 def ef_plan_set_lazy(plan, on):
     plan.set_lazy(on)
+
+
+def ef_plan_set_sync_group(plan, tiles):
+    plan.set_sync_group(tiles)
 
 
 def ef_plan_is_lazy(plan):

@@ -32,6 +32,7 @@ struct ef_plan {
         int32_t *d_lazy_tiles;      // [ntiles] capacity
         uint32_t n_lazy_tiles;
     } role[3];                      // worker, server, worker calls that run one workgroup per tile whatever `persistent` says
+    int sync_group;                 // tiles of a large block that are written out in step (ef_plan_set_sync_group)
     int lazy;                       // deferred correction on (ef_plan_set_lazy)
     // Host-side guard of the deferred mode: the residual buffers (workers, server) the last calls
     // left waiting for their correction, so that a call with other buffers is refused.  The
@@ -182,16 +183,23 @@ int upload_static_list(ef_plan *p, ef_plan::Role &r)
 }
 
 // Pick each role's one-pass limit and rebuild the lists that depend on it.
+// Deferred mode, one workgroup per tile: blocks of up to this many tiles still wait for their
+// scale in the kernel (measured: 6.6-6.75 ms on 2^28 elements and 8 workers for blocks of 2 to
+// 64 tiles, as fast as anything else in that mode, and their residual is finished at once).
+constexpr int32_t LAZY_WAIT_LIMIT = 64;
+
 int refresh_limits(ef_plan *p)
 {
     auto clamp = [](int64_t v) { return (int32_t)(v < 0 ? 0 : (v > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : v)); };
     if (p->user_fuse_limit >= 0) {
         p->role[0].fuse_limit = p->role[1].fuse_limit = p->role[2].fuse_limit = clamp(p->user_fuse_limit);
     } else if (p->lazy) {
-        // With the correction deferred nothing is gained by waiting for a block's scale inside the
-        // first kernel: every block of two or more tiles takes the deferred route (measured faster
-        // than the one-pass route for the server and the persistent worker kernel).
-        p->role[0].fuse_limit = p->persistent ? 0 : clamp(p->lim_direct);
+        // With the correction deferred nothing has to wait for a block's scale.  The server and
+        // the persistent worker kernel then run fastest without any wait; the worker kernel with
+        // one workgroup per tile runs fastest when consecutive tiles are written out in step,
+        // which small blocks get by waiting for their scale as usual and larger ones through
+        // Layout::sync_group.
+        p->role[0].fuse_limit = p->persistent_forced ? 0 : LAZY_WAIT_LIMIT;
         p->role[1].fuse_limit = 0;
         // the buffers a call leaves behind must fit the lists of whichever worker call comes next
         p->role[2].fuse_limit = p->role[0].fuse_limit;
@@ -309,18 +317,28 @@ int build_device(ef_plan *p)
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
     }
     p->user_fuse_limit = -1;
-    // The persistent kernel pays off when every workgroup gets many tiles, and when it lets blocks
-    // finish in one pass that are too large for the other kernel; otherwise one workgroup per
-    // tile (nothing to pipeline, and no ticket traffic).
+    // Which worker kernel for this layout.  The persistent kernel needs enough tiles per workgroup
+    // to fill its pipeline; beyond that the choice follows the measured cost per tile of each
+    // kernel by block size (2^28 elements, 8 workers, relative to the persistent kernel's 7.0 ms,
+    // which does not depend on the block size up to its one-pass limit): the kernel with one
+    // workgroup per tile is faster on blocks of up to 256 tiles, level up to 512, slower beyond,
+    // and sends blocks above its own limit through the second pass.
     {
         const int64_t tiles_per_wg = (int64_t)p->L.n_uniform * p->max_workers / (p->worker_grid > 0 ? p->worker_grid : 1);
         const int64_t lim_hi = p->lim_persistent < ef::FUSE_LIMIT_MAX ? p->lim_persistent : ef::FUSE_LIMIT_MAX;
-        bool larger_blocks = false;
-        for (int64_t b = 0; b < B && !larger_blocks; ++b) {
+        const int64_t lim_lo = p->lim_direct < ef::FUSE_LIMIT_MAX ? p->lim_direct : ef::FUSE_LIMIT_MAX;
+        double cost_direct = 0.0, cost_persistent = 0.0;
+        for (int64_t b = 0; b < B; ++b) {
             const int64_t n = tiles_of_block(p, b);
-            larger_blocks = n > p->lim_direct && n <= lim_hi && has_uniform_tile(p, b);
+            if (n < 2 || !has_uniform_tile(p, b)) continue;
+            const double two_pass = 1.4;        // 28.125 instead of 20.125 bytes per element
+            cost_persistent += (double)n * (n <= lim_hi ? 1.0 : two_pass);
+            cost_direct += (double)n * (n > lim_lo ? two_pass - 0.03 : n <= 128 ? 0.94 : n <= 256 ? 0.98 : n <= 512 ? 1.0 : 1.05);
         }
-        p->persistent_auto = (tiles_per_wg >= 64 || (larger_blocks && tiles_per_wg >= 16)) ? 1 : 0;
+        // a clear difference (blocks that only the persistent kernel finishes in one pass) decides from
+        // 16 tiles per workgroup on, a small one only once the pipeline is well filled
+        p->persistent_auto = ((tiles_per_wg >= 64 && cost_persistent < cost_direct) ||
+                              (tiles_per_wg >= 16 && cost_persistent < 0.9 * cost_direct)) ? 1 : 0;
     }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
@@ -354,6 +372,7 @@ ef::Layout role_layout(const ef_plan *plan, int role)
     L.fuse_limit = plan->role[role].fuse_limit;
     L.lazy = plan->lazy;
     L.late_index = plan->role[role].d_late_index;
+    L.sync_group = plan->sync_group;
     return L;
 }
 
@@ -418,6 +437,7 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_state = nullptr;
     p->d_lazy_scales = nullptr;
     p->lazy = 0;
+    p->sync_group = 16;
     p->lazy_buf[0] = p->lazy_buf[1] = nullptr;
     p->lazy_stride_seen = 0;
     p->lazy_sets_seen = 0;
@@ -479,6 +499,15 @@ int ef_plan_set_lazy(ef_plan *plan, int on)
 }
 
 int ef_plan_is_lazy(const ef_plan *plan) { return plan ? plan->lazy : 0; }
+
+int ef_plan_set_sync_group(ef_plan *plan, int tiles)
+{
+    if (!plan) return EF_ERR_NULL;
+    if (tiles < 0 || tiles > 256) return EF_ERR_ARG;
+    EF_HIP(hipDeviceSynchronize());
+    plan->sync_group = tiles;
+    return EF_OK;
+}
 
 int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_stride, float *server_err, void *stream)
 {
@@ -573,7 +602,11 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
 }
 
 int ef_plan_fuse_limit(const ef_plan *plan) { return plan ? plan->role[0].fuse_limit : 0; }
-int ef_plan_is_persistent(const ef_plan *plan) { return plan ? plan->persistent : 0; }
+int ef_plan_is_persistent(const ef_plan *plan)
+{
+    if (!plan) return 0;
+    return plan->lazy ? (plan->persistent && plan->persistent_forced) : plan->persistent;
+}
 
 int ef_plan_last_fallbacks(ef_plan *plan, unsigned int *parked_tiles, unsigned int *late_blocks)
 {
@@ -712,7 +745,9 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
     // make the ticket counter (about 84 tickets per microsecond) its bottleneck, so it runs one
     // workgroup per tile unless the persistent kernel was asked for explicitly.  That kernel has
     // its own one-pass limit, hence its own lists (role 2).
-    const bool ticketed = plan->L.n_uniform && plan->persistent && (has_mom || plan->persistent_forced);
+    // In the deferred mode the kernel with one workgroup per tile is the faster one (see refresh_limits).
+    const bool ticketed = plan->L.n_uniform && plan->persistent &&
+                          (plan->lazy ? plan->persistent_forced != 0 : (has_mom || plan->persistent_forced));
     const int role = ticketed || !plan->persistent ? 0 : 2;
     const ef::Layout L = role_layout(plan, role);
     if (plan->L.n_mixed) {

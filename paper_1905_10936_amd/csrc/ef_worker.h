@@ -296,9 +296,14 @@ void k_worker_uniform_direct(Layout L, ScratchRef R, WorkerArgs A)
     if (MOM) store_tile(m, mv, n_valid);
     float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
     const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker,
-                                      S, P);
+                                      S, P, true);
     resolve_posted(P, L, X, worker, scales_out, S);
-    if (kind == UNI_PENDING) finish_uniform(pv, tile, n_valid, L.tile_fb[tile], 0ull, e, L, X, worker, S);
+    if (kind == UNI_PENDING) {
+        finish_uniform(pv, tile, n_valid, L.tile_fb[tile], 0ull, e, L, X, worker, S);
+    } else if (kind == UNI_HELD) {
+        sync_group_wait(tile, L, X, worker, S);
+        store_tile(e, pv, n_valid);
+    }
 }
 
 }  // namespace ef

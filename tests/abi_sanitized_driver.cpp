@@ -44,6 +44,7 @@ int main()
     REQUIRE(ef_plan_tune(nullptr, 1, 1) == EF_ERR_NULL);
     REQUIRE(ef_plan_set_persistent(nullptr, 1) == EF_ERR_NULL);
     REQUIRE(ef_plan_set_lazy(nullptr, 1) == EF_ERR_NULL);
+    REQUIRE(ef_plan_set_sync_group(nullptr, 16) == EF_ERR_NULL);
     REQUIRE(ef_plan_last_fallbacks(nullptr, &a, &b) == EF_ERR_NULL);
     REQUIRE(ef_plan_fuse_limit(nullptr) == 0 && ef_plan_is_persistent(nullptr) == 0 && ef_plan_is_lazy(nullptr) == 0);
     REQUIRE(ef_plan_d(nullptr) == 0 && ef_plan_blocks(nullptr) == 0 && ef_plan_sign_words(nullptr) == 0);
@@ -81,6 +82,7 @@ int main()
             REQUIRE(ef_plan_tune(p, lim, -1) == EF_OK && ef_plan_fuse_limit(p) == lim);
             REQUIRE(ef_plan_set_persistent(p, lim & 1) == EF_OK);
             REQUIRE(ef_plan_set_lazy(p, (lim >> 1) & 1) == EF_OK);
+            REQUIRE(ef_plan_set_sync_group(p, lim * 3) == EF_OK);
         }
         REQUIRE(ef_plan_set_persistent(p, -1) == EF_OK);
         REQUIRE(ef_flush(p, 1, nullptr, 0, nullptr, nullptr) == EF_OK);

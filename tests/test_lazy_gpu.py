@@ -386,3 +386,41 @@ def test_deferred_equals_default_on_random_layouts(seed):
     _same_bits(lazy.te, ref.te, "seed %d: server residual" % seed)
     for st in (ref, lazy):
         st.plan.close()
+
+
+@pytest.mark.parametrize("group", [0, 1, 2, 3, 5, 16, 256])
+@pytest.mark.parametrize("layout", ["ragged_large", "one_large_block"])
+def test_writing_out_in_step_changes_nothing(layout, group):
+    """ef_plan_set_sync_group: whole tiles of blocks beyond the one-pass limit wait for their
+    neighbours before they write (one workgroup per tile).  Any group size, default and deferred
+    mode: the default mode against the oracle, the deferred mode against the default mode."""
+    offs = _offs(SIZES[layout])
+    d = int(offs[-1])
+    M, mu = 3, 0.9
+    rng = np.random.default_rng(77 + group)
+    x0 = rng.standard_normal(d).astype(F)
+    ref = GpuState(offs, M, x0=x0, route="direct")
+    lazy = GpuState(offs, M, x0=x0, route="direct")
+    for st in (ref, lazy):
+        st.plan.tune(fuse_limit=3)
+        st.plan.set_sync_group(group)
+    lazy.plan.set_lazy(True)
+    eta_prev = 0.0
+    for t in range(3):
+        eta = [0.4, 0.1, 0.1][t]
+        g = rng.standard_normal((M, d)).astype(F)
+        ref.set_grads(g)
+        lazy.set_grads(g)
+        synced_step(ref, mu, eta_prev, eta, None, "%s group %d step %d" % (layout, group, t))
+        _raw_step(lazy, "sgdm", mu, eta_prev, eta)
+        _compare_outputs(lazy, ref, "%s group %d step %d" % (layout, group, t))
+        eta_prev = eta
+    ef.ef_flush(lazy.plan, lazy.e, lazy.te)
+    torch.cuda.synchronize()
+    _same_bits(lazy.e, ref.e, "residuals after flush")
+    with pytest.raises(ef.EfError):
+        ref.plan.set_sync_group(257)
+    with pytest.raises(ef.EfError):
+        ref.plan.set_sync_group(-1)
+    for st in (ref, lazy):
+        st.plan.close()
