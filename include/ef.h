@@ -166,16 +166,15 @@ int ef_plan_set_lazy(ef_plan *plan, int on);
 int ef_plan_is_lazy(const ef_plan *plan);
 
 /*
- * Writing out in step.  In the worker kernel that runs one workgroup per tile,
- * the whole tiles of a block larger than fuse_limit have nothing to wait for;
- * they are made to wait (bounded by spin_limit, and with nothing depending on
- * the outcome) for their neighbours, in groups of `tiles` consecutive tiles,
- * and then write together: workgroups that write at the same moment were
- * measured to stream faster than workgroups that each write when done (worker
- * call on 2^28 elements, 8 workers, deferred mode: 7.6 ms without, 6.9 ms in
- * groups of 16, 6.7 ms in groups of 32).  tiles = 0 or 1 turns it off;
- * at most 256; default 16.  Results do not depend on it.  Synchronises the
- * device.
+ * Writing the residual out in step.  In the worker kernel that runs one
+ * workgroup per tile, the whole tiles of a block larger than fuse_limit have
+ * nothing to wait for; they are made to wait (bounded by spin_limit, and with
+ * nothing depending on the outcome) for their neighbours, in groups of `tiles`
+ * consecutive tiles, before they write their residual tile: measured faster
+ * than workgroups that each write when done (worker call on 2^28 elements,
+ * 8 workers, deferred mode: 7.6 ms without, 6.75 ms in groups of 16, 6.9 ms
+ * in groups of 24 or 32).  tiles = 0 or 1 turns it off; at most 256; default
+ * 16.  Results do not depend on it.  Synchronises the device.
  */
 int ef_plan_set_sync_group(ef_plan *plan, int tiles);
 

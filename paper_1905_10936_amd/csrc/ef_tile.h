@@ -813,16 +813,18 @@ __device__ __forceinline__ void finish_uniform(float4 (&p)[SUBROWS], int32_t til
     store_tile(err_tile, p, n_valid);
 }
 
-// Writing out in step.  Measured on this machine: workgroups that take consecutive tiles and
-// write their results at the same moment (as the tiles of a small one-pass block do, which wait
-// for one scale) stream faster than workgroups that each write as soon as they are done
-// (2^28 elements, 8 workers: 6.6 ms in blocks of 8 to 16 tiles against 7.7 ms without any wait).
-// For a uniform tile of a block larger than fuse_limit nothing has to be waited for, so the kernel
-// that runs one workgroup per tile makes it wait for its neighbours instead: the whole tiles of
-// the block form groups of L.sync_group consecutive tiles; the last tile of a group looks for
-// this call's tag on the partial words of the others (posted just before) and then posts the
-// call number in its own ready line, where the others look for it.  Both waits are bounded, and
-// nothing depends on their outcome: whoever runs out of patience just writes.
+// Writing the residual out in step.  Measured on this machine: workgroups that take consecutive
+// tiles and hold their residual tile back until all of them have posted their partial sums (as
+// the tiles of a small one-pass block do, which wait for one scale) stream faster than workgroups
+// that each write as soon as they are done (2^28 elements, 8 workers: 6.6 ms in blocks of 8 to
+// 16 tiles against 7.7 ms without any wait; the momentum tile is written at once in both cases,
+// holding it back as well was measured slower).  For a uniform tile of a block larger than
+// fuse_limit nothing has to be waited for, so the kernel that runs one workgroup per tile makes
+// it wait for its neighbours instead: the whole tiles of the block form groups of L.sync_group
+// consecutive tiles; the last tile of a group looks for this call's tag on the partial words of
+// the others (posted just before) and then posts the call number in its own ready line, where
+// the others look for it.  Both waits are bounded, and nothing depends on their outcome:
+// whoever runs out of patience just writes.
 // Called by every thread of the workgroup, after compress_uniform returned UNI_HELD.
 __device__ __forceinline__ void sync_group_wait(int32_t tile, const Layout &L, const Scratch &X, int set, SyncShared &S)
 {
