@@ -30,7 +30,8 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE, scaled by a torch add kernel of known size run
 # in the same process): see profiles/ef_step_flat_2p28.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"flat_2p28": 43296770554}
+MEASURED_TRAFFIC_BYTES = {("flat_2p28", "direct"): 43318430224,        # ef::k_worker_uniform_direct<true>
+                          ("flat_2p28", "persistent"): 43296770554}    # ef::k_worker_uniform<true>
 
 
 def algorithmic_bytes(d, B, M, variant="sgdm"):
@@ -293,7 +294,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if variant == "sgdm" else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "persistent" if plan.persistent else "direct"))
+            if variant == "sgdm" and not plan.lazy else None,
             "algorithmic_bytes_per_launch": bw,
             "ms_per_launch": round(t_worker, 4),
             "practical_ceiling": None if ceiling is None else {
