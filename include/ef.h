@@ -107,7 +107,10 @@ int ef_plan_destroy(ef_plan *plan);
  * elements (2304 tiles, the persistent worker kernel's default limit on a GPU
  * with 256 compute units) costs 20.125 bytes of HBM traffic per element and
  * worker; a larger block has its corrected gradient written out and read back
- * once more (28.125 bytes).  Proposition 1 favours finer blocks as well.
+ * once more (28.125 bytes) unless the deferred mode is on (ef_plan_set_lazy).
+ * Within one pass, blocks of 8 to 64 tiles (32 K to 256 K elements) stream
+ * fastest (about 6 % faster than blocks of 256 tiles, 12 % faster than blocks
+ * of 1024).  Proposition 1 favours finer blocks as well.
  */
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
 int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit in force */
