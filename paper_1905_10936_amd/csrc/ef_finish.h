@@ -17,6 +17,17 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
     const int n_valid = tile_valid(L, tile);
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     float *err_tile = err_set + tile_start;
+    if (fb == lb && n_valid == TILE) {
+        // a whole tile of one block (a block beyond fuse_limit, or a tile whose wait ran out):
+        // streamed like the first pass streams it
+        float4 v[SUBROWS];
+        load_tile(err_tile, v, TILE);
+        const float sb = scales[fb];
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) residual4(v[k], sb);
+        store_tile(err_tile, v, TILE);
+        return;
+    }
     int lo, hi;
     float s;
     if (which == 0) {
