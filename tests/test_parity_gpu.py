@@ -303,3 +303,25 @@ def test_two_plans_on_two_streams_at_once():
         sb.plan.close()
     for u, v in zip(*outs):
         assert np.array_equal(u.view(np.uint8), v.view(np.uint8))
+
+
+def test_kernel_choice_follows_the_block_sizes():
+    """Plan creation picks the worker kernel from the layout (include/ef.h, ef_plan_set_persistent):
+    one workgroup per tile where the blocks are mostly up to 512 tiles or the layout is small, the
+    persistent kernel where they are larger or where only it finishes them in one pass."""
+    import ef_workloads as wl
+    expect = {"flat_2p28": False, "odd_tiles": False, "resnet50_like": False, "resnet20_like": False,
+              "transformer_like": True, "skewed_blocks": True}
+    for name, persistent in expect.items():
+        w = wl.get(name)
+        plan = ef.ef_plan_create(w.offsets, w.M)
+        assert plan.persistent == persistent, name
+        assert plan.fuse_limit == (2304 if persistent else 1024), name
+        plan.set_lazy(True)                  # deferred mode: one workgroup per tile unless asked otherwise
+        assert not plan.persistent and plan.fuse_limit == 64, name
+        plan.set_persistent(True)
+        assert plan.persistent and plan.fuse_limit == 0, name
+        plan.set_lazy(False)
+        plan.set_persistent(None)
+        assert plan.persistent == persistent, name
+        plan.close()
