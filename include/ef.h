@@ -355,6 +355,19 @@ int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t 
 int ef_stream_probe(const float *g, float *m, float *e, int64_t n_elements, int repeats, float *ms_per_pass,
                     void *stream);
 
+/*
+ * The same traffic as ef_stream_probe with one workgroup per tile in grid
+ * order and the third array written in step: the workgroups of `group`
+ * consecutive tiles (0..256; 0 or 1: no waiting) write m at once, wait
+ * (bounded) until all of them have loaded their tile, and then write e.  This
+ * is how the worker kernel's one-pass blocks and its sync groups
+ * (ef_plan_set_sync_group) access memory, without the compression: the
+ * ceiling of that pattern.  Arguments, result and errors as for
+ * ef_stream_probe; allocates 132 bytes per tile for the duration of the call.
+ */
+int ef_stream_probe_grouped(const float *g, float *m, float *e, int64_t n_elements, int group, int repeats,
+                            float *ms_per_pass, void *stream);
+
 /* Static text for an error code; for EF_ERR_HIP the text of the last HIP error
  * seen by this thread is appended.  The returned pointer stays valid until the
  * same thread calls ef_strerror again. */

@@ -23,7 +23,7 @@ EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1
 EF_MAX_WORKERS = 64
 
 ABI_SYMBOLS = (
-    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_plan_set_sync_group", "ef_flush", "ef_stream_probe", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_plan_set_sync_group", "ef_flush", "ef_stream_probe", "ef_stream_probe_grouped", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
     "ef_sign_words", "ef_worker_step", "ef_worker_step_sgd", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
     "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused", "ef_compressor_quality",
 )
@@ -66,6 +66,8 @@ def lib():
     L.ef_plan_set_sync_group.argtypes = [vp, c_int]
     L.ef_plan_is_lazy.restype = c_int
     L.ef_plan_is_lazy.argtypes = [vp]
+    L.ef_stream_probe_grouped.restype = c_int
+    L.ef_stream_probe_grouped.argtypes = [vp, vp, vp, i64, c_int, c_int, ctypes.POINTER(f32), vp]
     L.ef_stream_probe.restype = c_int
     L.ef_stream_probe.argtypes = [vp, vp, vp, i64, c_int, ctypes.POINTER(f32), vp]
     L.ef_flush.restype = c_int
@@ -256,6 +258,18 @@ def ef_stream_probe(g, m, e, repeats=5, stream=None):
     ms = ctypes.c_float(0.0)
     _check(lib().ef_stream_probe(_ptr(g, torch.float32, "g"), _ptr(m, torch.float32, "m"),
                                  _ptr(e, torch.float32, "e"), n, int(repeats), ctypes.byref(ms), _stream_ptr(stream)))
+    return float(ms.value), 20 * (n // 4096) * 4096
+
+
+def ef_stream_probe_grouped(g, m, e, group=16, repeats=5, stream=None):
+    """As ef_stream_probe, one workgroup per tile, e written in step by groups of `group` tiles."""
+    n = g.numel()
+    if m.numel() != n or e.numel() != n:
+        raise TypeError("g, m, e must have the same number of elements")
+    ms = ctypes.c_float(0.0)
+    _check(lib().ef_stream_probe_grouped(_ptr(g, torch.float32, "g"), _ptr(m, torch.float32, "m"),
+                                         _ptr(e, torch.float32, "e"), n, int(group), int(repeats), ctypes.byref(ms),
+                                         _stream_ptr(stream)))
     return float(ms.value), 20 * (n // 4096) * 4096
 
 

@@ -586,6 +586,52 @@ int ef_stream_probe(const float *g, float *m, float *e, int64_t n_elements, int 
     return rc;
 }
 
+int ef_stream_probe_grouped(const float *g, float *m, float *e, int64_t n_elements, int group, int repeats,
+                            float *ms_per_pass, void *stream)
+{
+    if (!g || !m || !e || !ms_per_pass) return EF_ERR_NULL;
+    if (n_elements < ef::TILE || n_elements / ef::TILE > 0x7fffffffll || repeats < 1 || repeats > 1000 || group < 0 ||
+        group > 256)
+        return EF_ERR_ARG;
+    if (!aligned(g, 16) || !aligned(m, 16) || !aligned(e, 16)) return EF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned n_tiles = (unsigned)(n_elements / ef::TILE);
+    unsigned int *arrive = nullptr;
+    unsigned long long *line = nullptr;
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    int rc = EF_OK;
+    float ms = 0.f;
+    unsigned pass = 0;
+    auto run = [&]() {
+        ++pass;         // never 0, the value of the cleared words
+        hipLaunchKernelGGL(ef::k_probe_grouped, dim3(n_tiles), dim3(ef::THREADS), 0, s, g, m, e, n_tiles, group, pass,
+                           arrive, line, 1 << 14);
+    };
+    const size_t line_bytes = sizeof(unsigned long long) * ef::READY_STRIDE * (size_t)n_tiles;
+    if (hipMalloc(&arrive, sizeof(unsigned int) * (size_t)n_tiles) != hipSuccess ||
+        hipMalloc(&line, line_bytes) != hipSuccess || hipEventCreate(&t0) != hipSuccess ||
+        hipEventCreate(&t1) != hipSuccess ||
+        hipMemsetAsync(arrive, 0, sizeof(unsigned int) * (size_t)n_tiles, s) != hipSuccess ||
+        hipMemsetAsync(line, 0, line_bytes, s) != hipSuccess) {
+        rc = EF_ERR_HIP;
+    } else {
+        run();                                      // warm-up
+        bool ok = hipEventRecord(t0, s) == hipSuccess;
+        for (int r = 0; r < repeats; ++r) run();
+        ok = ok && hipEventRecord(t1, s) == hipSuccess && hipEventSynchronize(t1) == hipSuccess &&
+             hipEventElapsedTime(&ms, t0, t1) == hipSuccess && hipGetLastError() == hipSuccess;
+        if (ok)
+            *ms_per_pass = ms / (float)repeats;
+        else
+            rc = EF_ERR_HIP;
+    }
+    if (t0) (void)hipEventDestroy(t0);
+    if (t1) (void)hipEventDestroy(t1);
+    if (arrive) (void)hipFree(arrive);
+    if (line) (void)hipFree(line);
+    return rc;
+}
+
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
 {
     if (!plan) return EF_ERR_NULL;

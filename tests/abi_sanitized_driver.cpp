@@ -61,6 +61,8 @@ int main()
     REQUIRE(ef_compressor_quality(nullptr, 1, buf, 64, q, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_stream_probe(nullptr, buf, buf, 4096, 1, &ms, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_stream_probe(buf, buf, buf, 64, 1, &ms, nullptr) == EF_ERR_ARG);
+    REQUIRE(ef_stream_probe_grouped(nullptr, buf, buf, 4096, 16, 1, &ms, nullptr) == EF_ERR_NULL);
+    REQUIRE(ef_stream_probe_grouped(buf, buf, buf, 64, 16, 1, &ms, nullptr) == EF_ERR_ARG);
 
     REQUIRE(ef_sign_words(0) == 0 && ef_sign_words(1) == 1 && ef_sign_words(64) == 1 && ef_sign_words(65) == 2);
     REQUIRE(ef_sign_words(-5) == 0);

@@ -25,6 +25,28 @@ def test_probe_runs_and_stays_in_bounds():
     assert bool(torch.isfinite(m).all()) and bool(torch.isfinite(e).all())
 
 
+@pytest.mark.parametrize("group", [0, 1, 3, 16, 256])
+def test_grouped_probe_runs_and_stays_in_bounds(group):
+    n = 37 * 4096 + 100
+    g = torch.randn(n, device="cuda")
+    m = torch.randn(n, device="cuda")
+    e = torch.randn(n, device="cuda")
+    g0, m0, e0 = g.clone(), m.clone(), e.clone()
+    ms, nbytes = ef.ef_stream_probe_grouped(g, m, e, group=group, repeats=2)
+    torch.cuda.synchronize()
+    assert ms > 0.0 and nbytes == 20 * 37 * 4096
+    assert torch.equal(g, g0)
+    assert torch.equal(m[37 * 4096:], m0[37 * 4096:]) and torch.equal(e[37 * 4096:], e0[37 * 4096:])
+    # three passes (one warm-up) of m <- m/2 + g, e <- e/2 + m on every whole tile
+    mm, ee = m0[:37 * 4096].clone(), e0[:37 * 4096].clone()
+    for _ in range(3):
+        mm = 0.5 * mm + g0[:37 * 4096]
+        ee = 0.5 * ee + mm
+    assert torch.allclose(m[:37 * 4096], mm, rtol=1e-5, atol=1e-6) and torch.allclose(e[:37 * 4096], ee, rtol=1e-5, atol=1e-6)
+    with pytest.raises(ef.EfError):
+        ef.ef_stream_probe_grouped(g, m, e, group=257)
+
+
 def test_probe_argument_checks():
     g = torch.zeros(8192, device="cuda")
     with pytest.raises(ef.EfError):
