@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE, scaled by a torch add kernel of known size run
 # in the same process): see profiles/ef_step_flat_2p28.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {("flat_2p28", "direct"): 43318430224,        # ef::k_worker_uniform_direct<true>
+MEASURED_TRAFFIC_BYTES = {("flat_2p28", "direct"): 43318642898,        # ef::k_worker_uniform_direct<true>
                           ("flat_2p28", "persistent"): 43296770554}    # ef::k_worker_uniform<true>
 
 
