@@ -325,3 +325,25 @@ def test_kernel_choice_follows_the_block_sizes():
         plan.set_persistent(None)
         assert plan.persistent == persistent, name
         plan.close()
+
+
+@pytest.mark.parametrize("route", ["one_pass", "direct", "two_pass"])
+def test_subnormal_values_are_kept(route):
+    """Gradients in and around the subnormal range of fp32 (below 1.2e-38): Algorithm 4's products,
+    sums and sign decisions must treat them as IEEE-754 does on the host, nothing flushed to zero
+    (a flushed negative subnormal would flip its sign bit to +1)."""
+    offs = _offs(LAYOUTS["mixed_tiny_and_big"])
+    d = int(offs[-1])
+    M = 3
+    rng = np.random.default_rng(4141)
+    st = GpuState(offs, M, x0=(rng.standard_normal(d) * 1e-39).astype(F), route=route)
+    eta_prev = 0.0
+    for t in range(3):
+        scale = 10.0 ** rng.uniform(-44, -37, size=(M, d))
+        g = (rng.standard_normal((M, d)) * scale).astype(F)
+        g[rng.random((M, d)) < 0.05] = 0.0
+        assert (np.abs(g[g != 0]) < 1.1754944e-38).mean() > 0.3          # many subnormal inputs
+        st.set_grads(g)
+        synced_step(st, 0.9, eta_prev, 0.1, None, "subnormal %s step %d" % (route, t))
+        eta_prev = 0.1
+    st.plan.close()
