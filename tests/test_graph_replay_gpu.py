@@ -25,7 +25,7 @@ def _eager_step(st, mu, eta_prev, eta):
     ef.ef_apply(st.plan, st.x, st.ss, st.sc, eta)
 
 
-@pytest.mark.parametrize("route", ["one_pass", "direct", "deferred", "two_pass"])
+@pytest.mark.parametrize("route", ["one_pass", "direct", "deferred", "two_pass", "direct_mixed", "direct_deferred"])
 def test_graph_replays_match_eager_calls(route):
     offs = _offs(LAYOUTS["mixed_tiny_and_big"])
     d = int(offs[-1])
