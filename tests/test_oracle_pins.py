@@ -580,3 +580,31 @@ def test_oracle_rejects_bad_partitions():
     for offs in ([0, 2, 2, 4], [1, 4], [0, 3], [0, 5], [0, 3, 2, 4]):
         with pytest.raises(oracle.OracleError):
             oracle.compress(v, offs)
+
+
+# ------------------------------------ large blocks: exactly rounded sums ---
+
+def test_scale_of_a_large_block_against_the_exactly_rounded_sum():
+    """Section 3.2: scale_b = ||v_Gb||_1 / d_b.  For blocks of 10^5 to 10^6 elements with magnitudes
+    spread over many binades, math.fsum gives the correctly rounded fp64 value of the L1 norm; the
+    oracle's ascending fp64 sum may differ from it by at most n * 2^-53 relative, so the fp32 scale
+    is the correctly rounded one or its neighbour, and is the correctly rounded one whenever the
+    exact quotient is not within that distance of a rounding boundary."""
+    import math
+    rng = np.random.default_rng(2024)
+    sizes = [100003, 1 << 20, 250000]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    v = (rng.standard_normal(int(offs[-1])) * 10.0 ** rng.uniform(-6, 3, int(offs[-1]))).astype(F)
+    _, scales = oracle.compress(v, offs)
+    for b, n in enumerate(sizes):
+        seg = np.abs(v[offs[b]:offs[b + 1]].astype(np.float64))
+        exact = math.fsum(seg.tolist()) / n
+        want = np.float32(exact)
+        got = scales[b]
+        assert abs(float(got) - exact) <= abs(exact) * (2.0 ** -24 + n * 2.0 ** -53)
+        ulp = np.spacing(want)
+        assert abs(float(got) - float(want)) <= float(ulp)
+        # away from a rounding boundary the two must be the same float
+        lo, hi = float(want) - float(ulp) / 2, float(want) + float(ulp) / 2
+        if min(exact - lo, hi - exact) > abs(exact) * n * 2.0 ** -52:
+            assert got == want

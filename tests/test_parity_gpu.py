@@ -347,3 +347,32 @@ def test_subnormal_values_are_kept(route):
         synced_step(st, 0.9, eta_prev, 0.1, None, "subnormal %s step %d" % (route, t))
         eta_prev = 0.1
     st.plan.close()
+
+
+@pytest.mark.parametrize("route", ["one_pass", "direct", "two_pass"])
+def test_gpu_scales_against_the_exactly_rounded_sum(route):
+    """The GPU's fixed-tree fp64 sums checked against the exactly rounded L1 norm (math.fsum), not
+    against the oracle: with mu = 0 and a zero residual p is the gradient itself, so the scale of
+    block b is ||g_b||_1 / d_b (Section 3.2).  It must be the correctly rounded fp32 value or its
+    neighbour, and the correctly rounded one away from rounding boundaries."""
+    import math
+    rng = np.random.default_rng(31337)
+    sizes = [100003, 1 << 20, 5, 250000, 4096, 3 * 4096 + 1]
+    offs = _offs(sizes)
+    d = int(offs[-1])
+    st = GpuState(offs, 1, route=route)
+    g = (rng.standard_normal((1, d)) * 10.0 ** rng.uniform(-6, 3, (1, d))).astype(F)
+    st.set_grads(g)
+    ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.0, 0.0, 0.1, st.ws, st.wc)
+    torch.cuda.synchronize()
+    scales = to_np(st.wc)[0]
+    for b, n in enumerate(sizes):
+        seg = np.abs(g[0, offs[b]:offs[b + 1]].astype(np.float64))
+        exact = math.fsum(seg.tolist()) / n
+        want = np.float32(exact)
+        ulp = float(np.spacing(want))
+        assert abs(float(scales[b]) - float(want)) <= ulp, (b, scales[b], want)
+        lo, hi = float(want) - ulp / 2, float(want) + ulp / 2
+        if min(exact - lo, hi - exact) > abs(exact) * n * 2.0 ** -52:
+            assert scales[b] == want, (b, scales[b], want)
+    st.plan.close()
