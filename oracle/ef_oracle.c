@@ -33,8 +33,9 @@
  *
  * Pins (tests/test_oracle_pins.py): every function here is pinned by closed
  * forms, the paper's constant-magnitude example, the Proposition 1 energy
- * identity, the Lemma 3 recurrence, brute force on tiny inputs, and special
- * cases (identity compressor, M = 1, majority vote).  The Algorithm 3 worker
+ * identity, the Lemma 3 recurrence, brute force on tiny inputs, the exactly
+ * rounded L1 norm of blocks of up to 10^6 elements, and special cases
+ * (identity compressor, M = 1, majority vote).  The Algorithm 3 worker
  * is pinned to the Algorithm 4 worker at mu = 0 (the reduction Section 4.1
  * states) and to the brute force; the Appendix A update to efo_apply at
  * lambda = 0, to a float64 run of the decay-momentum recursion on dyadic values
