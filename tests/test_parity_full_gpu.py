@@ -13,6 +13,9 @@ otherwise.  On top of the samples, properties that hold at any size are checked
 over the whole vectors on the GPU (payload padding bits, Proposition 1 energy
 identity, the reconstruction p = C(p) + e').
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -23,6 +26,9 @@ import paper_1905_10936_amd as ef
 from tests.parity_util import F, check_scales, check_vector
 
 pytestmark = pytest.mark.gpu
+
+# oracle calls of independent workers run side by side (each call is the plain single-thread code)
+ORACLE_THREADS = max(1, min(8, (os.cpu_count() or 1)))
 
 
 def _cat(t, offs, blocks):
@@ -65,6 +71,81 @@ def _sample_blocks(w, rng, n_random, max_elems):
             out.append(b)
             tot += int(sizes[b])
     return sorted(out)
+
+
+def _decode_full(w, ws, wc):
+    """Delta of a payload over the whole vector, fp64 on the device, and the per-element scale."""
+    dev = ws.device
+    sizes = torch.as_tensor(np.diff(w.offsets), device=dev)
+    bid = torch.repeat_interleave(torch.arange(w.B, device=dev), sizes)
+    scale_b = wc[bid].double()
+    del bid
+    idx = torch.arange(w.d, device=dev)
+    bits = ((ws[idx // 64] >> (idx % 64)) & 1).bool()
+    return bits, scale_b
+
+
+def _props_from_p(w, tag, p_full, mag, ws, wc, e_new):
+    """Properties of one compression step that hold at any size, over the whole vector, in fp64
+    torch operations on the device (neither the library nor the oracle is involved): the payload's
+    bits are the signs of p, its scales are the blocks' mean |p|, p = C(p) + e' elementwise, the
+    Proposition 1 identity ||e'_b||^2 = ||p_b||^2 - ||p_b||_1^2 / d_b per block, and zero padding
+    bits.  p_full: p evaluated in fp64 from the inputs; mag: the size of its fp32 terms (bounds the
+    rounding of the fp32 evaluation); ws, wc, e_new: the step's outputs."""
+    dev = p_full.device
+    offs, d = w.offsets, w.d
+    bits, scale_b = _decode_full(w, ws, wc)
+    rec = torch.where(bits, scale_b, -scale_b) + e_new.double()
+    assert bool(((rec - p_full).abs() <= 2e-6 * (mag + scale_b) + 1e-30).all()), tag + ": p = C(p) + e' violated"
+    assert bool((bits == (p_full >= 0))[p_full.abs() > 1e-5 * (mag + scale_b)].all()), tag + ": a sign bit is not sign(p)"
+    del rec, bits, scale_b
+    # per-block sums as differences of fp64 running sums (index_add_ would serialise
+    # millions of atomic adds on the one address of a large block)
+    ends = torch.as_tensor(offs[1:] - 1, device=dev)
+
+    def block_sums(v):
+        cs = torch.cumsum(v, 0)[ends]
+        return torch.diff(cs, prepend=torch.zeros(1, dtype=torch.float64, device=dev))
+
+    l1, l2, en = block_sums(p_full.abs()), block_sums(p_full * p_full), block_sums(e_new.double() ** 2)
+    db = torch.as_tensor(np.diff(offs), device=dev).double()
+    tot = float(p_full.abs().sum())          # the running sums carry ~1e-16 * total of rounding
+    assert bool(((en - (l2 - l1 * l1 / db)).abs() <= 1e-5 * l2 + 1e-12 * tot * tot + 1e-30).all()), \
+        tag + ": Proposition 1 identity violated"
+    assert bool(((wc.double() - l1 / db).abs() <= 2e-6 * (l1 / db) + 1e-12 * tot + 1e-30).all()), \
+        tag + ": a scale is not the block's mean |p|"
+    if d % 64:
+        assert int(ws[-1].item()) >> (d % 64) == 0, tag + ": padding bits set"
+
+
+def whole_vector_props(w, tag, g, m_pre, e_pre, has_prev, ws, wc, e_new):
+    """_props_from_p for one worker's step.  g, m_pre, e_pre: the worker's gradient and its state
+    before the step (constant stepsize, so the ratio of Algorithm 4 is 1 after the first step)."""
+    p_full = w.mu * (w.mu * m_pre.double() + g.double()) + g.double()
+    mag = w.mu * w.mu * m_pre.double().abs() + (1 + w.mu) * g.double().abs()   # size of the fp32 terms
+    if has_prev:
+        p_full += e_pre.double()
+        mag += e_pre.double().abs()
+    _props_from_p(w, tag, p_full, mag, ws, wc, e_new)
+
+
+def whole_vector_props_server(w, tag, ws_all, wc_all, te_pre, has_prev, ss, sc, te_new):
+    """_props_from_p for the server's step: p~ = (1/M) sum_i Delta_i + e~ (constant stepsize)."""
+    M = ws_all.shape[0]
+    p_full = torch.zeros(w.d, dtype=torch.float64, device=ss.device)
+    mag = torch.zeros_like(p_full)
+    for i in range(M):
+        bits, scale_b = _decode_full(w, ws_all[i], wc_all[i])
+        p_full += torch.where(bits, scale_b, -scale_b)
+        mag += scale_b
+        del bits, scale_b
+    p_full /= M
+    mag /= M
+    mag *= 1 + M / 16.0          # M fp32 additions, each within half an ulp of a partial sum no larger than mag * M
+    if has_prev:
+        p_full += te_pre.double()
+        mag += te_pre.double().abs()
+    _props_from_p(w, tag, p_full, mag, ss, sc, te_new)
 
 
 def _run_sampled(w, steps, blocks, workers=None, check_props=True, variant="sgdm", etas=None):
@@ -117,11 +198,7 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True, variant="sgdm
         g_s, m_s, e_s = _cat(g, offs, blocks), _cat(m, offs, blocks), _cat(e, offs, blocks)
         te_s, x_s = _cat(te, offs, blocks), _cat(x, offs, blocks)
         if check_props:
-            p_full = w.mu * (w.mu * m[0].double() + g[0].double()) + g[0].double()
-            mag = w.mu * w.mu * m[0].double().abs() + (1 + w.mu) * g[0].double().abs()   # size of the fp32 terms
-            if eta_prev:
-                p_full += e[0].double()           # constant stepsize: ratio 1
-                mag += e[0].double().abs()
+            m_pre, e_pre = m.clone(), e.clone()
         ws.fill_(0x5555555555555555)
         wc.fill_(-7.0)
         print("[%s/%s] step %d: worker step on the GPU" % (w.name, variant, t), flush=True)
@@ -137,13 +214,20 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True, variant="sgdm
         wbits = _bits(ws, offs, blocks)
         wc_s = wc[:, bsel].cpu().numpy()
         m_out, e_out = _cat(m, offs, blocks), _cat(e, offs, blocks)
-        for i in workers:
+
+        def oracle_worker(i):
             mi, ei = np.ascontiguousarray(m_s[i]), np.ascontiguousarray(e_s[i])
             if variant == "sgd":
                 s_ref, c_ref = oracle.worker_step_sgd(np.ascontiguousarray(g_s[i]), ei, sub_offs, F(eta_prev), F(eta))
             else:
                 s_ref, c_ref = oracle.worker_step(np.ascontiguousarray(g_s[i]), mi, ei, sub_offs, F(w.mu),
                                                   F(eta_prev), F(eta))
+            return mi, ei, s_ref, c_ref
+
+        # the workers are independent: one oracle call each, side by side on the host's cores
+        with ThreadPoolExecutor(max_workers=ORACLE_THREADS) as pool:
+            refs = list(pool.map(oracle_worker, workers))
+        for i, (mi, ei, s_ref, c_ref) in zip(workers, refs):
             tag = "%s step %d worker %d" % (w.name, t, i)
             ref_bits = np.unpackbits(s_ref.view(np.uint8), bitorder="little")[:wbits.shape[-1]]
             assert np.array_equal(wbits[i], ref_bits), "%s: %d sign bits differ" % (tag, (wbits[i] != ref_bits).sum())
@@ -152,43 +236,25 @@ def _run_sampled(w, steps, blocks, workers=None, check_props=True, variant="sgdm
             loose += int((~same).sum())
             check_vector(e_out[i], ei, c_ref, same, sub_offs, tag + " residual")
         if check_props:
-            print("[%s] step %d: whole-vector properties" % (w.name, t), flush=True)
-            # properties over the whole vector of worker 0 (fp64 on the GPU)
-            bid = torch.repeat_interleave(torch.arange(B, device=dev), torch.as_tensor(np.diff(offs), device=dev))
-            dec = wc[0][bid].double()
-            bits0 = ((ws[0][torch.arange(d, device=dev) // 64] >> (torch.arange(d, device=dev) % 64)) & 1).bool()
-            dec = torch.where(bits0, dec, -dec)
-            rec = dec + e[0].double()
-            scale_b = wc[0][bid].double()
-            assert bool(((rec - p_full).abs() <= 2e-6 * (mag + scale_b) + 1e-30).all()), \
-                "%s step %d: p = C(p) + e' violated" % (w.name, t)
-            assert bool((bits0 == (p_full >= 0))[p_full.abs() > 1e-5 * (mag + scale_b)].all())
-            # per-block sums as differences of fp64 running sums (index_add_ would serialise
-            # millions of atomic adds on the one address of a large block)
-            ends = torch.as_tensor(offs[1:] - 1, device=dev)
-
-            def block_sums(v):
-                cs = torch.cumsum(v, 0)[ends]
-                return torch.diff(cs, prepend=torch.zeros(1, dtype=torch.float64, device=dev))
-
-            l1, l2, en = block_sums(p_full.abs()), block_sums(p_full * p_full), block_sums(e[0].double() ** 2)
-            db = torch.as_tensor(np.diff(offs), device=dev).double()
-            tot = float(p_full.abs().sum())          # the running sums carry ~1e-16 * total of rounding
-            assert bool(((en - (l2 - l1 * l1 / db)).abs() <= 1e-5 * l2 + 1e-12 * tot * tot + 1e-30).all()), \
-                "Prop. 1 identity violated"
-            assert bool(((wc[0].double() - l1 / db).abs() <= 2e-6 * (l1 / db) + 1e-12 * tot + 1e-30).all())
-            del bid, dec, bits0, rec, scale_b, l1, l2, en, db, p_full, ends, mag
-            if d % 64:
-                assert int(ws[0, -1].item()) >> (d % 64) == 0, "padding bits set"
+            print("[%s] step %d: whole-vector properties, all %d workers" % (w.name, t, M), flush=True)
+            for i in range(M):
+                whole_vector_props(w, "%s step %d worker %d" % (w.name, t, i), g[i], m_pre[i], e_pre[i], bool(eta_prev),
+                                   ws[i], wc[i], e[i])
+            del m_pre, e_pre
         # ---- server on the GPU's worker payloads
         ss.fill_(0x5555555555555555)
         sc.fill_(-7.0)
         print("[%s] step %d: server step" % (w.name, t), flush=True)
+        if check_props:
+            te_pre = te.clone()
         if variant == "fused":
             ef.ef_server_step_fused(plan, M, wmsg, te, eta_prev, eta, smsg)
         else:
             ef.ef_server_step(plan, M, ws, wc, te, eta_prev, eta, ss, sc)
         torch.cuda.synchronize()
+        if check_props:
+            whole_vector_props_server(w, "%s step %d server" % (w.name, t), ws, wc, te_pre, bool(eta_prev), ss, sc, te)
+            del te_pre
         te_ref = np.ascontiguousarray(te_s)
         ss_ref, sc_ref = oracle.server_step(_pack(wbits), np.ascontiguousarray(wc_s), te_ref, sub_offs, F(eta_prev),
                                             F(eta))
@@ -252,11 +318,11 @@ def test_skewed_blocks_sampled():
 
 def test_transformer_like_sampled():
     """Configuration 5: the 51 M-element embedding block (several times the
-    one-pass limit), one layer's 12 tensors and the last block, for 2 of the 16
-    workers on the oracle side; the GPU runs all 16."""
+    one-pass limit), one layer's 12 tensors and the last block through the oracle for all
+    16 workers, and the whole-vector properties of every worker and of the server."""
     w = wl.get("transformer_like")
     blocks = [0] + list(range(1, 13)) + [w.B - 1]
-    _run_sampled(w, w.steps, blocks, workers=[0, 15], check_props=False)
+    _run_sampled(w, w.steps, blocks)
 
 
 def test_flat_2p28_momentum_free_worker_sampled():
