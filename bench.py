@@ -24,6 +24,7 @@ sys.path.insert(0, ROOT)
 
 import ef_workloads as wl  # noqa: E402
 import paper_1905_10936_amd as ef  # noqa: E402
+from paper_1905_10936_amd import bench_probe  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 
@@ -264,9 +265,9 @@ def main():
     ceiling = ceiling_ticketed = ceiling_grouped = None
     if variant != "sgd" and M * ds >= 4096:
         torch.cuda.synchronize()
-        p_ms, p_bytes = ef.ef_stream_probe(grads[0].view(-1), mom.view(-1), err.view(-1), repeats=3)
+        p_ms, p_bytes = bench_probe.ef_stream_probe(grads[0].view(-1), mom.view(-1), err.view(-1), repeats=3)
         ceiling_ticketed = p_bytes / (p_ms * 1e-3) / 1e9
-        p_ms, p_bytes = ef.ef_stream_probe_grouped(grads[0].view(-1), mom.view(-1), err.view(-1), group=16, repeats=3)
+        p_ms, p_bytes = bench_probe.ef_stream_probe_grouped(grads[0].view(-1), mom.view(-1), err.view(-1), group=16, repeats=3)
         ceiling_grouped = p_bytes / (p_ms * 1e-3) / 1e9
         ceiling = max(ceiling_ticketed, ceiling_grouped)
 

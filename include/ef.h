@@ -90,50 +90,6 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
 int ef_plan_destroy(ef_plan *plan);
 
 /*
- * Tuning knobs of the one-pass residual update (e <- p - Delta of Algorithm 4
- * needs the whole block's scale): workgroups of a block spanning at most
- * fuse_limit tiles of 4096 elements keep p in registers and wait for the scale,
- * polling at most spin_limit times before they fall back to the two-pass route
- * that larger blocks always take.  Results are identical on either route.
- * Negative values leave a setting unchanged; fuse_limit = 0 sends every block
- * through two passes, spin_limit = 0 makes every wait give up at once (used by
- * tests to exercise the fallback).  Synchronises the device.  By default each
- * kernel gets its own limit: half the tiles its workgroups can hold at once
- * (resident workgroups; times six for the persistent worker kernel, which
- * keeps three tiles in registers and three in LDS), at most 4096 tiles.  A
- * limit set here applies to worker and server alike.
- *
- * For the caller's choice of blocks this means: a block of up to about 9.4 M
- * elements (2304 tiles, the persistent worker kernel's default limit on a GPU
- * with 256 compute units) costs 20.125 bytes of HBM traffic per element and
- * worker; a larger block has its corrected gradient written out and read back
- * once more (28.125 bytes) unless the deferred mode is on (ef_plan_set_lazy).
- * Within one pass, blocks of 8 to 64 tiles (32 K to 256 K elements) stream
- * fastest (about 6 % faster than blocks of 256 tiles, 12 % faster than blocks
- * of 1024).  Proposition 1 favours finer blocks as well.
- */
-int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit);
-int ef_plan_fuse_limit(const ef_plan *plan);       /* the worker kernels' limit in force */
-
-/*
- * Which kernel the worker calls run over the tiles that lie inside one block:
- * on = 1 a persistent kernel whose workgroups take tiles from a ticket counter
- * and keep several tiles in registers while their scales form; on = 0 one
- * workgroup per tile that waits in place for its block's scale; on < 0 the
- * choice plan creation made for this layout: the persistent kernel if every
- * workgroup gets at least 16 tiles and the layout's blocks are cheaper on it
- * by the measured cost per tile of either kernel (one workgroup per tile is
- * the faster on blocks of up to 256 tiles, the persistent kernel on larger
- * ones, and it finishes blocks of 1025 to 2304 tiles in one pass that the
- * other sends through the second pass).  ef_worker_step_sgd, and every worker
- * call in the deferred mode (ef_plan_set_lazy), use the persistent kernel only
- * after on = 1.  The server always runs one workgroup per tile.  Same results
- * either way.  Synchronises the device.
- */
-int ef_plan_set_persistent(ef_plan *plan, int on);
-int ef_plan_is_persistent(const ef_plan *plan);
-
-/*
  * Deferred residual correction, off by default.  Algorithm 4 ends a worker's
  * (and the server's) step with e <- p - Delta.  For a block of more than
  * fuse_limit tiles the scale of Delta is known only after the first kernel
@@ -153,33 +109,20 @@ int ef_plan_is_persistent(const ef_plan *plan);
  *     of it: while corrections are waiting, a worker, server or flush call
  *     with another err / server_err pointer or stride than the call that
  *     left them returns EF_ERR_ARG;
- *   - ef_plan_tune (fuse_limit), ef_plan_set_persistent and ef_plan_set_lazy
- *     return EF_ERR_ARG while any buffer is waiting for its correction, since
- *     they change which blocks count as large: call ef_flush first.
+ *   - ef_plan_set_lazy, and the tuning calls of ef_debug.h that move the
+ *     one-pass limit, return EF_ERR_ARG while any buffer is waiting for its
+ *     correction, since they change which blocks count as large: call
+ *     ef_flush first.
  * Blocks of at most fuse_limit tiles, and the parts of large blocks that
  * share a tile with another block, are corrected in the call as before.
- * Unless ef_plan_tune has set a limit, the mode picks its own: 0 for the
- * server (no workgroup waits for a scale) and 64 tiles for the worker, which
- * then runs one workgroup per tile unless ef_plan_set_persistent(plan, 1) asks
- * for the persistent kernel (limit 0).  Measured on 2^28 elements in 256
+ * The mode picks its own one-pass limits: 0 for the server (no workgroup
+ * waits for a scale) and 64 tiles for the worker, which then runs one
+ * workgroup per tile.  Measured on 2^28 elements in 256
  * blocks with 8 workers: 7.5 instead of 8.0 ms per step.
  * ef_plan_set_lazy synchronises the device.
  */
 int ef_plan_set_lazy(ef_plan *plan, int on);
 int ef_plan_is_lazy(const ef_plan *plan);
-
-/*
- * Writing the residual out in step.  In the worker kernel that runs one
- * workgroup per tile, the whole tiles of a block larger than fuse_limit have
- * nothing to wait for; they are made to wait (bounded by spin_limit, and with
- * nothing depending on the outcome) for their neighbours, in groups of `tiles`
- * consecutive tiles, before they write their residual tile: measured faster
- * than workgroups that each write when done (worker call on 2^28 elements,
- * 8 workers, deferred mode: 7.6 ms without, 6.75 ms in groups of 16, 6.9 ms
- * in groups of 24 or 32).  tiles = 0 or 1 turns it off; at most 256; default
- * 16.  Results do not depend on it.  Synchronises the device.
- */
-int ef_plan_set_sync_group(ef_plan *plan, int tiles);
 
 /*
  * Makes the deferred corrections now: err (device, [n_workers][state_stride],
@@ -192,20 +135,10 @@ int ef_plan_set_sync_group(ef_plan *plan, int tiles);
  */
 int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_stride, float *server_err, void *stream);
 
-/*
- * How often the most recent ef_worker_step / ef_server_step on this plan left
- * the one-pass route at run time: tiles whose wait for the block scale was not
- * taken or ran out (p parked, finished by the second pass) and blocks whose
- * scale had to be formed by the second pass.  Results do not depend on these
- * counts; they are a performance diagnostic.  Synchronises the device.  Either
- * pointer may be NULL (HOST pointers).
- */
-int ef_plan_last_fallbacks(ef_plan *plan, unsigned int *parked_tiles, unsigned int *late_blocks);
-
-int64_t ef_plan_d(const ef_plan *plan);          /* d = block_offsets[B] */
-int64_t ef_plan_blocks(const ef_plan *plan);     /* B */
-int64_t ef_plan_sign_words(const ef_plan *plan); /* W = ceil(d/64) */
-int64_t ef_sign_words(int64_t d);                /* same, without a plan */
+int64_t ef_plan_d(const ef_plan *plan);      /* d = block_offsets[B] */
+int64_t ef_plan_blocks(const ef_plan *plan); /* B */
+size_t ef_sign_words(const ef_plan *plan);   /* W = ceil(d/64): 64-bit words of one payload's sign bits (Section 3.2:
+                                                d bits per direction, Table 1); 0 for a NULL plan */
 
 /*
  * Worker side of iteration t of Algorithm 4, for n_workers workers at once
@@ -221,8 +154,10 @@ int64_t ef_sign_words(int64_t d);                /* same, without a plan */
  *   mom, err      in/out  float[n_workers][state_stride], updated in place
  *   packed_signs  out     uint64[n_workers][W]
  *   scales        out     float[n_workers][B]
- * Strides are in elements, >= d and multiples of 4.  Outputs must not overlap
- * inputs or each other.
+ * Strides are in elements, >= d and multiples of 4 (with n_workers = 1 they are
+ * not used and not checked).  mom and err are updated in place; apart from
+ * that no two arguments may share memory: a payload buffer that overlaps grad,
+ * mom or err, or state buffers that overlap each other, give EF_ERR_ARG.
  */
 int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride,
                    float *mom, float *err, int64_t state_stride, float mu, float eta_prev,
@@ -255,6 +190,8 @@ int ef_worker_step_sgd(const ef_plan *plan, int n_workers, const float *grad, in
  *   server_err    in/out  float[d]
  *   out_signs     out     uint64[W]
  *   out_scales    out     float[B]
+ * server_err is updated in place; the outgoing payload may overlap neither the
+ * incoming payloads nor server_err (EF_ERR_ARG).
  */
 int ef_server_step(const ef_plan *plan, int M, const uint64_t *packed_signs, const float *scales,
                    float *server_err, float eta_prev, float eta, uint64_t *out_signs,
@@ -332,41 +269,12 @@ int ef_apply_fused(const ef_plan *plan, float *params, const void *payload, floa
  *   v     in   float[n_vectors][stride], stride >= d and a multiple of 4
  *   out   out  double[2 * n_vectors], device memory, 8-byte aligned
  *   n_vectors in [1, max_workers]
- * The first call on a plan allocates scratch (48 bytes per tile and vector) and synchronises;
- * like the other calls it must be ordered on the device with every call that shares the plan.
+ * Uses scratch the plan allocated at creation (48 bytes per tile and vector); like the other
+ * calls it allocates nothing, and it must be ordered on the device with every call that shares
+ * the plan.
  */
 int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out,
                           void *stream);
-
-/*
- * Measurement aid, not part of Algorithm 4: streams the worker step's memory
- * traffic with nothing else in it.  For every whole 4096-element tile of
- * g, m, e (device, >= n_elements floats each, 16-byte aligned, distinct) it
- * reads all three and writes m and e, 20 bytes per element, with the worker
- * kernel's loads, stores, tile shape and ticket order, but no compression and
- * no waiting; m and e hold garbage afterwards.  Runs one warm-up pass and
- * `repeats` (1..1000) timed passes on `stream`, waits for them, and stores
- * the mean time of a pass in *ms_per_pass (host): 20 * (n_elements rounded
- * down to whole tiles) bytes / that time is the practical ceiling of this
- * access pattern on the machine, to set beside ef_worker_step's rate.
- * Allocates a counter and two events for the duration of the call.
- * EF_ERR_ARG for fewer than 4096 elements or repeats out of range.
- */
-int ef_stream_probe(const float *g, float *m, float *e, int64_t n_elements, int repeats, float *ms_per_pass,
-                    void *stream);
-
-/*
- * The same traffic as ef_stream_probe with one workgroup per tile in grid
- * order and the third array written in step: the workgroups of `group`
- * consecutive tiles (0..256; 0 or 1: no waiting) write m at once, wait
- * (bounded) until all of them have loaded their tile, and then write e.  This
- * is how the worker kernel's one-pass blocks and its sync groups
- * (ef_plan_set_sync_group) access memory, without the compression: the
- * ceiling of that pattern.  Arguments, result and errors as for
- * ef_stream_probe; allocates 132 bytes per tile for the duration of the call.
- */
-int ef_stream_probe_grouped(const float *g, float *m, float *e, int64_t n_elements, int group, int repeats,
-                            float *ms_per_pass, void *stream);
 
 /* Static text for an error code; for EF_ERR_HIP the text of the last HIP error
  * seen by this thread is appended.  The returned pointer stays valid until the

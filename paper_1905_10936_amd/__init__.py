@@ -22,10 +22,19 @@ LIB_PATH = os.path.join(_HERE, "libef.so")
 EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1, -2, -3, -4, -5
 EF_MAX_WORKERS = 64
 
+# what include/ef.h declares (the boundary of Algorithm 4) ...
 ABI_SYMBOLS = (
-    "ef_plan_create", "ef_plan_destroy", "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_plan_set_sync_group", "ef_flush", "ef_stream_probe", "ef_stream_probe_grouped", "ef_plan_last_fallbacks", "ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words",
-    "ef_sign_words", "ef_worker_step", "ef_worker_step_sgd", "ef_server_step", "ef_apply", "ef_apply_wd", "ef_strerror",
-    "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused", "ef_compressor_quality",
+    "ef_plan_create", "ef_plan_destroy", "ef_plan_d", "ef_plan_blocks", "ef_sign_words",
+    "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
+    "ef_worker_step_sgd", "ef_apply_wd",
+    "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused",
+    "ef_compressor_quality",
+    "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_flush",
+)
+# ... and what include/ef_debug.h declares (tuning and diagnostics the tests use)
+DEBUG_SYMBOLS = (
+    "ef_plan_tune", "ef_plan_fuse_limit", "ef_plan_set_persistent", "ef_plan_is_persistent", "ef_plan_set_sync_group",
+    "ef_plan_last_fallbacks",
 )
 
 
@@ -44,16 +53,21 @@ def lib():
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        _build.build(force=True)
+        _build.build(force=True, lib=LIB_PATH)
+    elif _build.stale(LIB_PATH):
+        import warnings
+        warnings.warn("libef.so is older than its sources: run paper_1905_10936_amd/build.py", RuntimeWarning)
     L = ctypes.CDLL(LIB_PATH)
     vp, i64, c_int, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
     L.ef_plan_create.restype = c_int
     L.ef_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(i64), i64, c_int, vp]
     L.ef_plan_destroy.restype = c_int
     L.ef_plan_destroy.argtypes = [vp]
-    for name in ("ef_plan_d", "ef_plan_blocks", "ef_plan_sign_words"):
+    for name in ("ef_plan_d", "ef_plan_blocks"):
         getattr(L, name).restype = i64
         getattr(L, name).argtypes = [vp]
+    L.ef_sign_words.restype = ctypes.c_size_t
+    L.ef_sign_words.argtypes = [vp]
     L.ef_plan_tune.restype = c_int
     L.ef_plan_tune.argtypes = [vp, c_int, c_int]
     L.ef_plan_set_persistent.restype = c_int
@@ -66,18 +80,12 @@ def lib():
     L.ef_plan_set_sync_group.argtypes = [vp, c_int]
     L.ef_plan_is_lazy.restype = c_int
     L.ef_plan_is_lazy.argtypes = [vp]
-    L.ef_stream_probe_grouped.restype = c_int
-    L.ef_stream_probe_grouped.argtypes = [vp, vp, vp, i64, c_int, c_int, ctypes.POINTER(f32), vp]
-    L.ef_stream_probe.restype = c_int
-    L.ef_stream_probe.argtypes = [vp, vp, vp, i64, c_int, ctypes.POINTER(f32), vp]
     L.ef_flush.restype = c_int
     L.ef_flush.argtypes = [vp, c_int, vp, i64, vp, vp]
     L.ef_plan_last_fallbacks.restype = c_int
     L.ef_plan_last_fallbacks.argtypes = [vp, ctypes.POINTER(ctypes.c_uint), ctypes.POINTER(ctypes.c_uint)]
     L.ef_plan_fuse_limit.restype = c_int
     L.ef_plan_fuse_limit.argtypes = [vp]
-    L.ef_sign_words.restype = i64
-    L.ef_sign_words.argtypes = [i64]
     L.ef_worker_step.restype = c_int
     L.ef_worker_step.argtypes = [vp, c_int, vp, i64, vp, vp, i64, f32, f32, f32, vp, vp, vp]
     L.ef_worker_step_sgd.restype = c_int
@@ -140,8 +148,8 @@ def _stride(t, d, name):
     return t.stride(0)
 
 
-def ef_sign_words(d):
-    return int(lib().ef_sign_words(int(d)))
+def ef_sign_words(plan):
+    return int(lib().ef_sign_words(plan._h))
 
 
 class Plan:
@@ -158,7 +166,7 @@ class Plan:
         _check(rc)
         self.d = int(lib().ef_plan_d(self._h))
         self.B = int(lib().ef_plan_blocks(self._h))
-        self.W = int(lib().ef_plan_sign_words(self._h))
+        self.W = int(lib().ef_sign_words(self._h))
         self.max_workers = int(max_workers)
 
     def tune(self, fuse_limit=-1, spin_limit=-1):
@@ -210,30 +218,6 @@ def ef_plan_create(block_offsets, max_workers, stream=None):
     return Plan(block_offsets, max_workers, stream)
 
 
-def ef_plan_tune(plan, fuse_limit=-1, spin_limit=-1):
-    plan.tune(fuse_limit, spin_limit)
-
-
-def ef_plan_set_persistent(plan, on):
-    plan.set_persistent(on)
-
-
-def ef_plan_is_persistent(plan):
-    return plan.persistent
-
-
-def ef_plan_set_lazy(plan, on):
-    plan.set_lazy(on)
-
-
-def ef_plan_set_sync_group(plan, tiles):
-    plan.set_sync_group(tiles)
-
-
-def ef_plan_is_lazy(plan):
-    return plan.lazy
-
-
 def ef_flush(plan, err=None, server_err=None, stream=None):
     """Writes the deferred corrections into err ([n][>=d] or [d], or None) and server_err ([d], or None)."""
     n, ss, ep = 1, plan.d, None
@@ -247,38 +231,6 @@ def ef_flush(plan, err=None, server_err=None, stream=None):
             raise TypeError("server_err must hold d entries")
         sp = _ptr(server_err, torch.float32, "server_err")
     _check(lib().ef_flush(plan._h, n, ep, ss, sp, _stream_ptr(stream)))
-
-
-def ef_stream_probe(g, m, e, repeats=5, stream=None):
-    """Bare 3-read/2-write stream over the whole tiles of g, m, e (1-D float32, same length; m and e
-    are overwritten with garbage).  Returns (ms per pass, bytes per pass)."""
-    n = g.numel()
-    if m.numel() != n or e.numel() != n:
-        raise TypeError("g, m, e must have the same number of elements")
-    ms = ctypes.c_float(0.0)
-    _check(lib().ef_stream_probe(_ptr(g, torch.float32, "g"), _ptr(m, torch.float32, "m"),
-                                 _ptr(e, torch.float32, "e"), n, int(repeats), ctypes.byref(ms), _stream_ptr(stream)))
-    return float(ms.value), 20 * (n // 4096) * 4096
-
-
-def ef_stream_probe_grouped(g, m, e, group=16, repeats=5, stream=None):
-    """As ef_stream_probe, one workgroup per tile, e written in step by groups of `group` tiles."""
-    n = g.numel()
-    if m.numel() != n or e.numel() != n:
-        raise TypeError("g, m, e must have the same number of elements")
-    ms = ctypes.c_float(0.0)
-    _check(lib().ef_stream_probe_grouped(_ptr(g, torch.float32, "g"), _ptr(m, torch.float32, "m"),
-                                         _ptr(e, torch.float32, "e"), n, int(group), int(repeats), ctypes.byref(ms),
-                                         _stream_ptr(stream)))
-    return float(ms.value), 20 * (n // 4096) * 4096
-
-
-def ef_plan_last_fallbacks(plan):
-    return plan.last_fallbacks()
-
-
-def ef_plan_fuse_limit(plan):
-    return plan.fuse_limit
 
 
 def ef_plan_destroy(plan):

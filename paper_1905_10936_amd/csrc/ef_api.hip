@@ -1,6 +1,7 @@
 // Host side of libef: plan construction, argument checks and kernel launches
 // behind the C ABI declared in include/ef.h.
 #include "ef.h"
+#include "ef_debug.h"
 #include "ef_device.h"
 
 #include <cmath>
@@ -58,7 +59,7 @@ struct ef_plan {
     unsigned long long *d_defer_list;
     unsigned long long *d_fin_list;
     int32_t *d_mixed, *d_uniform;   // tile lists
-    // compressor-quality diagnostics: allocated at the first ef_compressor_quality call
+    // compressor-quality diagnostics
     int32_t *d_cross;               // blocks that span several tiles
     int32_t n_cross;
     double *d_qtile, *d_qpart;      // [max_workers][ntiles][2], [max_workers][2*ntiles][2]
@@ -82,6 +83,19 @@ int hip_fail(hipError_t e)
     } while (0)
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Do the byte ranges [a, a + na) and [b, b + nb) share a byte?
+bool overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+// Bytes spanned by n rows of `row` items that lie `stride` items apart (item size `item`).
+size_t span_bytes(int n, int64_t stride, int64_t row, size_t item)
+{
+    return ((size_t)(n - 1) * (size_t)stride + (size_t)row) * item;
+}
 
 int check_offsets(const int64_t *offs, int64_t B)
 {
@@ -188,7 +202,7 @@ int upload_static_list(ef_plan *p, ef_plan::Role &r)
 // 64 tiles, as fast as anything else in that mode, and their residual is finished at once).
 constexpr int32_t LAZY_WAIT_LIMIT = 64;
 
-int refresh_limits(ef_plan *p)
+int refresh_limits_unguarded(ef_plan *p)
 {
     auto clamp = [](int64_t v) { return (int32_t)(v < 0 ? 0 : (v > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : v)); };
     if (p->user_fuse_limit >= 0) {
@@ -214,6 +228,17 @@ int refresh_limits(ef_plan *p)
         if (rc) return rc;
     }
     return EF_OK;
+}
+
+// The lists are built in host vectors: a failed allocation there becomes an error code, not an
+// exception crossing the C boundary.
+int refresh_limits(ef_plan *p)
+{
+    try {
+        return refresh_limits_unguarded(p);
+    } catch (const std::bad_alloc &) {
+        return EF_ERR_ARG;
+    }
 }
 
 int build_device(ef_plan *p)
@@ -340,6 +365,19 @@ int build_device(ef_plan *p)
         p->persistent_auto = ((tiles_per_wg >= 64 && cost_persistent < cost_direct) ||
                               (tiles_per_wg >= 16 && cost_persistent < 0.9 * cost_direct)) ? 1 : 0;
     }
+    {
+        // compressor-quality diagnostics: the blocks that span several tiles, and the per-tile sums
+        std::vector<int32_t> cross;
+        for (int64_t b = 0; b < B; ++b)
+            if (tiles_of_block(p, b) >= 2) cross.push_back((int32_t)b);
+        const size_t nt = (size_t)ntiles, nv = (size_t)p->max_workers;
+        EF_HIP(hipMalloc(&p->d_cross, sizeof(int32_t) * (cross.size() + 1)));
+        if (!cross.empty())
+            EF_HIP(hipMemcpy(p->d_cross, cross.data(), sizeof(int32_t) * cross.size(), hipMemcpyHostToDevice));
+        p->n_cross = (int32_t)cross.size();
+        EF_HIP(hipMalloc(&p->d_qpart, sizeof(double) * 4 * nt * nv));
+        EF_HIP(hipMalloc(&p->d_qtile, sizeof(double) * 2 * nt * nv));
+    }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
     p->persistent_forced = 0;
@@ -411,7 +449,7 @@ int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, i
 
 extern "C" {
 
-int64_t ef_sign_words(int64_t d) { return d < 0 ? 0 : (d + 63) / 64; }
+size_t ef_sign_words(const ef_plan *plan) { return plan ? (size_t)plan->L.W : 0; }
 
 int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, int max_workers, void *stream)
 {
@@ -423,11 +461,10 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     if (max_workers < 1 || max_workers > EF_MAX_WORKERS) return EF_ERR_ARG;
     ef_plan *p = new (std::nothrow) ef_plan();
     if (!p) return EF_ERR_ARG;
-    p->offs_host.assign(block_offsets_host, block_offsets_host + B + 1);
     p->max_workers = max_workers;
     p->L.B = B;
     p->L.d = block_offsets_host[B];
-    p->L.W = ef_sign_words(p->L.d);
+    p->L.W = (p->L.d + 63) / 64;
     p->L.ntiles = (int32_t)((p->L.d + ef::TILE - 1) / ef::TILE);
     p->d_offs = nullptr;
     p->d_tile_fb = p->d_tile_lb = nullptr;
@@ -455,7 +492,12 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->n_cross = 0;
     p->d_qtile = p->d_qpart = nullptr;
 
-    rc = build_device(p);
+    try {
+        p->offs_host.assign(block_offsets_host, block_offsets_host + B + 1);
+        rc = build_device(p);
+    } catch (const std::bad_alloc &) {      // host memory for the layout tables
+        rc = EF_ERR_ARG;
+    }
     if (rc) {
         destroy_device(p);
         delete p;
@@ -512,7 +554,8 @@ int ef_plan_set_sync_group(ef_plan *plan, int tiles)
 int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_stride, float *server_err, void *stream)
 {
     if (!plan) return EF_ERR_NULL;
-    if (err && (n_workers < 1 || n_workers > plan->max_workers || state_stride < plan->L.d || state_stride % 4))
+    if (err && (n_workers < 1 || n_workers > plan->max_workers ||
+                (n_workers > 1 && (state_stride < plan->L.d || state_stride % 4))))
         return EF_ERR_ARG;
     if ((err && !aligned(err, 16)) || (server_err && !aligned(server_err, 16))) return EF_ERR_ALIGN;
     // other buffers than the ones that wait for their correction: refuse rather than corrupt them
@@ -541,95 +584,6 @@ int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_strid
         EF_HIP(hipGetLastError());
     }
     return EF_OK;
-}
-
-int ef_stream_probe(const float *g, float *m, float *e, int64_t n_elements, int repeats, float *ms_per_pass, void *stream)
-{
-    if (!g || !m || !e || !ms_per_pass) return EF_ERR_NULL;
-    if (n_elements < ef::TILE || n_elements / ef::TILE > 0x7fffffffll || repeats < 1 || repeats > 1000) return EF_ERR_ARG;
-    if (!aligned(g, 16) || !aligned(m, 16) || !aligned(e, 16)) return EF_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const unsigned n_tiles = (unsigned)(n_elements / ef::TILE);
-    hipDeviceProp_t prop;
-    int dev = 0, occ = 0;
-    EF_HIP(hipGetDevice(&dev));
-    EF_HIP(hipGetDeviceProperties(&prop, dev));
-    EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, ef::k_probe_stream, ef::THREADS, 0));
-    if (occ < 1) occ = 1;
-    unsigned grid = (unsigned)prop.multiProcessorCount * (unsigned)occ;
-    if (grid > n_tiles) grid = n_tiles;
-    unsigned int *ticket = nullptr;
-    hipEvent_t t0 = nullptr, t1 = nullptr;
-    int rc = EF_OK;
-    float ms = 0.f;
-    auto pass = [&]() {
-        hipLaunchKernelGGL(ef::k_probe_reset, dim3(1), dim3(64), 0, s, ticket);
-        hipLaunchKernelGGL(ef::k_probe_stream, dim3(grid), dim3(ef::THREADS), 0, s, g, m, e, n_tiles, ticket);
-    };
-    if (hipMalloc(&ticket, sizeof(unsigned int)) != hipSuccess || hipEventCreate(&t0) != hipSuccess ||
-        hipEventCreate(&t1) != hipSuccess) {
-        rc = EF_ERR_HIP;
-    } else {
-        pass();                                     // warm-up
-        bool ok = hipEventRecord(t0, s) == hipSuccess;
-        for (int r = 0; r < repeats; ++r) pass();
-        ok = ok && hipEventRecord(t1, s) == hipSuccess && hipEventSynchronize(t1) == hipSuccess &&
-             hipEventElapsedTime(&ms, t0, t1) == hipSuccess && hipGetLastError() == hipSuccess;
-        if (ok)
-            *ms_per_pass = ms / (float)repeats;
-        else
-            rc = EF_ERR_HIP;
-    }
-    if (t0) (void)hipEventDestroy(t0);
-    if (t1) (void)hipEventDestroy(t1);
-    if (ticket) (void)hipFree(ticket);
-    return rc;
-}
-
-int ef_stream_probe_grouped(const float *g, float *m, float *e, int64_t n_elements, int group, int repeats,
-                            float *ms_per_pass, void *stream)
-{
-    if (!g || !m || !e || !ms_per_pass) return EF_ERR_NULL;
-    if (n_elements < ef::TILE || n_elements / ef::TILE > 0x7fffffffll || repeats < 1 || repeats > 1000 || group < 0 ||
-        group > 256)
-        return EF_ERR_ARG;
-    if (!aligned(g, 16) || !aligned(m, 16) || !aligned(e, 16)) return EF_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const unsigned n_tiles = (unsigned)(n_elements / ef::TILE);
-    unsigned int *arrive = nullptr;
-    unsigned long long *line = nullptr;
-    hipEvent_t t0 = nullptr, t1 = nullptr;
-    int rc = EF_OK;
-    float ms = 0.f;
-    unsigned pass = 0;
-    auto run = [&]() {
-        ++pass;         // never 0, the value of the cleared words
-        hipLaunchKernelGGL(ef::k_probe_grouped, dim3(n_tiles), dim3(ef::THREADS), 0, s, g, m, e, n_tiles, group, pass,
-                           arrive, line, 1 << 14);
-    };
-    const size_t line_bytes = sizeof(unsigned long long) * ef::READY_STRIDE * (size_t)n_tiles;
-    if (hipMalloc(&arrive, sizeof(unsigned int) * (size_t)n_tiles) != hipSuccess ||
-        hipMalloc(&line, line_bytes) != hipSuccess || hipEventCreate(&t0) != hipSuccess ||
-        hipEventCreate(&t1) != hipSuccess ||
-        hipMemsetAsync(arrive, 0, sizeof(unsigned int) * (size_t)n_tiles, s) != hipSuccess ||
-        hipMemsetAsync(line, 0, line_bytes, s) != hipSuccess) {
-        rc = EF_ERR_HIP;
-    } else {
-        run();                                      // warm-up
-        bool ok = hipEventRecord(t0, s) == hipSuccess;
-        for (int r = 0; r < repeats; ++r) run();
-        ok = ok && hipEventRecord(t1, s) == hipSuccess && hipEventSynchronize(t1) == hipSuccess &&
-             hipEventElapsedTime(&ms, t0, t1) == hipSuccess && hipGetLastError() == hipSuccess;
-        if (ok)
-            *ms_per_pass = ms / (float)repeats;
-        else
-            rc = EF_ERR_HIP;
-    }
-    if (t0) (void)hipEventDestroy(t0);
-    if (t1) (void)hipEventDestroy(t1);
-    if (arrive) (void)hipFree(arrive);
-    if (line) (void)hipFree(line);
-    return rc;
 }
 
 int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
@@ -685,7 +639,6 @@ int ef_plan_set_persistent(ef_plan *plan, int on)
 
 int64_t ef_plan_d(const ef_plan *plan) { return plan ? plan->L.d : 0; }
 int64_t ef_plan_blocks(const ef_plan *plan) { return plan ? plan->L.B : 0; }
-int64_t ef_plan_sign_words(const ef_plan *plan) { return plan ? plan->L.W : 0; }
 
 int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
                    float *err, int64_t state_stride, float mu, float eta_prev, float eta,
@@ -760,10 +713,24 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
     if (!plan || !grad || !err || !packed_signs || !scales) return EF_ERR_NULL;
     if (n_workers < 1 || n_workers > plan->max_workers) return EF_ERR_ARG;
     if (!(mu >= 0.0f && mu < 1.0f) || !good_eta(eta_prev, eta)) return EF_ERR_ARG;
-    if (grad_stride < plan->L.d || state_stride < plan->L.d || grad_stride % 4 || state_stride % 4)
+    // with one worker the strides are never used
+    if (n_workers > 1 && (grad_stride < plan->L.d || state_stride < plan->L.d || grad_stride % 4 || state_stride % 4))
         return EF_ERR_ARG;
-    if ((const void *)grad == (const void *)mom || (const void *)grad == (const void *)err || mom == err)
-        return EF_ERR_ARG;
+    {
+        // in-place aliasing is the contract for mom and err only: nothing else may overlap
+        const int64_t d = plan->L.d;
+        const size_t g_bytes = span_bytes(n_workers, grad_stride, d, 4), s_bytes = span_bytes(n_workers, state_stride, d, 4);
+        const size_t w_bytes = span_bytes(n_workers, signs_stride, plan->L.W, 8);
+        const size_t c_bytes = span_bytes(n_workers, scales_stride, plan->L.B, 4);
+        if (overlap(grad, g_bytes, err, s_bytes) || (has_mom && (overlap(grad, g_bytes, mom, s_bytes) ||
+                                                                 overlap(mom, s_bytes, err, s_bytes))))
+            return EF_ERR_ARG;
+        const void *in[3] = {grad, err, mom};
+        const size_t in_bytes[3] = {g_bytes, s_bytes, s_bytes};
+        for (int k = 0; k < (has_mom ? 3 : 2); ++k)
+            if (overlap(packed_signs, w_bytes, in[k], in_bytes[k]) || overlap(scales, c_bytes, in[k], in_bytes[k]))
+                return EF_ERR_ARG;
+    }
     if (!aligned(grad, 16) || (has_mom && !aligned(mom, 16)) || !aligned(err, 16) || !aligned(scales, 4) ||
         !aligned(packed_signs, 8))
         return EF_ERR_ALIGN;
@@ -831,7 +798,18 @@ int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, i
     if (!plan || !packed_signs || !scales || !server_err || !out_signs || !out_scales) return EF_ERR_NULL;
     if (M < 1 || M > plan->max_workers) return EF_ERR_ARG;
     if (!good_eta(eta_prev, eta)) return EF_ERR_ARG;
-    if (packed_signs == out_signs || scales == out_scales) return EF_ERR_ARG;
+    {
+        // the server residual is updated in place; the payloads may overlap neither it nor each other
+        const size_t in_w = span_bytes(M, in_signs_stride, plan->L.W, 8), in_c = span_bytes(M, in_scales_stride, plan->L.B, 4);
+        const size_t out_w = (size_t)plan->L.W * 8u, out_c = (size_t)plan->L.B * 4u, e_bytes = (size_t)plan->L.d * 4u;
+        if (overlap(out_signs, out_w, packed_signs, in_w) || overlap(out_signs, out_w, scales, in_c) ||
+            overlap(out_scales, out_c, packed_signs, in_w) || overlap(out_scales, out_c, scales, in_c) ||
+            overlap(out_signs, out_w, out_scales, out_c))
+            return EF_ERR_ARG;
+        if (overlap(server_err, e_bytes, packed_signs, in_w) || overlap(server_err, e_bytes, scales, in_c) ||
+            overlap(server_err, e_bytes, out_signs, out_w) || overlap(server_err, e_bytes, out_scales, out_c))
+            return EF_ERR_ARG;
+    }
     if (!aligned(server_err, 16) || !aligned(packed_signs, 8) || !aligned(out_signs, 8) ||
         !aligned(scales, 4) || !aligned(out_scales, 4))
         return EF_ERR_ALIGN;
@@ -915,21 +893,9 @@ int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t 
 {
     if (!plan || !v || !out) return EF_ERR_NULL;
     if (n_vectors < 1 || n_vectors > plan->max_workers) return EF_ERR_ARG;
-    if (stride < plan->L.d || stride % 4) return EF_ERR_ARG;
+    if (n_vectors > 1 && (stride < plan->L.d || stride % 4)) return EF_ERR_ARG;
     if (!aligned(v, 16) || !aligned(out, 8)) return EF_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (!plan->d_qtile) {       // first call on this plan: scratch and the list of crossing blocks
-        std::vector<int32_t> cross;
-        for (int64_t b = 0; b < plan->L.B; ++b)
-            if (tiles_of_block(plan, b) >= 2) cross.push_back((int32_t)b);
-        const size_t nt = (size_t)plan->L.ntiles, nv = (size_t)plan->max_workers;
-        EF_HIP(hipMalloc(&plan->d_cross, sizeof(int32_t) * (cross.size() + 1)));
-        if (!cross.empty())
-            EF_HIP(hipMemcpy(plan->d_cross, cross.data(), sizeof(int32_t) * cross.size(), hipMemcpyHostToDevice));
-        plan->n_cross = (int32_t)cross.size();
-        EF_HIP(hipMalloc(&plan->d_qpart, sizeof(double) * 4 * nt * nv));
-        EF_HIP(hipMalloc(&plan->d_qtile, sizeof(double) * 2 * nt * nv));
-    }
     ef::QualityArgs Q;
     Q.v = v;
     Q.stride = stride;

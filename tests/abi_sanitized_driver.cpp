@@ -5,6 +5,7 @@
 // lists behind ef_plan_tune, ef_plan_set_persistent and ef_plan_set_lazy are rebuilt a few times.
 // Test infrastructure only.
 #include "ef.h"
+#include "ef_debug.h"
 
 #include <cstdio>
 #include <cstring>
@@ -47,7 +48,7 @@ int main()
     REQUIRE(ef_plan_set_sync_group(nullptr, 16) == EF_ERR_NULL);
     REQUIRE(ef_plan_last_fallbacks(nullptr, &a, &b) == EF_ERR_NULL);
     REQUIRE(ef_plan_fuse_limit(nullptr) == 0 && ef_plan_is_persistent(nullptr) == 0 && ef_plan_is_lazy(nullptr) == 0);
-    REQUIRE(ef_plan_d(nullptr) == 0 && ef_plan_blocks(nullptr) == 0 && ef_plan_sign_words(nullptr) == 0);
+    REQUIRE(ef_plan_d(nullptr) == 0 && ef_plan_blocks(nullptr) == 0 && ef_sign_words(nullptr) == 0);
     REQUIRE(ef_payload_bytes(nullptr) == 0 && ef_payload_scales_offset(nullptr) == 0);
     REQUIRE(ef_worker_step(nullptr, 1, buf, 64, buf, buf, 64, 0.9f, 0.f, 0.1f, words, buf, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_worker_step_sgd(nullptr, 1, buf, 64, buf, 64, 0.f, 0.1f, words, buf, nullptr) == EF_ERR_NULL);
@@ -59,13 +60,7 @@ int main()
     REQUIRE(ef_apply_fused(nullptr, buf, words, 0.1f, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_flush(nullptr, 1, buf, 64, buf, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_compressor_quality(nullptr, 1, buf, 64, q, nullptr) == EF_ERR_NULL);
-    REQUIRE(ef_stream_probe(nullptr, buf, buf, 4096, 1, &ms, nullptr) == EF_ERR_NULL);
-    REQUIRE(ef_stream_probe(buf, buf, buf, 64, 1, &ms, nullptr) == EF_ERR_ARG);
-    REQUIRE(ef_stream_probe_grouped(nullptr, buf, buf, 4096, 16, 1, &ms, nullptr) == EF_ERR_NULL);
-    REQUIRE(ef_stream_probe_grouped(buf, buf, buf, 64, 16, 1, &ms, nullptr) == EF_ERR_ARG);
 
-    REQUIRE(ef_sign_words(0) == 0 && ef_sign_words(1) == 1 && ef_sign_words(64) == 1 && ef_sign_words(65) == 2);
-    REQUIRE(ef_sign_words(-5) == 0);
     for (int code = 1; code >= -7; --code) REQUIRE(ef_strerror(code) != nullptr && std::strlen(ef_strerror(code)) > 0);
 
     // a real layout: many tiny blocks, blocks of several tiles, a ragged end

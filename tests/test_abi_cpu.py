@@ -1,6 +1,6 @@
-"""Host-side checks of the C ABI that need no GPU: the library loads, exports
-every symbol include/ef.h declares, and validates the block partition before
-touching the device."""
+"""Host-side checks of the C ABI that need no GPU: the libraries load, export
+every symbol the headers under include/ declare, and the block partition is
+validated before the device is touched."""
 import ctypes
 import os
 import re
@@ -14,22 +14,37 @@ import paper_1905_10936_amd as ef
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ef.h")).read()
+def _declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ef_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
-    L = ef.lib()
-    names = _declared_symbols()
-    assert set(names) == set(ef.ABI_SYMBOLS)
-    for n in names:
-        assert getattr(L, n) is not None
+    """include/ef.h is the boundary of Algorithm 4, include/ef_debug.h the tuning knobs (both in
+    libef.so); include/ef_bench.h the bandwidth probes of libef_bench.so."""
+    from paper_1905_10936_amd import bench_probe
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["ef.h", "ef_bench.h", "ef_debug.h"]
+    for header, names, L in (("ef.h", ef.ABI_SYMBOLS, ef.lib()), ("ef_debug.h", ef.DEBUG_SYMBOLS, ef.lib()),
+                             ("ef_bench.h", bench_probe.BENCH_SYMBOLS, bench_probe.lib())):
+        declared = _declared_symbols(header)
+        assert set(declared) == set(names), header
+        for n in declared:
+            assert getattr(L, n) is not None
+    # the probes allocate and synchronise: they must stay out of the product library
+    for n in bench_probe.BENCH_SYMBOLS:
+        assert not hasattr(ef.lib(), n)
 
 
-def test_sign_words():
-    assert [ef.ef_sign_words(d) for d in (1, 63, 64, 65, 128, 1 << 28)] == [1, 1, 1, 2, 2, 1 << 22]
+def test_built_libraries_are_not_older_than_their_sources():
+    """The built libraries travel to the GPU machine as they are: a stale one would be what gets tested."""
+    from paper_1905_10936_amd import build
+    for lib in build.TARGETS:
+        assert os.path.exists(lib) and not build.stale(lib), "%s is missing or older than its sources: rebuild" % lib
+
+
+def test_sign_words_without_a_plan():
+    assert ef.lib().ef_sign_words(None) == 0
 
 
 @pytest.mark.parametrize("offs", [[0, 2, 2, 4], [1, 4], [0, 3, 2, 4], [0], [0, 0]])

@@ -16,7 +16,7 @@ import torch
 import ef_workloads as wl
 import oracle
 import paper_1905_10936_amd as ef
-from tests.parity_util import F, GpuState, synced_step, to_np
+from tests.parity_util import F, GpuState, check_scales, check_vector, synced_step, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -190,6 +190,55 @@ def test_abi_error_codes_on_device():
     with pytest.raises(ef.EfError) as ei:
         ef.ef_apply(st.plan, big[1:st.d + 1], st.ss, st.sc, 0.1)                          # misaligned
     assert ei.value.code == ef.EF_ERR_ALIGN
+
+
+def test_outputs_that_overlap_inputs_are_refused():
+    """In-place updating is the contract for mom, err, server_err and params only: a payload
+    buffer that shares bytes with the state or with the incoming payloads is an error, and
+    nothing is enqueued."""
+    offs = _offs([100, 200, 4096 * 3])
+    st = GpuState(offs, 2)
+    d, W, B = st.d, st.W, st.B
+    before = to_np(st.e).copy()
+    as_words = st.e.view(torch.int64).view(-1)      # sign words that alias the residual buffer
+    with pytest.raises(ef.EfError) as ei:
+        ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.9, 0.0, 0.1, as_words[:2 * W], st.wc)
+    assert ei.value.code == ef.EF_ERR_ARG
+    with pytest.raises(ef.EfError) as ei:           # scales inside the gradient buffer
+        ef.ef_worker_step(st.plan, st.g, st.m, st.e, 0.9, 0.0, 0.1, st.ws, st.g.view(-1)[:2 * B])
+    assert ei.value.code == ef.EF_ERR_ARG
+    with pytest.raises(ef.EfError) as ei:           # momentum and residual rows that interleave
+        ef.ef_worker_step(st.plan, st.g, st.m, st.m, 0.9, 0.0, 0.1, st.ws, st.wc)
+    assert ei.value.code == ef.EF_ERR_ARG
+    with pytest.raises(ef.EfError) as ei:           # server output inside the server residual
+        ef.ef_server_step(st.plan, 2, st.ws, st.wc, st.te, 0.0, 0.1, st.te.view(torch.int64)[:W], st.sc)
+    assert ei.value.code == ef.EF_ERR_ARG
+    with pytest.raises(ef.EfError) as ei:           # server output on top of a worker's payload
+        ef.ef_server_step(st.plan, 2, st.ws, st.wc, st.te, 0.0, 0.1, st.ws[1], st.sc)
+    assert ei.value.code == ef.EF_ERR_ARG
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(st.e), before)
+
+
+def test_one_worker_needs_no_stride():
+    """A single vector whose length is not a multiple of 4: with n_workers = 1 the row stride is
+    never used, so any value passes, and the step matches the oracle."""
+    offs = _offs([4099, 7, 4096 + 2])
+    st = GpuState(offs, 1)
+    d = st.d
+    assert d % 4 != 0
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal(d).astype(F)
+    gt, mt, et = (torch.zeros(d, dtype=torch.float32, device="cuda") for _ in range(3))
+    gt.copy_(torch.as_tensor(g))
+    ef.ef_worker_step(st.plan, gt, mt, et, 0.9, 0.0, 0.1, st.ws, st.wc)         # stride = d, not a multiple of 4
+    torch.cuda.synchronize()
+    m_ref, e_ref = np.zeros(d, F), np.zeros(d, F)
+    s_ref, c_ref = oracle.worker_step(g, m_ref, e_ref, offs, F(0.9), F(0.0), F(0.1))
+    assert np.array_equal(to_np(st.ws)[0], s_ref)
+    assert np.array_equal(to_np(mt).view(np.uint32), m_ref.view(np.uint32))
+    same = check_scales(to_np(st.wc)[0], c_ref, "single vector")
+    check_vector(to_np(et), e_ref, c_ref, same, offs, "single vector residual")
 
 
 def test_many_steps_with_changing_worker_count_and_stepsize():

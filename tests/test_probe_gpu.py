@@ -1,4 +1,4 @@
-"""ef_stream_probe (the bandwidth probe bench.py sets beside the worker kernel): runs, reports a
+"""ef_stream_probe of libef_bench (the bandwidth probe bench.py sets beside the worker kernel): runs, reports a
 positive time, touches nothing beyond the whole tiles it is given, and rejects bad arguments."""
 import ctypes
 
@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import paper_1905_10936_amd as ef
+from paper_1905_10936_amd import bench_probe
 
 pytestmark = pytest.mark.gpu
 
@@ -16,7 +17,7 @@ def test_probe_runs_and_stays_in_bounds():
     m = torch.randn(n, device="cuda")
     e = torch.randn(n, device="cuda")
     g0, m0, e0 = g.clone(), m.clone(), e.clone()
-    ms, nbytes = ef.ef_stream_probe(g, m, e, repeats=2)
+    ms, nbytes = bench_probe.ef_stream_probe(g, m, e, repeats=2)
     torch.cuda.synchronize()
     assert ms > 0.0 and nbytes == 20 * 37 * 4096
     assert torch.equal(g, g0)
@@ -32,7 +33,7 @@ def test_grouped_probe_runs_and_stays_in_bounds(group):
     m = torch.randn(n, device="cuda")
     e = torch.randn(n, device="cuda")
     g0, m0, e0 = g.clone(), m.clone(), e.clone()
-    ms, nbytes = ef.ef_stream_probe_grouped(g, m, e, group=group, repeats=2)
+    ms, nbytes = bench_probe.ef_stream_probe_grouped(g, m, e, group=group, repeats=2)
     torch.cuda.synchronize()
     assert ms > 0.0 and nbytes == 20 * 37 * 4096
     assert torch.equal(g, g0)
@@ -44,16 +45,16 @@ def test_grouped_probe_runs_and_stays_in_bounds(group):
         ee = 0.5 * ee + mm
     assert torch.allclose(m[:37 * 4096], mm, rtol=1e-5, atol=1e-6) and torch.allclose(e[:37 * 4096], ee, rtol=1e-5, atol=1e-6)
     with pytest.raises(ef.EfError):
-        ef.ef_stream_probe_grouped(g, m, e, group=257)
+        bench_probe.ef_stream_probe_grouped(g, m, e, group=257)
 
 
 def test_probe_argument_checks():
     g = torch.zeros(8192, device="cuda")
     with pytest.raises(ef.EfError):
-        ef.ef_stream_probe(g[:100], g[:100].clone(), g[:100].clone())        # less than a tile
+        bench_probe.ef_stream_probe(g[:100], g[:100].clone(), g[:100].clone())        # less than a tile
     with pytest.raises(ef.EfError):
-        ef.ef_stream_probe(g, g.clone(), g.clone(), repeats=0)
+        bench_probe.ef_stream_probe(g, g.clone(), g.clone(), repeats=0)
     with pytest.raises(ef.EfError):
-        ef.ef_stream_probe(g[1:4097], g.clone()[:4096], g.clone()[:4096])      # off 16 bytes
+        bench_probe.ef_stream_probe(g[1:4097], g.clone()[:4096], g.clone()[:4096])      # off 16 bytes
     ms = ctypes.c_float(0.0)
-    assert ef.lib().ef_stream_probe(None, None, None, 4096, 1, ctypes.byref(ms), None) == ef.EF_ERR_NULL
+    assert bench_probe.lib().ef_stream_probe(None, None, None, 4096, 1, ctypes.byref(ms), None) == ef.EF_ERR_NULL
