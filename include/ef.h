@@ -63,6 +63,7 @@ extern "C" {
                              eta <= 0, eta_prev < 0, non-finite, stride < d or not a multiple of 4 */
 #define EF_ERR_ALIGN -4   /* pointer not aligned as required */
 #define EF_ERR_HIP -5     /* the HIP runtime reported an error (allocation, launch, no device) */
+#define EF_ERR_SIZE -6    /* input beyond the fixed capacity of an entry point that allocates nothing */
 
 #define EF_MAX_WORKERS 64
 
@@ -275,6 +276,31 @@ int ef_apply_fused(const ef_plan *plan, float *params, const void *payload, floa
  */
 int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out,
                           void *stream);
+
+/*
+ * ef_compressor_quality for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * kernels and the same results, bit for bit, but the per-tile sums go to a
+ * fixed array in the library's own device image instead of plan-owned memory,
+ * and the call itself calls no hipMalloc, hipFree or other allocating routine
+ * (plan creation, which happens earlier, still does).
+ *
+ * Capacity: ceil(d/4096) * n_vectors <= EF_QUALITY_STATIC_MAX_TILE_VECTORS
+ * (131072, i.e. 2^29 elements over all vectors; the array takes 6 MiB of every
+ * GPU the library runs on until the process ends); larger inputs are refused
+ * with EF_ERR_SIZE before anything is enqueued.  The plan's device must be
+ * current (EF_ERR_ARG otherwise).  Other arguments and errors as for
+ * ef_compressor_quality.
+ *
+ * All calls on one GPU share the one array, whatever their plan: calls that
+ * overlap on the device (different streams, no ordering between them) race on
+ * it and give wrong results; order them.  The array keeps the last call's
+ * contents; nothing in it has to start at zero, since every word a call reads
+ * it has written before.
+ */
+#define EF_QUALITY_STATIC_MAX_TILE_VECTORS 131072
+int ef_compressor_quality_static(const ef_plan *plan, int n_vectors, const float *v, int64_t stride,
+                                 double *out, void *stream);
 
 /* Static text for an error code; for EF_ERR_HIP the text of the last HIP error
  * seen by this thread is appended.  The returned pointer stays valid until the

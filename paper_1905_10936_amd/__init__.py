@@ -19,7 +19,7 @@ from . import build as _build
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libef.so")
 
-EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP = 0, -1, -2, -3, -4, -5
+EF_OK, EF_ERR_NULL, EF_ERR_OFFSETS, EF_ERR_ARG, EF_ERR_ALIGN, EF_ERR_HIP, EF_ERR_SIZE = 0, -1, -2, -3, -4, -5, -6
 EF_MAX_WORKERS = 64
 
 # what include/ef.h declares (the boundary of Algorithm 4) ...
@@ -28,7 +28,7 @@ ABI_SYMBOLS = (
     "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
     "ef_worker_step_sgd", "ef_apply_wd",
     "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused",
-    "ef_compressor_quality",
+    "ef_compressor_quality", "ef_compressor_quality_static",
     "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_flush",
 )
 # ... and what include/ef_debug.h declares (tuning and diagnostics the tests use)
@@ -104,8 +104,9 @@ def lib():
     L.ef_server_step_fused.argtypes = [vp, c_int, vp, vp, f32, f32, vp, vp]
     L.ef_apply_fused.restype = c_int
     L.ef_apply_fused.argtypes = [vp, vp, vp, f32, vp]
-    L.ef_compressor_quality.restype = c_int
-    L.ef_compressor_quality.argtypes = [vp, c_int, vp, i64, vp, vp]
+    for name in ("ef_compressor_quality", "ef_compressor_quality_static"):
+        getattr(L, name).restype = c_int
+        getattr(L, name).argtypes = [vp, c_int, vp, i64, vp, vp]
     L.ef_apply_wd.restype = c_int
     L.ef_apply_wd.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, vp]
     L.ef_strerror.restype = ctypes.c_char_p
@@ -346,11 +347,17 @@ def ef_worker_step_sgd(plan, grad, err, eta_prev, eta, packed_signs, scales, str
     _check(rc)
 
 
-def ef_compressor_quality(plan, v, out, stream=None):
-    """v: float32 [n][>=d] (or [d]); out: float64 [n][2] receives (phi, delta) per vector."""
+def ef_compressor_quality(plan, v, out, stream=None, static_scratch=False):
+    """v: float32 [n][>=d] (or [d]); out: float64 [n][2] receives (phi, delta) per vector.
+    static_scratch: go through ef_compressor_quality_static (allocates nothing, bounded size)."""
     n = 1 if v.dim() == 1 else v.shape[0]
     if out.numel() != 2 * n:
         raise TypeError("out must hold 2 doubles per vector")
-    rc = lib().ef_compressor_quality(plan._h, n, _ptr(v, torch.float32, "v"), _stride(v, plan.d, "v"),
-                                     _ptr(out, torch.float64, "out"), _stream_ptr(stream))
+    fn = lib().ef_compressor_quality_static if static_scratch else lib().ef_compressor_quality
+    rc = fn(plan._h, n, _ptr(v, torch.float32, "v"), _stride(v, plan.d, "v"), _ptr(out, torch.float64, "out"),
+            _stream_ptr(stream))
     _check(rc)
+
+
+def ef_compressor_quality_static(plan, v, out, stream=None):
+    ef_compressor_quality(plan, v, out, stream, static_scratch=True)

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -65,7 +66,17 @@ struct ef_plan {
     double *d_qtile, *d_qpart;      // [max_workers][ntiles][2], [max_workers][2*ntiles][2]
 };
 
+// Scratch of ef_compressor_quality_static: device memory that exists from the moment the library
+// is loaded on a GPU, so that the call allocates nothing.  In host code the array's name is only a
+// stand-in for the symbol; the memory is reached through the per-device address that
+// static_scratch() looks up once per device.
+static __device__ __align__(256) double scratch[(size_t)EF_QUALITY_STATIC_MAX_TILE_VECTORS * 6];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[MAX_DEVICES];     // [device] address of `scratch` on that device, once looked up
 
 thread_local char g_errbuf[512];
 thread_local hipError_t g_last_hip = hipSuccess;
@@ -81,6 +92,22 @@ int hip_fail(hipError_t e)
         hipError_t e_ = (call);                       \
         if (e_ != hipSuccess) return hip_fail(e_);    \
     } while (0)
+
+// Address of the static scratch on the current device (which must be `device`).  The first call
+// per device asks the runtime for the symbol's address; no memory is allocated.
+int static_scratch(int device, double **out)
+{
+    if (device < 0 || device >= MAX_DEVICES) return EF_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        g_scratch_ptr[device] = static_cast<double *>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return EF_OK;
+}
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -377,6 +404,11 @@ int build_device(ef_plan *p)
         p->n_cross = (int32_t)cross.size();
         EF_HIP(hipMalloc(&p->d_qpart, sizeof(double) * 4 * nt * nv));
         EF_HIP(hipMalloc(&p->d_qtile, sizeof(double) * 2 * nt * nv));
+    }
+    {
+        double *unused = nullptr;       // the static scratch of this device, looked up once, ahead of the first call that needs it
+        int rc_scratch = static_scratch(p->device, &unused);
+        if (rc_scratch) return rc_scratch;
     }
     p->spin_limit = 1 << 14;
     p->persistent = p->persistent_auto;
@@ -889,18 +921,14 @@ int ef_apply_wd(const ef_plan *plan, float *params, float *decay_mom, const uint
     return EF_OK;
 }
 
-int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out, void *stream)
+static int quality_launch(const ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out,
+                          double *tile_sums, double *part_sums, hipStream_t s)
 {
-    if (!plan || !v || !out) return EF_ERR_NULL;
-    if (n_vectors < 1 || n_vectors > plan->max_workers) return EF_ERR_ARG;
-    if (n_vectors > 1 && (stride < plan->L.d || stride % 4)) return EF_ERR_ARG;
-    if (!aligned(v, 16) || !aligned(out, 8)) return EF_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     ef::QualityArgs Q;
     Q.v = v;
     Q.stride = stride;
-    Q.tile_sums = plan->d_qtile;
-    Q.part_sums = plan->d_qpart;
+    Q.tile_sums = tile_sums;
+    Q.part_sums = part_sums;
     Q.out = out;
     hipLaunchKernelGGL(ef::k_quality_init, dim3(1), dim3(ef::THREADS), 0, s, out, n_vectors);
     EF_HIP(hipGetLastError());
@@ -913,6 +941,40 @@ int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t 
     return EF_OK;
 }
 
+static int quality_args(const ef_plan *plan, int n_vectors, const float *v, int64_t stride, const double *out)
+{
+    if (!plan || !v || !out) return EF_ERR_NULL;
+    if (n_vectors < 1 || n_vectors > plan->max_workers) return EF_ERR_ARG;
+    if (n_vectors > 1 && (stride < plan->L.d || stride % 4)) return EF_ERR_ARG;
+    if (!aligned(v, 16) || !aligned(out, 8)) return EF_ERR_ALIGN;
+    return EF_OK;
+}
+
+int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out, void *stream)
+{
+    const int rc = quality_args(plan, n_vectors, v, stride, out);
+    if (rc) return rc;
+    return quality_launch(plan, n_vectors, v, stride, out, plan->d_qtile, plan->d_qpart, static_cast<hipStream_t>(stream));
+}
+
+int ef_compressor_quality_static(const ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out,
+                                 void *stream)
+{
+    int rc = quality_args(plan, n_vectors, v, stride, out);
+    if (rc) return rc;
+    const int64_t tile_vectors = (int64_t)plan->L.ntiles * n_vectors;
+    if (tile_vectors > (int64_t)EF_QUALITY_STATIC_MAX_TILE_VECTORS) return EF_ERR_SIZE;
+    int device = -1;
+    EF_HIP(hipGetDevice(&device));
+    if (device != plan->device) return EF_ERR_ARG;      // the plan's tables live on its own device
+    double *base = nullptr;
+    rc = static_scratch(device, &base);
+    if (rc) return rc;
+    // [n][ntiles][2] tile sums, then [n][2*ntiles][2] sums of open segments; every word the kernels read
+    // is written earlier in the same call, so nothing has to be cleared
+    return quality_launch(plan, n_vectors, v, stride, out, base, base + 2 * tile_vectors, static_cast<hipStream_t>(stream));
+}
+
 const char *ef_strerror(int code)
 {
     const char *t;
@@ -922,6 +984,10 @@ const char *ef_strerror(int code)
     case EF_ERR_OFFSETS: t = "block_offsets is not a partition (0 = o[0] < o[1] < ... < o[B] = d)"; break;
     case EF_ERR_ARG: t = "argument out of range"; break;
     case EF_ERR_ALIGN: t = "pointer not aligned (fp32 arrays 16 bytes, sign words 8 bytes)"; break;
+    case EF_ERR_SIZE:
+        t = "input too large for the static scratch of ef_compressor_quality_static (tiles x vectors above "
+            "EF_QUALITY_STATIC_MAX_TILE_VECTORS): use ef_compressor_quality";
+        break;
     case EF_ERR_HIP:
         snprintf(g_errbuf, sizeof g_errbuf, "HIP runtime error: %s", hipGetErrorString(g_last_hip));
         return g_errbuf;

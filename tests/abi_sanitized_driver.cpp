@@ -60,6 +60,7 @@ int main()
     REQUIRE(ef_apply_fused(nullptr, buf, words, 0.1f, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_flush(nullptr, 1, buf, 64, buf, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_compressor_quality(nullptr, 1, buf, 64, q, nullptr) == EF_ERR_NULL);
+    REQUIRE(ef_compressor_quality_static(nullptr, 1, buf, 64, q, nullptr) == EF_ERR_NULL);
 
     for (int code = 1; code >= -7; --code) REQUIRE(ef_strerror(code) != nullptr && std::strlen(ef_strerror(code)) > 0);
 
