@@ -223,7 +223,7 @@ def test_outputs_that_overlap_inputs_are_refused():
 def test_one_worker_needs_no_stride():
     """A single vector whose length is not a multiple of 4: with n_workers = 1 the row stride is
     never used, so any value passes, and the step matches the oracle."""
-    offs = _offs([4099, 7, 4096 + 2])
+    offs = _offs([4099, 7, 4096 + 1])
     st = GpuState(offs, 1)
     d = st.d
     assert d % 4 != 0
