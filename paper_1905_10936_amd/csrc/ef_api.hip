@@ -20,8 +20,9 @@ struct ef_plan {
     ef::CallState *d_state;         // calls made so far and the tags of the scratch sets: advanced on the device
     std::vector<int64_t> offs_host;
     std::vector<int32_t> fb_host, lb_host;
-    // What depends on the one-pass limit, which differs between the worker kernels and the
-    // server kernel (each is bounded by what its own grid keeps resident): role 0 = worker, 1 = server.
+    // What depends on the one-pass limit, which differs between the kernels (each is bounded by what
+    // the kernel's own grid keeps resident): role 0 = the persistent worker kernel, 1 = the server,
+    // 2 = the worker kernel that runs one workgroup per tile.
     struct Role {
         int32_t fuse_limit;
         uint32_t n_static;          // segments whose p the first kernels always park
@@ -33,7 +34,7 @@ struct ef_plan {
         int32_t *d_late_index;      // [B]
         int32_t *d_lazy_tiles;      // [ntiles] capacity
         uint32_t n_lazy_tiles;
-    } role[3];                      // worker, server, worker calls that run one workgroup per tile whatever `persistent` says
+    } role[3];
     int sync_group;                 // tiles of a large block that are written out in step (ef_plan_set_sync_group)
     int lazy;                       // deferred correction on (ef_plan_set_lazy)
     // Host-side guard of the deferred mode: the residual buffers (workers, server) the last calls
@@ -52,7 +53,7 @@ struct ef_plan {
     int32_t *d_tile_lb;
     unsigned long long *d_part;
     unsigned long long *d_ready;
-    unsigned int *d_list_cnt;       // [6]: defer_cnt[2], fin_cnt[2], ticket[2], alternating between calls
+    unsigned int *d_list_cnt;       // [8]: defer_cnt[2], fin_cnt[2], ticket[2] (alternating between calls), done, unused
     int worker_grid;                // workgroups of the persistent worker kernel
     int persistent;                 // worker: 1 pipelined persistent kernel, 0 one workgroup per tile
     int persistent_auto;            // what plan creation chose for this layout
@@ -73,6 +74,8 @@ struct ef_plan {
 static __device__ __align__(256) double scratch[(size_t)EF_QUALITY_STATIC_MAX_TILE_VECTORS * 6];
 
 namespace {
+
+enum { ROLE_TICKET = 0, ROLE_SERVER = 1, ROLE_TILES = 2 };
 
 constexpr int MAX_DEVICES = 64;
 std::mutex g_scratch_mutex;
@@ -178,10 +181,18 @@ bool has_uniform_tile(const ef_plan *p, int64_t b)
     return tiles_of_block(p, b) - (o[b] % ef::TILE != 0 ? 1 : 0) - (o[b + 1] % ef::TILE != 0 ? 1 : 0) >= 1;
 }
 
-// What the first kernels of a call always leave to the two short kernels after
-// them: the scales of crossing blocks that have no uniform tile or span more
-// than fuse_limit tiles, and the residual of every open segment of a mixed tile
-// and of every tile of a block larger than fuse_limit.
+// A one-pass block without a whole tile is finished among the mixed tiles.  (Host mirror of
+// finishes_with_mixed in ef_tile.h.)
+bool finishes_with_mixed(const ef_plan *p, const ef_plan::Role &r, int64_t b)
+{
+    const int64_t n = tiles_of_block(p, b);
+    return n >= 2 && n <= r.fuse_limit && !has_uniform_tile(p, b);
+}
+
+// What the main kernels of a call always leave to the kernel that ends it: the scales of the
+// blocks larger than fuse_limit, and the residual of every open segment that is not finished
+// where it is computed (the segments of those large blocks, and the segments that blocks with
+// whole tiles have in mixed tiles).
 int upload_static_list(ef_plan *p, ef_plan::Role &r)
 {
     std::vector<uint32_t> items;
@@ -189,26 +200,27 @@ int upload_static_list(ef_plan *p, ef_plan::Role &r)
     const int64_t *o = p->offs_host.data();
     for (int64_t b = 0; b < p->L.B; ++b) {
         const int64_t n = tiles_of_block(p, b);
-        if (n < 2) continue;
-        if (n > r.fuse_limit || !has_uniform_tile(p, b)) {
-            if (n > r.fuse_limit && has_uniform_tile(p, b)) late_index[(size_t)b] = (int32_t)late.size();
-            late.push_back((int32_t)b);
-        }
+        if (n < 2 || n <= r.fuse_limit) continue;
+        if (has_uniform_tile(p, b)) late_index[(size_t)b] = (int32_t)late.size();
+        late.push_back((int32_t)b);
     }
     for (int32_t t = 0; t < p->L.ntiles; ++t) {
         const int64_t start = (int64_t)t * ef::TILE, end = start + ef::TILE;
         const int32_t fb = p->fb_host[t], lb = p->lb_host[t];
         const bool full = end <= p->L.d;
-        if (fb == lb) {
-            // a full tile parks p only for blocks beyond fuse_limit, the ragged last tile always
+        if (fb == lb && full) {
+            // a whole tile parks p only for blocks beyond fuse_limit
             const bool open = (o[fb] < start) || (o[fb + 1] > end);
-            if (open && full && tiles_of_block(p, fb) > r.fuse_limit && p->lazy)
-                lazy_tiles.push_back(t);        // deferred: corrected when the buffer is next loaded
-            else if (open && (!full || tiles_of_block(p, fb) > r.fuse_limit))
-                items.push_back(((uint32_t)t << 1) | 0u);
+            if (open && tiles_of_block(p, fb) > r.fuse_limit) {
+                if (p->lazy)
+                    lazy_tiles.push_back(t);        // deferred: corrected when the buffer is next loaded
+                else
+                    items.push_back(((uint32_t)t << 1) | 0u);
+            }
         } else {
-            if (o[fb] < start) items.push_back(((uint32_t)t << 1) | 0u);
-            if (o[lb + 1] > end) items.push_back(((uint32_t)t << 1) | 1u);
+            // a tile the mixed-tile code handles (several blocks, or the ragged end of the vector)
+            if (o[fb] < start && !finishes_with_mixed(p, r, fb)) items.push_back(((uint32_t)t << 1) | 0u);
+            if (o[lb + 1] > end && !finishes_with_mixed(p, r, lb)) items.push_back(((uint32_t)t << 1) | 1u);
         }
     }
     r.n_late = (uint32_t)late.size();
@@ -232,22 +244,22 @@ constexpr int32_t LAZY_WAIT_LIMIT = 64;
 int refresh_limits_unguarded(ef_plan *p)
 {
     auto clamp = [](int64_t v) { return (int32_t)(v < 0 ? 0 : (v > ef::FUSE_LIMIT_MAX ? ef::FUSE_LIMIT_MAX : v)); };
+    ef_plan::Role &ticket = p->role[ROLE_TICKET], &server = p->role[ROLE_SERVER], &tiles = p->role[ROLE_TILES];
     if (p->user_fuse_limit >= 0) {
-        p->role[0].fuse_limit = p->role[1].fuse_limit = p->role[2].fuse_limit = clamp(p->user_fuse_limit);
+        ticket.fuse_limit = server.fuse_limit = tiles.fuse_limit = clamp(p->user_fuse_limit);
     } else if (p->lazy) {
         // With the correction deferred nothing has to wait for a block's scale.  The server and
         // the persistent worker kernel then run fastest without any wait; the worker kernel with
         // one workgroup per tile runs fastest when consecutive tiles are written out in step,
         // which small blocks get by waiting for their scale as usual and larger ones through
-        // Layout::sync_group.
-        p->role[0].fuse_limit = p->persistent_forced ? 0 : LAZY_WAIT_LIMIT;
-        p->role[1].fuse_limit = 0;
-        // the buffers a call leaves behind must fit the lists of whichever worker call comes next
-        p->role[2].fuse_limit = p->role[0].fuse_limit;
+        // Layout::sync_group.  Both worker roles get the same limit: the buffers a call leaves
+        // behind must fit the lists of whichever worker call comes next.
+        ticket.fuse_limit = tiles.fuse_limit = p->persistent_forced ? 0 : LAZY_WAIT_LIMIT;
+        server.fuse_limit = 0;
     } else {
-        p->role[0].fuse_limit = clamp(p->persistent ? p->lim_persistent : p->lim_direct);
-        p->role[1].fuse_limit = clamp(p->lim_server);
-        p->role[2].fuse_limit = clamp(p->lim_direct);
+        ticket.fuse_limit = clamp(p->lim_persistent);
+        server.fuse_limit = clamp(p->lim_server);
+        tiles.fuse_limit = clamp(p->lim_direct);
     }
     p->L.fuse_limit = p->role[0].fuse_limit;
     for (auto &r : p->role) {
@@ -305,7 +317,7 @@ int build_device(ef_plan *p)
     // one 128-byte line per tile and set: a block's ready word sits in the line of its gatherer tile
     EF_HIP(hipMalloc(&p->d_ready, sizeof(unsigned long long) * ef::READY_STRIDE * (size_t)ntiles * nsets));
     EF_HIP(hipMemset(p->d_ready, 0, sizeof(unsigned long long) * ef::READY_STRIDE * (size_t)ntiles * nsets));
-    EF_HIP(hipMalloc(&p->d_list_cnt, sizeof(unsigned int) * 6));
+    EF_HIP(hipMalloc(&p->d_list_cnt, sizeof(unsigned int) * 8));
     EF_HIP(hipMalloc(&p->d_defer_list, sizeof(unsigned long long) * 2 * (size_t)ntiles * nsets));
     EF_HIP(hipMalloc(&p->d_fin_list, sizeof(unsigned long long) * max_cross * nsets));
     for (auto &r : p->role) {
@@ -334,7 +346,7 @@ int build_device(ef_plan *p)
         p->L.mixed_tiles = p->d_mixed;
         p->L.uniform_tiles = p->d_uniform;
     }
-    EF_HIP(hipMemset(p->d_list_cnt, 0, sizeof(unsigned int) * 6));
+    EF_HIP(hipMemset(p->d_list_cnt, 0, sizeof(unsigned int) * 8));
     EF_HIP(hipMalloc(&p->d_state, sizeof(ef::CallState)));
     EF_HIP(hipMemset(p->d_state, 0, sizeof(ef::CallState)));     // the zeroed partial words carry tag 0
     p->L.offs = p->d_offs;
@@ -355,7 +367,7 @@ int build_device(ef_plan *p)
         EF_HIP(hipGetDeviceProperties(&prop, p->device));
         int occ_w = 0, occ_s = 0;
         EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_w, ef::k_worker_uniform<true>, ef::THREADS, 0));
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server_uniform, ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_s, ef::k_server_tiles<true>, ef::THREADS, 0));
         if (occ_w < 1) occ_w = 1;
         p->worker_grid = prop.multiProcessorCount * occ_w;
         // one-pass blocks must fit twice over into the tiles a kernel's workgroups hold at once:
@@ -363,7 +375,7 @@ int build_device(ef_plan *p)
         // run one workgroup per tile (dispatched in grid order).  Larger limits were measured slower:
         // a block that fills most of the machine makes its first tiles wait for its last.
         int occ_d = 0;
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, ef::k_worker_uniform_direct<true>, ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, (ef::k_worker_tiles<true, true>), ef::THREADS, 0));
         p->lim_persistent = (int32_t)((int64_t)p->worker_grid * (ef::PIPE_DEPTH + ef::STAGE_DEPTH) / 2);
         p->lim_direct = (int32_t)((int64_t)prop.multiProcessorCount * occ_d / 2);
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
@@ -419,6 +431,19 @@ int build_device(ef_plan *p)
     return EF_OK;
 }
 
+// Which worker kernel a call runs.  The persistent kernel (ROLE_TICKET) where plan creation or
+// the caller chose it, with two exceptions.  The momentum-free worker moves 48 KiB per tile
+// instead of 80: one ticket per tile would make the ticket counter (about 84 tickets per
+// microsecond) its bottleneck, so it runs one workgroup per tile unless the persistent kernel
+// was asked for explicitly.  And in the deferred mode the kernel with one workgroup per tile is
+// the faster one (see refresh_limits).
+int worker_role(const ef_plan *plan, bool has_mom)
+{
+    const bool ticketed = plan->L.n_uniform && plan->persistent &&
+                          (plan->lazy ? plan->persistent_forced != 0 : (has_mom || plan->persistent_forced));
+    return ticketed ? ROLE_TICKET : ROLE_TILES;
+}
+
 // Scratch argument of one call over the sets [set_base, set_base + nsets).  Everything that
 // differs between two calls of the same kind is read by the kernels from device memory.
 struct CallScratch {
@@ -435,7 +460,7 @@ CallScratch next_call(const ef_plan *plan, int set_base, int nsets)
     return c;
 }
 
-// The kernels after the main one: missing scales, parked residuals, and the step to the next call.
+// The kernel after the main one(s): missing scales, parked residuals, and the step to the next call.
 ef::Layout role_layout(const ef_plan *plan, int role)
 {
     ef::Layout L = plan->L;
@@ -446,20 +471,38 @@ ef::Layout role_layout(const ef_plan *plan, int role)
     return L;
 }
 
-int launch_second_pass(const ef_plan *plan, int role, const CallScratch &c, int nsets, float *err,
-                       int64_t err_stride, float *scales, int64_t scales_stride, hipStream_t s)
+int launch_tail(const ef_plan *plan, int role, const CallScratch &c, int nsets, float *err, int64_t err_stride,
+                float *scales, int64_t scales_stride, hipStream_t s)
 {
     const ef_plan::Role &r = plan->role[role];
     const ef::Layout L = role_layout(plan, role);
-    hipLaunchKernelGGL(ef::k_finalize_scales, dim3(r.n_late * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s, L, c.X,
-                       (const int32_t *)r.d_late, (int)r.n_late, nsets, scales, scales_stride);
+    ef::TailArgs T;
+    T.late_blocks = r.d_late;
+    T.n_late = (int)r.n_late;
+    T.items = r.d_static;
+    T.n_items = (int)r.n_static;
+    T.nsets = nsets;
+    T.err = err;
+    T.err_stride = err_stride;
+    T.scales = scales;
+    T.scales_stride = scales_stride;
+    const int64_t n_fin = (int64_t)r.n_late * nsets, n_res = (int64_t)r.n_static * nsets;
+    // a long list of parked segments is streamed by a kernel of its own, after this one has formed the scales
+    const bool res_apart = n_res > ef::RES_IN_TAIL_MAX;
+    if (res_apart) T.n_items = 0;
+    T.fin_wgs = (int)(n_fin < ef::FIN_WGS_MAX ? n_fin : ef::FIN_WGS_MAX);
+    T.res_wgs = res_apart ? 0 : (int)(n_res < ef::RES_WGS_MAX ? n_res : ef::RES_WGS_MAX);
+    T.state = plan->d_state;
+    T.lazy = plan->lazy;
+    hipLaunchKernelGGL(ef::k_tail, dim3((unsigned)(T.fin_wgs + T.res_wgs + ef::DEFER_WGS)), dim3(ef::THREADS), 0, s, L,
+                       c.X, T);
     EF_HIP(hipGetLastError());
-    hipLaunchKernelGGL(ef::k_residual_parked, dim3(r.n_static * nsets + ef::DEFER_WGS), dim3(ef::THREADS), 0, s, L,
-                       c.X, (const uint32_t *)r.d_static, (int)r.n_static, nsets, err, err_stride,
-                       (const float *)scales, scales_stride);
-    EF_HIP(hipGetLastError());
-    hipLaunchKernelGGL(ef::k_advance, dim3(1), dim3(64), 0, s, plan->d_state, c.X.set_base, nsets, plan->lazy);
-    EF_HIP(hipGetLastError());
+    if (res_apart) {
+        hipLaunchKernelGGL(ef::k_residual_static, dim3(r.n_static, (unsigned)nsets), dim3(ef::THREADS), 0, s, L,
+                           (const uint32_t *)r.d_static, (int)r.n_static, err, err_stride, (const float *)scales,
+                           scales_stride);
+        EF_HIP(hipGetLastError());
+    }
     return EF_OK;
 }
 
@@ -603,12 +646,12 @@ int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_strid
             plan->lazy_buf[0] = nullptr;
             plan->lazy_sets_seen = 0;
         }
-        const ef_plan::Role &r = plan->role[role];
+        const ef_plan::Role &r = plan->role[role == 0 ? ROLE_TILES : ROLE_SERVER];
         const int nsets = role == 0 ? n_workers : 1;
         const CallScratch c = next_call(plan, role == 0 ? 0 : plan->max_workers, nsets);
         if (r.n_lazy_tiles) {
             hipLaunchKernelGGL(ef::k_flush, dim3(r.n_lazy_tiles, (unsigned)nsets), dim3(ef::THREADS), 0, s,
-                               role_layout(plan, role), c.X, (const int32_t *)r.d_lazy_tiles, (int)r.n_lazy_tiles, buf,
+                               role_layout(plan, role == 0 ? ROLE_TILES : ROLE_SERVER), c.X, (const int32_t *)r.d_lazy_tiles, (int)r.n_lazy_tiles, buf,
                                role == 0 ? state_stride : (int64_t)0);
             EF_HIP(hipGetLastError());
         }
@@ -633,7 +676,11 @@ int ef_plan_tune(ef_plan *plan, int fuse_limit, int spin_limit)
     return EF_OK;
 }
 
-int ef_plan_fuse_limit(const ef_plan *plan) { return plan ? plan->role[0].fuse_limit : 0; }
+int ef_plan_fuse_limit(const ef_plan *plan)
+{
+    if (!plan) return 0;
+    return plan->role[worker_role(plan, true)].fuse_limit;
+}
 int ef_plan_is_persistent(const ef_plan *plan)
 {
     if (!plan) return 0;
@@ -786,24 +833,18 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
         if (n_workers > plan->lazy_sets_seen) plan->lazy_sets_seen = n_workers;
     }
     const CallScratch c = next_call(plan, 0, n_workers);
-    // The momentum-free worker moves 48 KiB per tile instead of 80: one ticket per tile would
-    // make the ticket counter (about 84 tickets per microsecond) its bottleneck, so it runs one
-    // workgroup per tile unless the persistent kernel was asked for explicitly.  That kernel has
-    // its own one-pass limit, hence its own lists (role 2).
-    // In the deferred mode the kernel with one workgroup per tile is the faster one (see refresh_limits).
-    const bool ticketed = plan->L.n_uniform && plan->persistent &&
-                          (plan->lazy ? plan->persistent_forced != 0 : (has_mom || plan->persistent_forced));
-    const int role = ticketed || !plan->persistent ? 0 : 2;
+    const int role = worker_role(plan, has_mom);
     const ef::Layout L = role_layout(plan, role);
-    if (plan->L.n_mixed) {
-        const dim3 grid((unsigned)plan->L.n_mixed, (unsigned)n_workers);
-        if (has_mom)
-            hipLaunchKernelGGL(ef::k_worker_mixed<true>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
-        else
-            hipLaunchKernelGGL(ef::k_worker_mixed<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
-        EF_HIP(hipGetLastError());
-    }
-    if (ticketed) {
+    if (role == ROLE_TICKET) {
+        // the mixed tiles first, in a kernel of their own, then the persistent kernel
+        if (plan->L.n_mixed) {
+            const dim3 grid((unsigned)plan->L.n_mixed, (unsigned)n_workers);
+            if (has_mom)
+                hipLaunchKernelGGL(ef::k_worker_mixed<true>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
+            else
+                hipLaunchKernelGGL(ef::k_worker_mixed<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
+            EF_HIP(hipGetLastError());
+        }
         int64_t wgs = (int64_t)plan->L.n_uniform * n_workers;
         if (wgs > plan->worker_grid) wgs = plan->worker_grid;
         const dim3 grid((unsigned)wgs), block(ef::THREADS);
@@ -812,15 +853,21 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
         else
             hipLaunchKernelGGL(ef::k_worker_uniform<false>, grid, block, 0, s, L, c.X, A, n_workers);
         EF_HIP(hipGetLastError());
-    } else if (plan->L.n_uniform) {
-        const dim3 grid((unsigned)plan->L.n_uniform, (unsigned)n_workers);
-        if (has_mom)
-            hipLaunchKernelGGL(ef::k_worker_uniform_direct<true>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
+    } else {
+        // every tile in one launch, the mixed tiles first
+        const dim3 grid((unsigned)plan->L.ntiles, (unsigned)n_workers), block(ef::THREADS);
+        const bool mixed = plan->L.n_mixed != 0;
+        if (has_mom && mixed)
+            hipLaunchKernelGGL((ef::k_worker_tiles<true, true>), grid, block, 0, s, L, c.X, A);
+        else if (has_mom)
+            hipLaunchKernelGGL((ef::k_worker_tiles<true, false>), grid, block, 0, s, L, c.X, A);
+        else if (mixed)
+            hipLaunchKernelGGL((ef::k_worker_tiles<false, true>), grid, block, 0, s, L, c.X, A);
         else
-            hipLaunchKernelGGL(ef::k_worker_uniform_direct<false>, grid, dim3(ef::THREADS), 0, s, L, c.X, A);
+            hipLaunchKernelGGL((ef::k_worker_tiles<false, false>), grid, block, 0, s, L, c.X, A);
         EF_HIP(hipGetLastError());
     }
-    return launch_second_pass(plan, role, c, n_workers, err, state_stride, scales, scales_stride, s);
+    return launch_tail(plan, role, c, n_workers, err, state_stride, scales, scales_stride, s);
 }
 
 int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, int64_t in_signs_stride,
@@ -863,19 +910,15 @@ int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, i
         plan->lazy_buf[1] = server_err;
     }
     const CallScratch c = next_call(plan, plan->max_workers, 1);
-    const ef::Layout L = role_layout(plan, 1);
-    // mixed tiles first: they never wait, and the uniform tiles' gathers need their partials
-    if (L.n_mixed) {
-        hipLaunchKernelGGL(ef::k_server_mixed, dim3((unsigned)L.n_mixed), dim3(ef::THREADS), 0, s, L, c.X, A,
+    const ef::Layout L = role_layout(plan, ROLE_SERVER);
+    if (L.n_mixed)
+        hipLaunchKernelGGL(ef::k_server_tiles<true>, dim3((unsigned)L.ntiles), dim3(ef::THREADS), 0, s, L, c.X, A,
                            plan->max_workers);
-        EF_HIP(hipGetLastError());
-    }
-    if (L.n_uniform) {
-        hipLaunchKernelGGL(ef::k_server_uniform, dim3((unsigned)L.n_uniform), dim3(ef::THREADS), 0, s, L, c.X, A,
+    else
+        hipLaunchKernelGGL(ef::k_server_tiles<false>, dim3((unsigned)L.ntiles), dim3(ef::THREADS), 0, s, L, c.X, A,
                            plan->max_workers);
-        EF_HIP(hipGetLastError());
-    }
-    return launch_second_pass(plan, 1, c, 1, server_err, (int64_t)0, out_scales, (int64_t)0, s);
+    EF_HIP(hipGetLastError());
+    return launch_tail(plan, ROLE_SERVER, c, 1, server_err, (int64_t)0, out_scales, (int64_t)0, s);
 }
 
 }  // namespace

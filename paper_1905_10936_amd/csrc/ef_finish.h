@@ -4,14 +4,13 @@
 
 namespace ef {
 
-// ---------------------------------------------------- second-pass kernels ---
+// ------------------------------------------- the kernel that ends a call ---
 
 // e <- p - Delta on one open segment of a tile whose p was parked in the
-// residual buffer (e_{t+1} = p_t - Delta_t of Algorithm 4), now that every scale
-// exists.  The sign is taken from p itself.  which: 0 = first (or only)
+// residual buffer (e_{t+1} = p_t - Delta_t of Algorithm 4), now that its block's
+// scale s exists.  The sign is taken from p itself.  which: 0 = first (or only)
 // segment of the tile, 1 = last segment.
-__device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, int which, float *err_set,
-                                                 const float *scales)
+__device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, int which, float *err_set, float s)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const int n_valid = tile_valid(L, tile);
@@ -22,22 +21,18 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
         // streamed like the first pass streams it
         float4 v[SUBROWS];
         load_tile(err_tile, v, TILE);
-        const float sb = scales[fb];
 #pragma unroll
-        for (int k = 0; k < SUBROWS; ++k) residual4(v[k], sb);
+        for (int k = 0; k < SUBROWS; ++k) residual4(v[k], s);
         store_tile(err_tile, v, TILE);
         return;
     }
     int lo, hi;
-    float s;
     if (which == 0) {
         lo = 0;
         hi = (int)min(L.offs[fb + 1] - tile_start, (int64_t)n_valid);
-        s = scales[fb];
     } else {
         lo = (int)(L.offs[lb] - tile_start);
         hi = n_valid;
-        s = scales[lb];
     }
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
@@ -59,88 +54,158 @@ __device__ __forceinline__ void residual_segment(const Layout &L, int32_t tile, 
     }
 }
 
-// Scales the first kernels of a call did not write: those of the blocks on the
-// per-layout list (crossing blocks without a uniform tile, blocks larger than
-// fuse_limit: workgroups 0 .. n_late*nsets-1) and those whose gatherer gave
-// up gathering (list filled at run time: the last DEFER_WGS workgroups).
-__global__ __launch_bounds__(THREADS) void k_finalize_scales(Layout L, ScratchRef R, const int32_t *late_blocks,
-                                                             int n_late, int nsets, float *scales,
+// What the kernel that ends a call works through.
+struct TailArgs {
+    const int32_t *late_blocks;     // [n_late] blocks larger than fuse_limit: their scales are formed here
+    int n_late;
+    const uint32_t *items;          // [n_items] (tile << 1) | which: segments whose p the main kernels always park
+    int n_items;
+    int nsets;
+    float *err;                     // residual buffers of the call's sets, err_stride apart
+    int64_t err_stride;
+    float *scales;                  // scale arrays of the call's sets, scales_stride apart
+    int64_t scales_stride;
+    int fin_wgs, res_wgs;           // workgroups given to the two lists above
+    CallState *state;
+    int lazy;
+};
+
+// Scale of block b of `set` inside the kernel that ends a call.  Every partial of the call has
+// been posted by then, so the scale can always be formed on the spot from the partials (the
+// same sum in the same order, hence the same bits, whoever forms it); for a block of many tiles
+// that is worth avoiding, so the ready word is looked at first (bounded), where the main kernels
+// and this kernel's own workgroups post every scale they form.  Called by every thread of the
+// workgroup; same answer to all.
+__device__ __forceinline__ float tail_scale(const Layout &L, const Scratch &X, int set, int64_t b, SyncShared &S)
+{
+    const BlockSpan sp = block_span(L, b);
+    float s = 0.f;
+    if (sp.n > 2 * THREADS && wait_ready(b, 0ull, L, X, set, S, &s)) return s;
+    const double total = sum_block_partials(L, b, set_part(X, L, set), S.red);
+    return (float)(total / (double)(sp.be - sp.bs));
+}
+
+// The call is over: count it, flip the tags of the sets it used, clear the counters the next
+// call will use (one thread).
+__device__ __forceinline__ void advance_call(CallState *state, const Scratch &X, int nsets, int lazy)
+{
+    const unsigned long long used = nsets >= 64 ? ~0ull : ((1ull << nsets) - 1ull);
+    X.next_cnt[0] = 0u;
+    X.next_cnt[2] = 0u;
+    X.next_cnt[4] = 0u;
+    *X.done = 0u;
+    state->calls = state->calls + 1u;
+    if (X.set_base == 0) {
+        state->worker_tags ^= used;
+        // with the deferred correction on, the large blocks of these sets now hold p
+        state->worker_pending = lazy ? (state->worker_pending | used) : (state->worker_pending & ~used);
+    } else {
+        state->server_tag ^= 1u;
+        state->server_pending = lazy ? 1u : 0u;
+    }
+}
+
+// Ends a worker or server call.  In this order of workgroups:
+//   fin_wgs workgroups   form the scales of the blocks larger than fuse_limit (per-layout list),
+//                        write them out and post them in the blocks' ready words;
+//   res_wgs workgroups   e <- p - Delta on the segments whose p is always parked (per-layout
+//                        list: the open segments of those blocks, and the segments that
+//                        blocks with whole tiles have in mixed tiles);
+//   DEFER_WGS workgroups the same two jobs for what the main kernels gave up on at run time
+//                        (a gather or a wait that ran out): normally nothing.
+// Each workgroup strides over its list.  The last workgroup to finish steps the plan's call
+// state to the next call (no workgroup reads it after its first instructions).
+__global__ __launch_bounds__(THREADS) void k_tail(Layout L, ScratchRef R, TailArgs T)
+{
+    const Scratch X = open_call(R);
+    __shared__ SyncShared S;
+    const int wg = blockIdx.x;
+    if (wg < T.fin_wgs) {
+        const int n = T.n_late * T.nsets;
+        for (int i = wg; i < n; i += T.fin_wgs) {
+            const int64_t b = T.late_blocks[i % T.n_late];
+            const int w = i / T.n_late;
+            const int set = X.set_base + w;
+            const double total = sum_block_partials(L, b, set_part(X, L, set), S.red);
+            if (threadIdx.x == 0) {
+                const float sc = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+                T.scales[(int64_t)w * T.scales_stride + b] = sc;
+                __hip_atomic_store(ready_word(X, L, set, b),
+                                   ((unsigned long long)X.epoch << 32) | (unsigned long long)__float_as_uint(sc),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // remembered for the deferred correction of the block's residual
+                if (L.lazy && L.late_index[b] >= 0)
+                    X.lazy_scales[(int64_t)set * X.lazy_stride + L.late_index[b]] = sc;
+            }
+        }
+    } else if (wg < T.fin_wgs + T.res_wgs) {
+        const int64_t n = (int64_t)T.n_items * T.nsets;
+        int64_t have_b = -1;
+        int have_w = -1;
+        float s = 0.f;
+        for (int64_t i = wg - T.fin_wgs; i < n; i += T.res_wgs) {
+            const uint32_t it = T.items[i % T.n_items];
+            const int w = (int)(i / T.n_items);
+            const int32_t tile = (int32_t)(it >> 1);
+            const int which = (int)(it & 1u);
+            const int64_t b = which ? L.tile_lb[tile] : L.tile_fb[tile];
+            if (b != have_b || w != have_w) {       // consecutive items of a workgroup mostly share the block
+                s = tail_scale(L, X, X.set_base + w, b, S);
+                have_b = b;
+                have_w = w;
+            }
+            residual_segment(L, tile, which, T.err + (int64_t)w * T.err_stride, s);
+        }
+    } else {
+        const int q = wg - T.fin_wgs - T.res_wgs;
+        const unsigned n_fin = *X.fin_cnt;
+        for (unsigned i = q; i < n_fin; i += DEFER_WGS) {
+            const unsigned long long it = X.fin_list[i];
+            const int set = (int)(it >> 32);
+            const int64_t b = (int64_t)(it & 0xffffffffull);
+            const double total = sum_block_partials(L, b, set_part(X, L, set), S.red);
+            if (threadIdx.x == 0) {
+                const float sc = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
+                T.scales[(int64_t)(set - X.set_base) * T.scales_stride + b] = sc;
+                __hip_atomic_store(ready_word(X, L, set, b),
+                                   ((unsigned long long)X.epoch << 32) | (unsigned long long)__float_as_uint(sc),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        const unsigned n_def = *X.defer_cnt;
+        for (unsigned i = q; i < n_def; i += DEFER_WGS) {
+            const unsigned long long it = X.defer_list[i];
+            const int set = (int)(it >> 33);
+            const int32_t tile = (int32_t)((it >> 1) & 0xffffffffull);
+            const int which = (int)(it & 1ull);
+            const int64_t b = which ? L.tile_lb[tile] : L.tile_fb[tile];
+            const float s = tail_scale(L, X, set, b, S);
+            residual_segment(L, tile, which, T.err + (int64_t)(set - X.set_base) * T.err_stride, s);
+        }
+    }
+    // last one out steps the call state
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned before = atomicAdd(X.done, 1u);
+        if (before + 1u == gridDim.x) advance_call(T.state, X, T.nsets, T.lazy);
+    }
+}
+
+// A long per-layout list of parked segments (the whole tiles of blocks larger than fuse_limit when
+// the correction is not deferred) streams faster with one workgroup per item, dispatched in list
+// order, than through the strided loop of k_tail, and a grid of that size is too large for that
+// kernel's count of finished workgroups.  So this kernel runs after k_tail, with the scales taken
+// from the call's finished scale arrays.  One workgroup per (item, set).
+__global__ __launch_bounds__(THREADS) void k_residual_static(Layout L, const uint32_t *items, int n_items, float *err,
+                                                             int64_t err_stride, const float *scales,
                                                              int64_t scales_stride)
 {
-    const Scratch X = open_call(R);
-    __shared__ double red[NWAVES];
-    const int n_static = n_late * nsets;
-    if ((int)blockIdx.x < n_static) {
-        const int64_t b = late_blocks[blockIdx.x % n_late];
-        const int w = blockIdx.x / n_late;
-        const double total = sum_block_partials(L, b, set_part(X, L, X.set_base + w), red);
-        if (threadIdx.x == 0) {
-            const float sc = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
-            scales[(int64_t)w * scales_stride + b] = sc;
-            // remembered for the deferred correction of the block's residual
-            if (L.lazy && L.late_index[b] >= 0)
-                X.lazy_scales[(int64_t)(X.set_base + w) * X.lazy_stride + L.late_index[b]] = sc;
-        }
-        return;
-    }
-    const unsigned n = *X.fin_cnt;
-    for (unsigned i = blockIdx.x - n_static; i < n; i += DEFER_WGS) {
-        const unsigned long long it = X.fin_list[i];
-        const int set = (int)(it >> 32);
-        const int64_t b = (int64_t)(it & 0xffffffffull);
-        const double total = sum_block_partials(L, b, set_part(X, L, set), red);
-        if (threadIdx.x == 0)
-            scales[(int64_t)(set - X.set_base) * scales_stride + b] = (float)(total / (double)(L.offs[b + 1] - L.offs[b]));
-    }
-}
-
-// e <- p - Delta wherever the first kernels parked p: the segments on the
-// per-layout list (open segments of mixed tiles, tiles of blocks larger than
-// fuse_limit: workgroups 0 .. n_items*nsets-1) and the tiles whose wait ran out
-// (list filled at run time: the last DEFER_WGS workgroups).  Also clears the
-// list counters the next call will use.
-__global__ __launch_bounds__(THREADS) void k_residual_parked(Layout L, ScratchRef R, const uint32_t *items,
-                                                             int n_items, int nsets, float *err, int64_t err_stride,
-                                                             const float *scales, int64_t scales_stride)
-{
-    const Scratch X = open_call(R);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        X.next_cnt[0] = 0u;
-        X.next_cnt[2] = 0u;
-        X.next_cnt[4] = 0u;
-    }
-    const int n_static = n_items * nsets;
-    if ((int)blockIdx.x < n_static) {
-        const uint32_t it = items[blockIdx.x % n_items];
-        const int w = blockIdx.x / n_items;
-        residual_segment(L, (int32_t)(it >> 1), (int)(it & 1u), err + (int64_t)w * err_stride,
-                         scales + (int64_t)w * scales_stride);
-        return;
-    }
-    const unsigned n = *X.defer_cnt;
-    for (unsigned i = blockIdx.x - n_static; i < n; i += DEFER_WGS) {
-        const unsigned long long it = X.defer_list[i];
-        const int w = (int)(it >> 33) - X.set_base;
-        const int32_t tile = (int32_t)((it >> 1) & 0xffffffffull);
-        residual_segment(L, tile, (int)(it & 1ull), err + (int64_t)w * err_stride, scales + (int64_t)w * scales_stride);
-    }
-}
-
-// The call is over: count it and flip the tags of the sets it used (one thread).
-__global__ void k_advance(CallState *state, int set_base, int nsets, int lazy)
-{
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        const unsigned long long used = nsets >= 64 ? ~0ull : ((1ull << nsets) - 1ull);
-        state->calls = state->calls + 1u;
-        if (set_base == 0) {
-            state->worker_tags ^= used;
-            // with the deferred correction on, the large blocks of these sets now hold p
-            state->worker_pending = lazy ? (state->worker_pending | used) : (state->worker_pending & ~used);
-        } else {
-            state->server_tag ^= 1u;
-            state->server_pending = lazy ? 1u : 0u;
-        }
-    }
+    const uint32_t it = items[blockIdx.x];
+    const int w = blockIdx.y;
+    const int32_t tile = (int32_t)(it >> 1);
+    const int which = (int)(it & 1u);
+    const int64_t b = which ? L.tile_lb[tile] : L.tile_fb[tile];
+    residual_segment(L, tile, which, err + (int64_t)w * err_stride, scales[(int64_t)w * scales_stride + b]);
 }
 
 // Deferred correction made now (ef_flush): e <- p - Delta on the whole tiles of the blocks larger

@@ -40,10 +40,17 @@
 //     writes the scale and posts (call number, scale) in the block's "ready"
 //     word -- no counter, hence no read-modify-write on a shared address;
 //   * the others look at the ready word when they come to write the tile.
-// Mixed tiles never wait: their open segments, like all tiles of blocks larger
-// than fuse_limit and any tile whose (bounded) wait ran out, get p parked in
-// the residual buffer; a small kernel then computes the scales still missing
-// and another subtracts the decoded value where p was parked.
+// Mixed tiles are handed out before the whole tiles (first in the grid of the
+// kernel that runs one workgroup per tile; in a kernel of their own before the
+// persistent worker kernel), so their partial sums are there when a block's
+// last whole tile comes to form the scale.  They never wait for a whole tile:
+// a block without whole tiles is finished among the mixed tiles themselves
+// (its last tile forms its scale, the others wait for it), while the segments
+// that a block with whole tiles has in mixed tiles get p parked in the
+// residual buffer.  Parked p (those segments, all tiles of blocks larger than
+// fuse_limit, any tile whose bounded wait ran out) is finished by one kernel
+// after the main one, which also computes the scales still missing and steps
+// the plan to its next call.
 //
 // Deferred correction (optional)
 // ------------------------------
@@ -63,7 +70,10 @@ constexpr int NWAVES = THREADS / 64;
 constexpr int SUBROWS = 4;      // float4 per thread
 constexpr int SMALL_SEG = 64;   // segments up to this length are summed by one thread
 constexpr int MAX_LONG = TILE / SMALL_SEG;
-constexpr int DEFER_WGS = 64;   // workgroups that serve the run-time lists of the second-pass kernels
+constexpr int DEFER_WGS = 16;   // workgroups that serve the run-time lists in the kernel that ends a call
+constexpr int FIN_WGS_MAX = 512;    // most workgroups that kernel gives to the scales of blocks larger than fuse_limit ...
+constexpr int RES_WGS_MAX = 2048;   // ... and to the segments whose p was parked
+constexpr int RES_IN_TAIL_MAX = 4 * RES_WGS_MAX;    // longer lists of parked segments get a kernel of their own
 #ifndef EF_PIPE_DEPTH
 #define EF_PIPE_DEPTH 3
 #endif
@@ -111,7 +121,7 @@ struct ScratchRef {
     unsigned long long *ready;
     unsigned long long *defer_list;
     unsigned long long *fin_list;
-    unsigned int *list_cnt;             // [6]: defer_cnt[2], fin_cnt[2], ticket[2]; a call uses those of its parity
+    unsigned int *list_cnt;             // [8]: defer_cnt[2], fin_cnt[2], ticket[2] (a call uses those of its parity), done, unused
     float *lazy_scales;                 // [nsets][lazy_stride] last scale of every block larger than fuse_limit
     int lazy_stride;
     const CallState *state;
@@ -133,6 +143,7 @@ struct Scratch {
     int set_base;               // first set this call uses (0 for workers, max_workers for the server)
     int spin_limit;             // polls before a waiting workgroup gives up and parks p
     unsigned int *next_cnt;     // the three list counters of the next call (zeroed by this call's last kernel)
+    unsigned int *done;         // workgroups of the call's last kernel that have finished (0 between calls)
     // Deferred correction.  A block larger than fuse_limit cannot have its residual finished in
     // the first kernel; instead of a second pass over it (p written, read back, e written: 8 more
     // bytes per element), the residual buffer keeps p, the block's scale is remembered here, and
@@ -158,6 +169,7 @@ __device__ __forceinline__ Scratch open_call(const ScratchRef &R)
     X.fin_cnt = R.list_cnt + 2 + cur;
     X.ticket = R.list_cnt + 4 + cur;
     X.next_cnt = R.list_cnt + (cur ^ 1u);
+    X.done = R.list_cnt + 6;
     // this call's tags are the stored ones flipped
     if (R.set_base == 0) {
         const unsigned long long t = R.state->worker_tags;
@@ -437,10 +449,17 @@ __device__ __forceinline__ bool has_uniform_tile(const BlockSpan &s)
     return s.n - ((s.bs % TILE) != 0 ? 1 : 0) - ((s.be % TILE) != 0 ? 1 : 0) >= 1;
 }
 
-// One-pass blocks: their scale is formed and posted inside the first kernels.
+// One-pass blocks: their scale is formed and posted inside the main kernel(s) of the call.
 __device__ __forceinline__ bool is_counted(const Layout &L, const BlockSpan &s)
 {
-    return s.n >= 2 && s.n <= L.fuse_limit && has_uniform_tile(s);
+    return s.n >= 2 && s.n <= L.fuse_limit;
+}
+
+// A one-pass block without a whole tile: all its tiles are mixed ones, which form its scale (in
+// the block's last tile) and finish its segments among themselves.
+__device__ __forceinline__ bool finishes_with_mixed(const Layout &L, const BlockSpan &s)
+{
+    return is_counted(L, s) && !has_uniform_tile(s);
 }
 
 // Scratch word of block b's segment in tile t: slot 1 of the block's first tile
@@ -451,14 +470,21 @@ __device__ __forceinline__ int64_t part_index(int64_t t, const BlockSpan &s)
     return 2 * t + ((t == s.t0 && (s.bs % TILE) != 0) ? 1 : 0);
 }
 
-// The block's last whole tile: the workgroup that takes it forms the scale.
-__device__ __forceinline__ int64_t gatherer_tile(const BlockSpan &s)
+// The block's last whole tile (meaningful if it has one).
+__device__ __forceinline__ int64_t last_whole_tile(const BlockSpan &s)
 {
     return s.t0 + s.n - 1 - ((s.be % TILE) != 0 ? 1 : 0);
 }
 
-// The ready word of a one-pass block: where its gatherer posts (call number, scale) and the
-// workgroups of its other tiles look for it.  Every block has a 128-byte line of its own, found
+// The tile whose workgroup forms the block's scale: the block's last whole tile, or its last tile
+// if it has no whole one.
+__device__ __forceinline__ int64_t gatherer_tile(const Layout &L, const BlockSpan &s)
+{
+    return has_uniform_tile(s) ? last_whole_tile(s) : s.t0 + s.n - 1;
+}
+
+// The ready word of a block that spans tiles: where its scale is posted with the call number and
+// the workgroups of its other tiles look for it.  Every block has a 128-byte line of its own, found
 // through its gatherer tile (different blocks have different gatherer tiles): with the words of
 // neighbouring blocks in one line, the gatherers' stores and the other tiles' polls of up to 16
 // blocks met in that line, which cost the kernels that wait in place up to a third of their
@@ -467,7 +493,7 @@ __device__ __forceinline__ int64_t gatherer_tile(const BlockSpan &s)
 constexpr int READY_STRIDE = 16;    // 64-bit words
 __device__ __forceinline__ unsigned long long *ready_word(const Scratch &X, const Layout &L, int set, int64_t b)
 {
-    return X.ready + ((int64_t)set * L.ntiles + gatherer_tile(block_span(L, b))) * READY_STRIDE;
+    return X.ready + ((int64_t)set * L.ntiles + gatherer_tile(L, block_span(L, b))) * READY_STRIDE;
 }
 
 // What a uniform tile has to follow up on after posting its partial: the block
@@ -564,14 +590,15 @@ __device__ __forceinline__ bool gather_scale(int64_t b, const Layout &L, const S
     return true;
 }
 
-// The workgroup that holds the last whole tile of counted block b forms the
+// The workgroup that holds the gatherer tile of one-pass block b forms the
 // scale from the partials (waiting, bounded, for those still in flight: every
 // other tile of the block was handed out earlier), writes it out and posts it
-// for the block's other tiles.  Called by every thread of that workgroup.
-__device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const Scratch &X, int set,
-                                             float *scales_out, SyncShared &S)
+// for the block's other tiles.  Called by every thread of that workgroup;
+// returns to all of them whether the scale could be formed, and the scale.
+__device__ __forceinline__ bool finish_block(int64_t b, const Layout &L, const Scratch &X, int set,
+                                             float *scales_out, SyncShared &S, float *scale)
 {
-    float s;
+    float s = 0.f;
     const bool ok = gather_scale(b, L, X, set, S, &s);
     if (threadIdx.x == 0) {
         if (ok) {
@@ -584,6 +611,8 @@ __device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const S
             X.fin_list[k] = ((unsigned long long)set << 32) | (unsigned long long)b;
         }
     }
+    *scale = s;
+    return ok;
 }
 
 // Follow up on what a uniform tile posted: if it is its block's last whole
@@ -591,7 +620,8 @@ __device__ __forceinline__ void finish_block(int64_t b, const Layout &L, const S
 __device__ __forceinline__ void resolve_posted(const Posted &P, const Layout &L, const Scratch &X, int set,
                                                float *scales_out, SyncShared &S)
 {
-    if (P.gather >= 0) finish_block(P.gather, L, X, set, scales_out, S);
+    float s;
+    if (P.gather >= 0) (void)finish_block(P.gather, L, X, set, scales_out, S, &s);
 }
 
 // Thread 0's early look at the ready word of block b (b < 0: none).
@@ -641,11 +671,12 @@ __device__ __forceinline__ void defer_segment(int32_t tile, int which, const Scr
 
 // ------------------------------------------------------- tile compression ---
 
-// Mixed tile (several blocks meet): sign words; segmented fp64 sums through LDS;
-// scales and residuals e' = p - Delta of the closed segments; partial sums of
-// the (at most two) open segments posted, their elements stored as p for the
-// second-pass kernels.  Never waits for another workgroup.  (Section 3.2 and
-// e_{t+1} = p_t - Delta_t of Algorithm 4.)
+// Mixed tile (several blocks meet, or the ragged end of the vector): sign words;
+// segmented fp64 sums through LDS; scales and residuals e' = p - Delta of the
+// closed segments; partial sums of the (at most two) open segments posted, and
+// their residuals finished too where the block's scale forms inside this kernel
+// (bounded waits), else their elements stored as p for the kernel that ends the
+// call.  (Section 3.2 and e_{t+1} = p_t - Delta_t of Algorithm 4.)
 __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layout &L, int32_t tile, int n_valid,
                                                uint64_t *signs, float *scales_out, float *err_tile,
                                                const Scratch &X, int set, TileShared &S)
@@ -709,6 +740,22 @@ __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layou
     const int tail_begin = tail_open ? (int)(L.offs[lb] - tile_start) : TILE;
     if (head_open) store_partial(S.open_sum[0], 0, tile, L, X, set);
     if (tail_open) store_partial(S.open_sum[1], 1, tile, L, X, set);
+    // An open segment whose block has no whole tile is finished in place: all tiles of such a
+    // block are mixed ones, handed out before any whole tile and in ascending order.  The first
+    // segment's block ends in this tile, which makes this workgroup the one that forms its scale;
+    // the last segment's block goes on, and its scale comes from the next mixed tile.  The segments
+    // of other blocks, and any whose wait runs out, keep p in the residual buffer for the kernel
+    // that ends the call.
+    float s_head = 0.f, s_tail = 0.f;
+    bool fin_head = false, fin_tail = false;
+    if (head_open && finishes_with_mixed(L, block_span(L, fb))) {
+        fin_head = finish_block(fb, L, X, set, scales_out, S, &s_head);
+        if (!fin_head) defer_segment(tile, 0, X, set);
+    }
+    if (tail_open && finishes_with_mixed(L, block_span(L, lb))) {
+        fin_tail = wait_ready(lb, 0ull, L, X, set, S, &s_tail);
+        if (!fin_tail) defer_segment(tile, 1, X, set);
+    }
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
         const int lb0 = local_base(k);
@@ -719,7 +766,12 @@ __device__ __forceinline__ void compress_mixed(float4 (&p)[SUBROWS], const Layou
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int j = lb0 + c;
-            ev[c] = (j < head_end || j >= tail_begin) ? pv[c] : residual(pv[c], sv[c]);
+            if (j < head_end)
+                ev[c] = fin_head ? residual(pv[c], s_head) : pv[c];
+            else if (j >= tail_begin)
+                ev[c] = fin_tail ? residual(pv[c], s_tail) : pv[c];
+            else
+                ev[c] = residual(pv[c], sv[c]);
         }
         p[k] = make_float4(ev[0], ev[1], ev[2], ev[3]);
     }
@@ -791,7 +843,7 @@ __device__ __forceinline__ int compress_uniform(float4 (&p)[SUBROWS], const Layo
         store_tile(err_tile, p, n_valid);
         return UNI_PARKED;
     }
-    if ((int64_t)tile == gatherer_tile(sp)) P.gather = b;
+    if ((int64_t)tile == gatherer_tile(L, sp)) P.gather = b;
     return UNI_PENDING;
 }
 
@@ -830,11 +882,12 @@ __device__ __forceinline__ void sync_group_wait(int32_t tile, const Layout &L, c
 {
     const BlockSpan sp = block_span(L, L.tile_fb[tile]);
     const int64_t first_whole = sp.t0 + ((sp.bs % TILE) != 0 ? 1 : 0);
-    const int64_t last_whole = gatherer_tile(sp);
+    const int64_t last_whole = last_whole_tile(sp);
     const int64_t g0 = first_whole + ((int64_t)tile - first_whole) / L.sync_group * L.sync_group;
     const int64_t g1 = min(g0 + L.sync_group - 1, last_whole);
     if (g1 == g0) return;
-    unsigned long long *line = X.ready + ((int64_t)set * L.ntiles + g1) * READY_STRIDE;
+    // the second word of the tile's line: the first may be the block's ready word
+    unsigned long long *line = X.ready + ((int64_t)set * L.ntiles + g1) * READY_STRIDE + 1;
     if ((int64_t)tile == g1) {
         const unsigned long long *part = set_part(X, L, set);
         const unsigned long long tag = set_tag(X, set);
@@ -864,7 +917,7 @@ __device__ __forceinline__ void sync_group_wait(int32_t tile, const Layout &L, c
 }
 
 // Fill S.val (read as int) with the segment index of every element of a mixed
-// tile, so that element j can look up scale[fb + seg].
+// tile (0 past the end of the vector), so that element j can look up scale[fb + seg].
 __device__ __forceinline__ void build_segment_index(const Layout &L, int32_t tile, int n_valid, int32_t fb,
                                                     int nseg, TileShared &S)
 {
@@ -872,6 +925,7 @@ __device__ __forceinline__ void build_segment_index(const Layout &L, int32_t til
     int *seg = reinterpret_cast<int *>(S.val);
     if (threadIdx.x == 0) S.n_long = 0;
     __syncthreads();
+    for (int j = n_valid + (int)threadIdx.x; j < TILE; j += THREADS) seg[j] = 0;
     for (int sg = threadIdx.x; sg < nseg; sg += THREADS) {
         const int lo = (int)max(L.offs[fb + sg] - tile_start, (int64_t)0);
         const int hi = (int)min(L.offs[fb + sg + 1] - tile_start, (int64_t)n_valid);

@@ -264,45 +264,82 @@ void k_worker_uniform(Layout L, ScratchRef R, WorkerArgs A, int n_workers)
     persistent_uniform(L, X, prod, n_workers, S, stage);
 }
 
-// Uniform tiles of all workers, one workgroup per (tile, worker): the same
-// steps without the pipeline; the workgroup waits in place for its block's
-// scale.  Relies on workgroups being dispatched in grid order (fuse_limit keeps
-// a block's tiles well inside what is resident at once) and on spin_limit.
-// Eight workgroups per CU (64 VGPRs, a few spilled): the one-pass limit is half
-// of what is resident, and 2048 resident workgroups let blocks of up to 1024
-// tiles (4 Mi elements) finish in one pass (measured: 27.1 -> 24.4 ms on the
-// transformer-like layout, no change elsewhere).
+// All tiles of all workers in one launch, one workgroup per (tile, worker): the mixed tiles first
+// (the first n_mixed workgroups of every worker's row of the grid), then the whole tiles in
+// ascending order.  A whole tile goes through the steps of the persistent kernel without the
+// pipeline: the workgroup waits in place for its block's scale; the momentum tile is written at
+// once, the residual tile when the scale is there, so the tiles of a block write their residuals
+// in step.  The mixed tiles run the mixed-tile code and never wait for a whole tile (MIXED =
+// false: the layout has no such tile, and the code for them is left out).  Relies on workgroups
+// being dispatched in grid order (the mixed tiles' partial sums are posted before a block's last
+// whole tile looks for them; fuse_limit keeps a block's tiles well inside what is resident at
+// once) and on spin_limit where that fails.
+// Eight workgroups per CU (64 VGPRs, a few spilled): the one-pass limit is half of what is
+// resident, and 2048 resident workgroups let blocks of up to 1024 tiles (4 Mi elements) finish
+// in one pass (measured: 27.1 -> 24.4 ms on the transformer-like layout, no change elsewhere).
 template <bool MOM>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k_worker_uniform_direct(Layout L, ScratchRef R, WorkerArgs A)
+__device__ __forceinline__ void worker_mixed_tile(const Layout &L, const Scratch &X, const WorkerArgs &A, int32_t tile,
+                                                  int worker, int n_valid, TileShared &S)
 {
-    const Scratch X = open_call(R);
-    __shared__ SyncShared S;
-    const int32_t tile = L.uniform_tiles[blockIdx.x];
-    const int worker = blockIdx.y;
-    constexpr int n_valid = TILE;
     const int64_t tile_start = (int64_t)tile * TILE;
     const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
     float *m = MOM ? A.mom + (int64_t)worker * A.state_stride + tile_start : nullptr;
     float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
-    Posted P;
     float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
-    const LoadedCorrection corr = loaded_correction(L, tile, X, worker);
     load_tile(g, gv, n_valid);
     if (MOM) load_tile(m, mv, n_valid);
     load_tile(e, pv, n_valid);
-    correct_loaded_residual(pv, corr);
     worker_values<MOM>(gv, mv, pv, A.mu, A.r);
     if (MOM) store_tile(m, mv, n_valid);
+    compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride,
+                   A.scales + (int64_t)worker * A.scales_stride, e, X, worker, S);
+}
+
+template <bool MIXED>
+struct TilesShared {
+    typedef SyncShared type;
+};
+template <>
+struct TilesShared<true> {
+    typedef TileShared type;
+};
+
+template <bool MOM, bool MIXED>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void k_worker_tiles(Layout L, ScratchRef R, WorkerArgs A)
+{
+    const Scratch X = open_call(R);
+    __shared__ typename TilesShared<MIXED>::type S;
+    const bool whole = !MIXED || (int)blockIdx.x >= L.n_mixed;
+    const int32_t tile = whole ? L.uniform_tiles[blockIdx.x - (MIXED ? L.n_mixed : 0)] : L.mixed_tiles[blockIdx.x];
+    const int worker = blockIdx.y;
+    const int n_valid = whole ? TILE : tile_valid(L, tile);
+    const int64_t tile_start = (int64_t)tile * TILE;
+    const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
+    float *m = MOM ? A.mom + (int64_t)worker * A.state_stride + tile_start : nullptr;
+    float *e = A.err + (int64_t)worker * A.state_stride + tile_start;
     float *scales_out = A.scales + (int64_t)worker * A.scales_stride;
-    const int kind = compress_uniform(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride, scales_out, e, X, worker,
-                                      S, P, true);
-    resolve_posted(P, L, X, worker, scales_out, S);
-    if (kind == UNI_PENDING) {
-        finish_uniform(pv, tile, n_valid, L.tile_fb[tile], 0ull, e, L, X, worker, S);
-    } else if (kind == UNI_HELD) {
-        sync_group_wait(tile, L, X, worker, S);
-        store_tile(e, pv, n_valid);
+    uint64_t *signs = A.signs + (int64_t)worker * A.signs_stride;
+    float4 gv[SUBROWS], mv[SUBROWS], pv[SUBROWS];
+    if (whole) {
+        Posted P;
+        const LoadedCorrection corr = loaded_correction(L, tile, X, worker);
+        load_tile(g, gv, TILE);
+        if (MOM) load_tile(m, mv, TILE);
+        load_tile(e, pv, TILE);
+        correct_loaded_residual(pv, corr);
+        worker_values<MOM>(gv, mv, pv, A.mu, A.r);
+        if (MOM) store_tile(m, mv, TILE);
+        const int kind = compress_uniform(pv, L, tile, TILE, signs, scales_out, e, X, worker, S, P, true);
+        resolve_posted(P, L, X, worker, scales_out, S);
+        if (kind == UNI_PENDING) {
+            finish_uniform(pv, tile, TILE, L.tile_fb[tile], 0ull, e, L, X, worker, S);
+        } else if (kind == UNI_HELD) {
+            sync_group_wait(tile, L, X, worker, S);
+            store_tile(e, pv, TILE);
+        }
+    } else if constexpr (MIXED) {
+        worker_mixed_tile<MOM>(L, X, A, tile, worker, n_valid, S);
     }
 }
 
