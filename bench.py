@@ -5,14 +5,17 @@ One "step" = ef_worker_step for all M workers + ef_server_step + ef_apply over
 one batch of synthetic gradients that are already resident in HBM.  Prints ONE
 JSON line: throughput in Gelem/s counted as (M+1)*d elements through a
 compressor per step, the HBM roofline of the dominant kernel (measured with
-HIP events on the launch stream), and the CPU oracle timed on a bounded sample
-of the same workload on this host.
+HIP events on the launch stream), the other benchmark configurations timed the
+same way (`other_workloads`), and the CPU oracle timed on a bounded sample of
+the headline workload on this host.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 """
 import argparse
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -27,22 +30,38 @@ import paper_1905_10936_amd as ef  # noqa: E402
 from paper_1905_10936_amd import bench_probe  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
+TILE = 4096                     # elements a workgroup takes at a time (only used to name the dominant kernel's share)
 
-# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
-# (FETCH_SIZE, then WRITE_SIZE, scaled by a torch add kernel of known size run
-# in the same process): see profiles/ef_step_flat_2p28.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {("flat_2p28", "direct"): 43318642898,        # ef::k_worker_uniform_direct<true>
-                          ("flat_2p28", "persistent"): 43296770554}    # ef::k_worker_uniform<true>
+# The benchmark configurations besides the headline one, timed after it (`other_workloads`).
+OTHER_WORKLOADS = ("resnet20_like", "resnet50_like", "skewed_blocks", "transformer_like")
 
 
 def algorithmic_bytes(d, B, M, variant="sgdm"):
-    """Bytes the method itself must move per element of d (fp32 state read
-    once and written once, sign bits, scales)."""
+    """Bytes the method itself must move per step (fp32 state read once and
+    written once, sign bits, scales): worker call, server call, apply call."""
     state = 12.0 if variant == "sgd" else 20.0              # g,e in, e out (+ m in, m out with momentum)
     worker = M * (state * d + d / 8.0 + 4.0 * B)            # + signs, scales
     server = 8.0 * d + (M + 1) * d / 8.0 + 4.0 * B * (M + 1)
     apply_ = (16.0 if variant == "wd" else 8.0) * d + d / 8.0 + 4.0 * B   # x (+ decay momentum) in and out
     return worker, server, apply_
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from rocprofv3's FETCH_SIZE / WRITE_SIZE
+    counters, as recorded in a summary under profiles/ (a line `traffic-json: {...}` written by
+    bench_profile.py; each record names the commit it was measured at).  None if no summary has a
+    record for this kernel on this workload: the figure is never a constant of this file."""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for m in re.finditer(r"traffic-json:\s*(\{.*\})", open(path).read()):
+            try:
+                rec = json.loads(m.group(1))
+            except ValueError:
+                continue
+            if rec.get("workload") == workload and kernel in rec.get("kernels", {}):
+                k = rec["kernels"][kernel]
+                return {"bytes_per_launch": k["traffic_bytes"], "ratio_to_algorithmic": k.get("ratio"),
+                        "measured_at_commit": rec.get("commit"), "summary": os.path.relpath(path, ROOT)}
+    return None
 
 
 def cpu_baseline(w, grads0, n_blocks, steps):
@@ -65,6 +84,141 @@ def cpu_baseline(w, grads0, n_blocks, steps):
     return (M + 1) * ds / dt / 1e9, ds, first
 
 
+class Run:
+    """Device state of one workload and the step over it."""
+
+    def __init__(self, w, variant, n_sets, dev):
+        self.w, self.variant, self.dev = w, variant, dev
+        d, B, M = w.d, w.B, w.M
+        W = (d + 63) // 64
+        self.plan = ef.ef_plan_create(w.offsets, M)
+        self.n_sets = n_sets
+        ds = (d + 3) // 4 * 4           # row stride in elements: the ABI wants a multiple of 4
+        self.ds = ds
+        self.grads = torch.zeros((n_sets, M, ds), dtype=torch.float32, device=dev)
+        for s in range(n_sets):
+            for i in range(M):
+                w.grad(s, i, device=dev, out=self.grads[s, i, :d])
+        self.mom = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+        self.err = torch.zeros((M, ds), dtype=torch.float32, device=dev)
+        self.te = torch.zeros(d, dtype=torch.float32, device=dev)
+        self.x = torch.zeros(d, dtype=torch.float32, device=dev)
+        self.ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
+        self.wc = torch.zeros((M, B), dtype=torch.float32, device=dev)
+        self.ss = torch.zeros(W, dtype=torch.int64, device=dev)
+        self.sc = torch.zeros(B, dtype=torch.float32, device=dev)
+        if variant == "fused":
+            pb = ef.ef_payload_bytes(self.plan)
+            self.wmsg = torch.zeros((M, pb), dtype=torch.uint8, device=dev)
+            self.smsg = torch.zeros(pb, dtype=torch.uint8, device=dev)
+        if variant == "wd":
+            self.decay_mom = torch.zeros(d, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        self.stream = torch.cuda.current_stream()
+        self.eta_prev, self.t = 0.0, 0
+
+    def step(self, ev=None):
+        w, plan, variant, M = self.w, self.plan, self.variant, self.w.M
+        g = self.grads[self.t % self.n_sets]
+        if ev:
+            ev[0].record(self.stream)
+        if variant == "fused":
+            ef.ef_worker_step_fused(plan, g, self.mom, self.err, w.mu, self.eta_prev, w.eta, self.wmsg)
+        elif variant == "sgd":
+            ef.ef_worker_step_sgd(plan, g, self.err, self.eta_prev, w.eta, self.ws, self.wc)
+        else:
+            ef.ef_worker_step(plan, g, self.mom, self.err, w.mu, self.eta_prev, w.eta, self.ws, self.wc)
+        if ev:
+            ev[1].record(self.stream)
+        if variant == "fused":
+            ef.ef_server_step_fused(plan, M, self.wmsg, self.te, self.eta_prev, w.eta, self.smsg)
+        else:
+            ef.ef_server_step(plan, M, self.ws, self.wc, self.te, self.eta_prev, w.eta, self.ss, self.sc)
+        if ev:
+            ev[2].record(self.stream)
+        if variant == "fused":
+            ef.ef_apply_fused(plan, self.x, self.smsg, w.eta)
+        elif variant == "wd":
+            ef.ef_apply_wd(plan, self.x, self.decay_mom, self.ss, self.sc, w.eta, w.mu, 5e-4)
+        else:
+            ef.ef_apply(plan, self.x, self.ss, self.sc, w.eta)
+        if ev:
+            ev[3].record(self.stream)
+        self.eta_prev = w.eta
+        self.t += 1
+
+    def timed(self, steps, warmup, first_payload=False):
+        """`warmup` untimed steps, then exactly `steps` timed ones.  Returns (ms per step by the host
+        clock around the synchronised region, mean ms of the three calls by HIP events, first payload)."""
+        payload = None
+        for k in range(warmup):
+            self.step()
+            if k == 0 and first_payload:
+                torch.cuda.synchronize()
+                payload = (self.ws.cpu().numpy().view(np.uint64).copy(), self.ss.cpu().numpy().view(np.uint64).copy())
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            self.step(events[k])
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        calls = [float(np.mean([e[q].elapsed_time(e[q + 1]) for e in events])) for q in range(3)]
+        return ms, calls, payload
+
+    def worker_kernel(self):
+        w = self.w
+        mixed = bool(np.any(w.offsets[1:] % TILE != 0))
+        mom = "false" if self.variant == "sgd" else "true"
+        if self.plan.persistent and self.variant != "sgd":
+            return "ef::k_worker_uniform<%s>" % mom
+        return "ef::k_worker_tiles<%s, %s>" % (mom, "true" if mixed else "false")
+
+    def close(self):
+        self.plan.close()
+
+
+def summary_of(run, ms, calls, variant):
+    """Figures of one timed run that the headline and the other workloads share."""
+    w = run.w
+    d, B, M = w.d, w.B, w.M
+    bw, bs, ba = algorithmic_bytes(d, B, M, variant)
+    t_worker, t_server, t_apply = calls
+    return {
+        "ms_per_step": round(ms, 4),
+        "value": round((M + 1) * d / (ms * 1e-3) / 1e9, 3), "unit": "Gelem/s",
+        "per_call_ms": {"ef_worker_step": round(t_worker, 4), "ef_server_step": round(t_server, 4),
+                        "ef_apply": round(t_apply, 4)},
+        "step_hbm_frac_algorithmic": round((bw + bs + ba) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "per_call_hbm_frac": {"ef_worker_step": round(bw / (t_worker * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                              "ef_server_step": round(bs / (t_server * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                              "ef_apply": round(ba / (t_apply * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "dominant_kernel": run.worker_kernel(),
+    }
+
+
+def other_workload(name, dev, steps, warmup):
+    """One of the other benchmark configurations: default plan settings, eager calls, one gradient
+    set resident, timed like the headline run (a few steps; the headline figure is not affected)."""
+    w = wl.get(name)
+    run = Run(w, "sgdm", 1, dev)
+    ms, calls, _ = run.timed(steps, warmup)
+    out = dict(summary_of(run, ms, calls, "sgdm"), d=w.d, B=w.B, M=w.M, steps=steps, warmup=warmup,
+               worker_fuse_limit_tiles=run.plan.fuse_limit)
+    run.plan.set_lazy(True)
+    ms2, calls2, _ = run.timed(steps, max(warmup, 1))
+    ef.ef_flush(run.plan, run.err, run.te)
+    torch.cuda.synchronize()
+    out["deferred_correction_mode"] = {"ms_per_step": round(ms2, 4),
+                                       "per_call_ms": {"ef_worker_step": round(calls2[0], 4),
+                                                       "ef_server_step": round(calls2[1], 4),
+                                                       "ef_apply": round(calls2[2], 4)}}
+    run.close()
+    del run
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +228,7 @@ def main():
     ap.add_argument("--grad-sets", type=int, default=0, help="distinct gradient sets kept in HBM (0 = auto)")
     ap.add_argument("--cpu-blocks", type=int, default=0, help="blocks in the CPU oracle sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-others", action="store_true", help="skip the other benchmark configurations")
     ap.add_argument("--fuse-limit", type=int, default=-1, help="override the plan's one-pass block limit")
     ap.add_argument("--spin-limit", type=int, default=-1, help="override the plan's wait budget")
     ap.add_argument("--persistent", type=int, default=-1, help="1/0: force the persistent worker kernel on/off")
@@ -103,70 +258,17 @@ def main():
     torch.cuda.set_device(dev)
     w = wl.get(args.workload)
     d, B, M = w.d, w.B, w.M
-    W = (d + 63) // 64
-    plan = ef.ef_plan_create(w.offsets, M)
+    variant = args.variant
+    # gradient sets resident in HBM, cycled over the steps
+    n_sets = args.grad_sets or max(1, min(args.steps + args.warmup, int(64e9 // (4.0 * d * M)), 4))
+    run = Run(w, variant, n_sets, dev)
+    plan = run.plan
     if args.fuse_limit >= 0 or args.spin_limit >= 0:
         plan.tune(args.fuse_limit, args.spin_limit)
     if args.persistent >= 0:
         plan.set_persistent(args.persistent)
     if args.lazy:
         plan.set_lazy(True)
-
-    # gradient sets resident in HBM, cycled over the steps
-    n_sets = args.grad_sets or max(1, min(args.steps + args.warmup, int(64e9 // (4.0 * d * M)), 4))
-    ds = (d + 3) // 4 * 4           # row stride in elements: the ABI wants a multiple of 4
-    grads = torch.zeros((n_sets, M, ds), dtype=torch.float32, device=dev)
-    for s in range(n_sets):
-        for i in range(M):
-            w.grad(s, i, device=dev, out=grads[s, i, :d])
-    mom = torch.zeros((M, ds), dtype=torch.float32, device=dev)
-    err = torch.zeros((M, ds), dtype=torch.float32, device=dev)
-    te = torch.zeros(d, dtype=torch.float32, device=dev)
-    x = torch.zeros(d, dtype=torch.float32, device=dev)
-    ws = torch.zeros((M, W), dtype=torch.int64, device=dev)
-    wc = torch.zeros((M, B), dtype=torch.float32, device=dev)
-    ss = torch.zeros(W, dtype=torch.int64, device=dev)
-    sc = torch.zeros(B, dtype=torch.float32, device=dev)
-    variant = args.variant
-    if variant == "fused":
-        pb = ef.ef_payload_bytes(plan)
-        wmsg = torch.zeros((M, pb), dtype=torch.uint8, device=dev)
-        smsg = torch.zeros(pb, dtype=torch.uint8, device=dev)
-    if variant == "wd":
-        decay_mom = torch.zeros(d, dtype=torch.float32, device=dev)
-    torch.cuda.synchronize()
-
-    stream = torch.cuda.current_stream()
-    state = {"eta_prev": 0.0, "t": 0}
-
-    def step(ev=None):
-        g = grads[state["t"] % n_sets]
-        if ev:
-            ev[0].record(stream)
-        if variant == "fused":
-            ef.ef_worker_step_fused(plan, g, mom, err, w.mu, state["eta_prev"], w.eta, wmsg)
-        elif variant == "sgd":
-            ef.ef_worker_step_sgd(plan, g, err, state["eta_prev"], w.eta, ws, wc)
-        else:
-            ef.ef_worker_step(plan, g, mom, err, w.mu, state["eta_prev"], w.eta, ws, wc)
-        if ev:
-            ev[1].record(stream)
-        if variant == "fused":
-            ef.ef_server_step_fused(plan, M, wmsg, te, state["eta_prev"], w.eta, smsg)
-        else:
-            ef.ef_server_step(plan, M, ws, wc, te, state["eta_prev"], w.eta, ss, sc)
-        if ev:
-            ev[2].record(stream)
-        if variant == "fused":
-            ef.ef_apply_fused(plan, x, smsg, w.eta)
-        elif variant == "wd":
-            ef.ef_apply_wd(plan, x, decay_mom, ss, sc, w.eta, w.mu, 5e-4)
-        else:
-            ef.ef_apply(plan, x, ss, sc, w.eta)
-        if ev:
-            ev[3].record(stream)
-        state["eta_prev"] = w.eta
-        state["t"] += 1
 
     if args.calib:
         # known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE: reads 2^28 floats, writes 2^28 floats
@@ -177,29 +279,16 @@ def main():
         torch.cuda.synchronize()
         del ca, cb
 
-    first_payload = None
-    for k in range(args.warmup):
-        step()
-        if k == 0:
-            torch.cuda.synchronize()
-            if variant in ("sgdm", "wd"):
-                first_payload = (ws.cpu().numpy().view(np.uint64).copy(), ss.cpu().numpy().view(np.uint64).copy())
-    torch.cuda.synchronize()
-
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
     if args.graph:
         # per-call breakdown from an eager pass, then the timed region replays captured graphs
-        for k in range(args.steps):
-            step(events[k])
-        torch.cuda.synchronize()
+        _, calls, first_payload = run.timed(args.steps, args.warmup, first_payload=variant in ("sgdm", "wd"))
         side = torch.cuda.Stream()
         graphs = []
         for s_ in range(n_sets):
-            state["t"] = s_
+            run.t = s_
             gr = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gr, stream=side):
-                step()
+                run.step()
             graphs.append(gr)
         torch.cuda.synchronize()
         for k in range(max(args.warmup, 1)):
@@ -209,53 +298,36 @@ def main():
         for k in range(args.steps):
             graphs[k % n_sets].replay()
         torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     else:
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            step(events[k])
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
+        ms_per_step, calls, first_payload = run.timed(args.steps, args.warmup, first_payload=variant in ("sgdm", "wd"))
 
     fuse_limit_used = plan.fuse_limit
     # untimed diagnostic: one more worker and server call, asking each how many tiles left the one-pass route
-    g = grads[state["t"] % n_sets]
-    ef.ef_worker_step(plan, g, mom, err, w.mu, w.eta, w.eta, ws, wc)
+    g = run.grads[run.t % n_sets]
+    ef.ef_worker_step(plan, g, run.mom, run.err, w.mu, w.eta, w.eta, run.ws, run.wc)
     fb_worker = plan.last_fallbacks()
-    ef.ef_server_step(plan, M, ws, wc, te, w.eta, w.eta, ss, sc)
+    ef.ef_server_step(plan, M, run.ws, run.wc, run.te, w.eta, w.eta, run.ss, run.sc)
     fb_server = plan.last_fallbacks()
 
-    t_worker = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    t_server = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
-    t_apply = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
-    bw, bs, ba = algorithmic_bytes(d, B, M, variant)
-    step_bytes = bw + bs + ba
+    head = summary_of(run, ms_per_step, calls, variant)
+    t_worker = calls[0]
+    bw, _, _ = algorithmic_bytes(d, B, M, variant)
     achieved = bw / (t_worker * 1e-3) / 1e9
 
     # beside the headline (not part of `value`): the same steps with the deferred residual correction on
     deferred = None
     if not args.lazy and not args.graph and not args.no_deferred:
         plan.set_lazy(True)
-        for k in range(max(args.warmup, 1)):
-            step()
-        ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            step(ev2[k])
-        torch.cuda.synchronize()
-        ms2 = (time.perf_counter() - t0) * 1e3 / args.steps
-        ef.ef_flush(plan, err, te)
+        ms2, calls2, _ = run.timed(args.steps, max(args.warmup, 1))
+        ef.ef_flush(plan, run.err, run.te)
         torch.cuda.synchronize()
         plan.set_lazy(False)
-        tw2 = float(np.mean([e[0].elapsed_time(e[1]) for e in ev2]))
         deferred = {
             "ms_per_step": round(ms2, 4), "value": round((M + 1) * d / (ms2 * 1e-3) / 1e9, 3), "unit": "Gelem/s",
-            "per_call_ms": {"ef_worker_step": round(tw2, 4),
-                            "ef_server_step": round(float(np.mean([e[1].elapsed_time(e[2]) for e in ev2])), 4),
-                            "ef_apply": round(float(np.mean([e[2].elapsed_time(e[3]) for e in ev2])), 4)},
-            "worker_hbm_frac": round(bw / (tw2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "per_call_ms": {"ef_worker_step": round(calls2[0], 4), "ef_server_step": round(calls2[1], 4),
+                            "ef_apply": round(calls2[2], 4)},
+            "worker_hbm_frac": round(bw / (calls2[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "what": "ef_plan_set_lazy(1): e <- p - Delta of blocks beyond the one-pass limit is formed when the next "
                     "call loads the buffer (same bits), so no workgroup waits for a scale; same steps, same inputs, "
                     "timed after the headline run"}
@@ -263,43 +335,46 @@ def main():
     # untimed: the practical ceiling of the worker's access pattern on this machine (a bare stream of
     # the same reads and writes over the same buffers; the state is not needed any more)
     ceiling = ceiling_ticketed = ceiling_grouped = None
-    if variant != "sgd" and M * ds >= 4096:
+    if variant != "sgd" and M * run.ds >= 4096:
         torch.cuda.synchronize()
-        p_ms, p_bytes = bench_probe.ef_stream_probe(grads[0].view(-1), mom.view(-1), err.view(-1), repeats=3)
+        bufs = (run.grads[0].view(-1), run.mom.view(-1), run.err.view(-1))
+        p_ms, p_bytes = bench_probe.ef_stream_probe(*bufs, repeats=3)
         ceiling_ticketed = p_bytes / (p_ms * 1e-3) / 1e9
-        p_ms, p_bytes = bench_probe.ef_stream_probe_grouped(grads[0].view(-1), mom.view(-1), err.view(-1), group=16, repeats=3)
+        p_ms, p_bytes = bench_probe.ef_stream_probe_grouped(*bufs, group=16, repeats=3)
         ceiling_grouped = p_bytes / (p_ms * 1e-3) / 1e9
         ceiling = max(ceiling_ticketed, ceiling_grouped)
 
-    value = (M + 1) * d / (ms_per_step * 1e-3) / 1e9
+    kernel = head["dominant_kernel"]
     out = {
         "metric": "EF-compress step Gelem/s (worker+server, M workers) and % of HBM roofline",
-        "value": round(value, 3),
+        "value": head["value"],
         "unit": "Gelem/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": dict(w.describe(), variant=variant, launch="hip graph replay" if args.graph else "eager calls",
+        "config": dict({k: v for k, v in w.describe().items() if k != "steps"},
+                       steps_of_the_configuration=w.steps, variant=variant,
+                       launch="hip graph replay" if args.graph else "eager calls",
                        deferred_residual_correction=bool(plan.lazy),
                        grad_sets_in_hbm=n_sets, elements_counted="(M+1)*d per step",
                        d_per_step_Gelem_s=round(d / (ms_per_step * 1e-3) / 1e9, 3)),
         "roofline": {
             "bound": "hbm",
-            "kernel": ("ef::k_worker_uniform<true> (persistent)" if plan.persistent else "ef::k_worker_uniform_direct<true>") +
-                      ", all M workers in one launch; timed as the whole ef_worker_step call (its mixed-tile and "
-                      "list kernels included)",
+            "kernel": kernel + ", all M workers in one launch; timed as the whole ef_worker_step call (the short "
+                               "kernel that ends the call included)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "persistent" if plan.persistent else "direct"))
+            "traffic": (measured_traffic(args.workload, kernel) or {}).get("bytes_per_launch")
             if variant == "sgdm" and not plan.lazy else None,
+            "traffic_source": measured_traffic(args.workload, kernel) if variant == "sgdm" and not plan.lazy else None,
             "algorithmic_bytes_per_launch": bw,
             "ms_per_launch": round(t_worker, 4),
             "practical_ceiling": None if ceiling is None else {
@@ -312,35 +387,44 @@ def main():
                         "synchronised) and ef_stream_probe_grouped (one workgroup per tile, the third array written "
                         "in step by groups of 16 tiles, as the worker kernel writes its residual)"},
         },
-        "per_call_ms": {"ef_worker_step": round(t_worker, 4), "ef_server_step": round(t_server, 4),
-                        "ef_apply": round(t_apply, 4)},
-        "step_hbm_frac_algorithmic": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "per_call_ms": head["per_call_ms"],
+        "per_call_hbm_frac": head["per_call_hbm_frac"],
+        "step_hbm_frac_algorithmic": head["step_hbm_frac_algorithmic"],
         "worker_fuse_limit_tiles": fuse_limit_used,
         "deferred_correction_mode": deferred,
         "run_time_fallbacks": {"worker_parked_tiles": fb_worker[0], "worker_late_blocks": fb_worker[1],
                                "server_parked_tiles": fb_server[0], "server_late_blocks": fb_server[1]},
     }
 
+    cpu = None
     if not args.no_cpu and variant in ("sgdm", "wd"):
         # bounded sample: a prefix of blocks sized for roughly 10-30 s of single-thread work
         avg_block = d / B
         n_blocks = args.cpu_blocks or int(max(1, min(B, round(5e7 / avg_block))))
         cpu_steps = 2
-        g0 = grads[0]
-        cpu_val, ds, first = cpu_baseline(w, g0, n_blocks, cpu_steps)
+        cpu_val, ds, first = cpu_baseline(w, run.grads[0], n_blocks, cpu_steps)
         # the oracle's first step on the sample must reproduce the GPU's first payload there
         check = None
         if first_payload is not None and args.warmup >= 1:
             nw = ds // 64
             check = bool(np.array_equal(first[0][:, :nw], first_payload[0][:, :nw]) and
                          np.array_equal(first[2][:nw], first_payload[1][:nw]))
-        out["cpu_baseline"] = {
+        cpu = {
             "value": round(cpu_val, 4), "unit": "Gelem/s", "cores": 1, "kind": "oracle",
             "sample": "first %d blocks (%d elements) of the same workload, all M=%d workers + server + apply, "
                       "%d steps after one warm-up, single thread; host has %d logical cores"
                       % (n_blocks, ds, M, cpu_steps, os.cpu_count()),
             "first_step_signs_match_gpu": check,
         }
+
+    # the other benchmark configurations, after the headline run has given its memory back
+    run.close()
+    del run, plan, g
+    torch.cuda.empty_cache()
+    if not args.no_others and variant == "sgdm" and not args.lazy and not args.graph and args.workload == "flat_2p28":
+        out["other_workloads"] = {name: other_workload(name, dev, 5, 2) for name in OTHER_WORKLOADS}
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 
