@@ -278,6 +278,25 @@ int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t 
                           void *stream);
 
 /*
+ * ef_worker_step that also reports how well the compressor approximated what
+ * it was given: exactly ef_worker_step (same arguments, same results, bit for
+ * bit), plus quality[2i] = phi(p_i) and quality[2i+1] = delta(p_i) of worker
+ * i's corrected gradient p_i (Proposition 1 bounds the step's compression
+ * error by (1 - phi(p)) ||p||^2).  The sums of |p| and p^2 are taken inside
+ * the worker kernel on the values it holds anyway, so no tensor is read a
+ * second time; the figures are those ef_compressor_quality would give on p_i
+ * (fp64, fixed order).  The call always runs the worker kernel that takes one
+ * workgroup per tile.  In the deferred mode it follows the same rules as
+ * ef_worker_step.
+ *
+ *   quality   out  double[2 * n_workers], device memory, 8-byte aligned
+ */
+int ef_worker_step_quality(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride,
+                           float *mom, float *err, int64_t state_stride, float mu, float eta_prev,
+                           float eta, uint64_t *packed_signs, float *scales, double *quality,
+                           void *stream);
+
+/*
  * ef_compressor_quality for callers that cannot allocate: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  The same
  * kernels and the same results, bit for bit, but the per-tile sums go to a

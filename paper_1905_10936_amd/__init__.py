@@ -28,7 +28,7 @@ ABI_SYMBOLS = (
     "ef_worker_step", "ef_server_step", "ef_apply", "ef_strerror",
     "ef_worker_step_sgd", "ef_apply_wd",
     "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused",
-    "ef_compressor_quality", "ef_compressor_quality_static",
+    "ef_compressor_quality", "ef_compressor_quality_static", "ef_worker_step_quality",
     "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_flush",
 )
 # ... and what include/ef_debug.h declares (tuning and diagnostics the tests use)
@@ -88,6 +88,8 @@ def lib():
     L.ef_plan_fuse_limit.argtypes = [vp]
     L.ef_worker_step.restype = c_int
     L.ef_worker_step.argtypes = [vp, c_int, vp, i64, vp, vp, i64, f32, f32, f32, vp, vp, vp]
+    L.ef_worker_step_quality.restype = c_int
+    L.ef_worker_step_quality.argtypes = [vp, c_int, vp, i64, vp, vp, i64, f32, f32, f32, vp, vp, vp, vp]
     L.ef_worker_step_sgd.restype = c_int
     L.ef_worker_step_sgd.argtypes = [vp, c_int, vp, i64, vp, i64, f32, f32, vp, vp, vp]
     L.ef_server_step.restype = c_int
@@ -252,6 +254,24 @@ def ef_worker_step(plan, grad, mom, err, mu, eta_prev, eta, packed_signs, scales
                               float(mu), float(eta_prev), float(eta),
                               _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
                               _ptr(scales, torch.float32, "scales"), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_worker_step_quality(plan, grad, mom, err, mu, eta_prev, eta, packed_signs, scales, quality, stream=None):
+    """ef_worker_step that also writes (phi(p_i), delta(p_i)) of every worker's corrected gradient
+    into quality: float64 [n][2]."""
+    n = 1 if grad.dim() == 1 else grad.shape[0]
+    gs, ss = _stride(grad, plan.d, "grad"), _stride(mom, plan.d, "mom")
+    if _stride(err, plan.d, "err") != ss or mom.shape != err.shape:
+        raise TypeError("mom and err must share shape and stride")
+    if packed_signs.numel() != n * plan.W or scales.numel() != n * plan.B or quality.numel() != 2 * n:
+        raise TypeError("packed_signs must hold n*W words, scales n*B floats, quality 2*n doubles")
+    rc = lib().ef_worker_step_quality(plan._h, n, _ptr(grad, torch.float32, "grad"), gs,
+                                      _ptr(mom, torch.float32, "mom"), _ptr(err, torch.float32, "err"), ss,
+                                      float(mu), float(eta_prev), float(eta),
+                                      _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                                      _ptr(scales, torch.float32, "scales"), _ptr(quality, torch.float64, "quality"),
+                                      _stream_ptr(stream))
     _check(rc)
 
 

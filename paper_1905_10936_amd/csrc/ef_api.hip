@@ -375,7 +375,7 @@ int build_device(ef_plan *p)
         // run one workgroup per tile (dispatched in grid order).  Larger limits were measured slower:
         // a block that fills most of the machine makes its first tiles wait for its last.
         int occ_d = 0;
-        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, (ef::k_worker_tiles<true, true>), ef::THREADS, 0));
+        EF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_d, (ef::k_worker_tiles<true, true, false>), ef::THREADS, 0));
         p->lim_persistent = (int32_t)((int64_t)p->worker_grid * (ef::PIPE_DEPTH + ef::STAGE_DEPTH) / 2);
         p->lim_direct = (int32_t)((int64_t)prop.multiProcessorCount * occ_d / 2);
         p->lim_server = (int32_t)((int64_t)prop.multiProcessorCount * occ_s / 2);
@@ -515,7 +515,7 @@ size_t payload_bytes(const ef_plan *plan)
 
 int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
                      float *err, int64_t state_stride, float mu, float eta_prev, float eta, uint64_t *packed_signs,
-                     int64_t signs_stride, float *scales, int64_t scales_stride, void *stream);
+                     int64_t signs_stride, float *scales, int64_t scales_stride, void *stream, double *quality = nullptr);
 int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, int64_t in_signs_stride,
                      const float *scales, int64_t in_scales_stride, float *server_err, float eta_prev, float eta,
                      uint64_t *out_signs, float *out_scales, void *stream);
@@ -728,6 +728,15 @@ int ef_worker_step(const ef_plan *plan, int n_workers, const float *grad, int64_
                             packed_signs, plan->L.W, scales, plan->L.B, stream);
 }
 
+int ef_worker_step_quality(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
+                           float *err, int64_t state_stride, float mu, float eta_prev, float eta,
+                           uint64_t *packed_signs, float *scales, double *quality, void *stream)
+{
+    if (!plan || !mom || !quality) return EF_ERR_NULL;
+    return worker_step_impl(plan, n_workers, grad, grad_stride, mom, err, state_stride, mu, eta_prev, eta,
+                            packed_signs, plan->L.W, scales, plan->L.B, stream, quality);
+}
+
 int ef_worker_step_sgd(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *err,
                        int64_t state_stride, float eta_prev, float eta, uint64_t *packed_signs, float *scales,
                        void *stream)
@@ -785,7 +794,7 @@ namespace {
 
 int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int64_t grad_stride, float *mom,
                      float *err, int64_t state_stride, float mu, float eta_prev, float eta, uint64_t *packed_signs,
-                     int64_t signs_stride, float *scales, int64_t scales_stride, void *stream)
+                     int64_t signs_stride, float *scales, int64_t scales_stride, void *stream, double *quality)
 {
     // mom == nullptr selects Algorithm 3 (callers of the momentum entry points have checked theirs)
     const bool has_mom = mom != nullptr;
@@ -833,8 +842,13 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
         if (n_workers > plan->lazy_sets_seen) plan->lazy_sets_seen = n_workers;
     }
     const CallScratch c = next_call(plan, 0, n_workers);
-    const int role = worker_role(plan, has_mom);
+    const int role = quality ? (int)ROLE_TILES : worker_role(plan, has_mom);
     const ef::Layout L = role_layout(plan, role);
+    if (quality) {
+        if (!aligned(quality, 8)) return EF_ERR_ALIGN;
+        hipLaunchKernelGGL(ef::k_quality_init, dim3(1), dim3(ef::THREADS), 0, s, quality, n_workers);
+        EF_HIP(hipGetLastError());
+    }
     if (role == ROLE_TICKET) {
         // the mixed tiles first, in a kernel of their own, then the persistent kernel
         if (plan->L.n_mixed) {
@@ -857,17 +871,39 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
         // every tile in one launch, the mixed tiles first
         const dim3 grid((unsigned)plan->L.ntiles, (unsigned)n_workers), block(ef::THREADS);
         const bool mixed = plan->L.n_mixed != 0;
-        if (has_mom && mixed)
-            hipLaunchKernelGGL((ef::k_worker_tiles<true, true>), grid, block, 0, s, L, c.X, A);
+        ef::QualityArgs Q;
+        Q.v = nullptr;
+        Q.stride = 0;
+        Q.tile_sums = plan->d_qtile;
+        Q.part_sums = plan->d_qpart;
+        Q.out = quality;
+        if (quality && has_mom)
+            hipLaunchKernelGGL((ef::k_worker_tiles<true, true, true>), grid, block, 0, s, L, c.X, A, Q);
+        else if (quality)
+            hipLaunchKernelGGL((ef::k_worker_tiles<false, true, true>), grid, block, 0, s, L, c.X, A, Q);
+        else if (has_mom && mixed)
+            hipLaunchKernelGGL((ef::k_worker_tiles<true, true, false>), grid, block, 0, s, L, c.X, A, Q);
         else if (has_mom)
-            hipLaunchKernelGGL((ef::k_worker_tiles<true, false>), grid, block, 0, s, L, c.X, A);
+            hipLaunchKernelGGL((ef::k_worker_tiles<true, false, false>), grid, block, 0, s, L, c.X, A, Q);
         else if (mixed)
-            hipLaunchKernelGGL((ef::k_worker_tiles<false, true>), grid, block, 0, s, L, c.X, A);
+            hipLaunchKernelGGL((ef::k_worker_tiles<false, true, false>), grid, block, 0, s, L, c.X, A, Q);
         else
-            hipLaunchKernelGGL((ef::k_worker_tiles<false, false>), grid, block, 0, s, L, c.X, A);
+            hipLaunchKernelGGL((ef::k_worker_tiles<false, false, false>), grid, block, 0, s, L, c.X, A, Q);
         EF_HIP(hipGetLastError());
     }
-    return launch_tail(plan, role, c, n_workers, err, state_stride, scales, scales_stride, s);
+    int rc = launch_tail(plan, role, c, n_workers, err, state_stride, scales, scales_stride, s);
+    if (rc || !quality) return rc;
+    // the quality sums of the tiles are there: combine them per block and per vector
+    ef::QualityArgs Q;
+    Q.v = nullptr;
+    Q.stride = 0;
+    Q.tile_sums = plan->d_qtile;
+    Q.part_sums = plan->d_qpart;
+    Q.out = quality;
+    hipLaunchKernelGGL(ef::k_quality_blocks, dim3((unsigned)plan->n_cross + 1u, (unsigned)n_workers), dim3(ef::THREADS), 0,
+                       s, plan->L, Q, (const int32_t *)plan->d_cross, (int)plan->n_cross);
+    EF_HIP(hipGetLastError());
+    return EF_OK;
 }
 
 int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, int64_t in_signs_stride,

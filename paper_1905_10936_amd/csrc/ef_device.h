@@ -4,7 +4,7 @@
 // compressor-quality diagnostics (ef_quality.h).
 #pragma once
 #include "ef_tile.h"
+#include "ef_quality.h"
 #include "ef_worker.h"
 #include "ef_server.h"
 #include "ef_finish.h"
-#include "ef_quality.h"

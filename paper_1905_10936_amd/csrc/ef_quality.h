@@ -9,7 +9,8 @@ namespace ef {
 // phi(v) = min_b ||v_Gb||_1^2 / (d_b ||v_Gb||_2^2) (Proposition 1) and
 // delta(v) = ||v||_1^2 / (d ||v||_2^2) (non-block compressor, Eq. (1)), in
 // fp64.  Three small kernels: out[2i] = 1 (the ratio of an all-zero block,
-// which the compressor reproduces exactly); per tile the sums of |v| and v^2
+// which the compressor reproduces exactly); per tile (a pass of its own over v, or
+// inside the worker kernel on the p it has in registers anyway) the sums of |v| and v^2
 // of the tile and of its open segments, and the ratios of the segments that
 // close inside the tile; per crossing block the sums of its tiles' partials in
 // a fixed order.  The minimum is taken with an integer atomic on the bits of
@@ -39,18 +40,17 @@ __global__ __launch_bounds__(THREADS) void k_quality_init(double *out, int n)
     }
 }
 
-__global__ __launch_bounds__(THREADS) void k_quality_tiles(Layout L, QualityArgs Q)
+// The share of one tile of vector `vec` in phi and delta: a holds the tile's values (any sign; past
+// the end of the vector 0).  Called by every thread of the workgroup; uses S.red, and for a tile
+// where several blocks meet S.val and S.long_list as well (free again on return).
+__device__ __forceinline__ void quality_of_tile(float4 (&a)[SUBROWS], const Layout &L, const QualityArgs &Q, int32_t tile,
+                                                int vec, int n_valid, TileShared &S)
 {
-    __shared__ TileShared S;
     __shared__ double seg_sum[2][2];            // [head, tail][l1, l2] of the open segments
-    const int32_t tile = blockIdx.x;
-    const int vec = blockIdx.y;
-    const int n_valid = tile_valid(L, tile);
+    __shared__ unsigned long long tile_min;
     const int64_t tile_start = (int64_t)tile * TILE;
     const int32_t fb = L.tile_fb[tile], lb = L.tile_lb[tile];
     unsigned long long *phi_bits = reinterpret_cast<unsigned long long *>(Q.out + 2 * (int64_t)vec);
-    float4 a[SUBROWS];
-    load_tile(Q.v + (int64_t)vec * Q.stride + tile_start, a, n_valid);     // elements past d read as 0
     double l1 = 0.0, l2 = 0.0;
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) {
@@ -81,7 +81,6 @@ __global__ __launch_bounds__(THREADS) void k_quality_tiles(Layout L, QualityArgs
     }
     // several blocks meet in this tile: segmented sums through LDS; the smallest ratio of the
     // segments that close here is collected in LDS first, one global atomic per tile
-    __shared__ unsigned long long tile_min;
 #pragma unroll
     for (int k = 0; k < SUBROWS; ++k) *reinterpret_cast<float4 *>(&S.val[local_base(k)]) = a[k];
     if (threadIdx.x == 0) {
@@ -153,6 +152,18 @@ __global__ __launch_bounds__(THREADS) void k_quality_tiles(Layout L, QualityArgs
             ps[3] = seg_sum[1][1];
         }
     }
+    __syncthreads();            // S.val and seg_sum are free again
+}
+
+__global__ __launch_bounds__(THREADS) void k_quality_tiles(Layout L, QualityArgs Q)
+{
+    __shared__ TileShared S;
+    const int32_t tile = blockIdx.x;
+    const int vec = blockIdx.y;
+    const int n_valid = tile_valid(L, tile);
+    float4 a[SUBROWS];
+    load_tile(Q.v + (int64_t)vec * Q.stride + (int64_t)tile * TILE, a, n_valid);     // elements past d read as 0
+    quality_of_tile(a, L, Q, tile, vec, n_valid, S);
 }
 
 // Workgroups 0 .. n_cross-1: one block that spans several tiles each.  The last

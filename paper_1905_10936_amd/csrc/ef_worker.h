@@ -1,6 +1,7 @@
 // Worker kernels of libef (Algorithm 4 and Algorithm 3 of arxiv 1905.10936): see ef_tile.h for the tile scheme.
 #pragma once
 #include "ef_tile.h"
+#include "ef_quality.h"
 
 namespace ef {
 
@@ -277,9 +278,10 @@ void k_worker_uniform(Layout L, ScratchRef R, WorkerArgs A, int n_workers)
 // Eight workgroups per CU (64 VGPRs, a few spilled): the one-pass limit is half of what is
 // resident, and 2048 resident workgroups let blocks of up to 1024 tiles (4 Mi elements) finish
 // in one pass (measured: 27.1 -> 24.4 ms on the transformer-like layout, no change elsewhere).
-template <bool MOM>
-__device__ __forceinline__ void worker_mixed_tile(const Layout &L, const Scratch &X, const WorkerArgs &A, int32_t tile,
-                                                  int worker, int n_valid, TileShared &S)
+template <bool MOM, bool QUAL>
+__device__ __forceinline__ void worker_mixed_tile(const Layout &L, const Scratch &X, const WorkerArgs &A,
+                                                  const QualityArgs &Q, int32_t tile, int worker, int n_valid,
+                                                  TileShared &S)
 {
     const int64_t tile_start = (int64_t)tile * TILE;
     const float *g = A.grad + (int64_t)worker * A.grad_stride + tile_start;
@@ -291,6 +293,12 @@ __device__ __forceinline__ void worker_mixed_tile(const Layout &L, const Scratch
     load_tile(e, pv, n_valid);
     worker_values<MOM>(gv, mv, pv, A.mu, A.r);
     if (MOM) store_tile(m, mv, n_valid);
+    if constexpr (QUAL) {
+        float4 a[SUBROWS];
+#pragma unroll
+        for (int k = 0; k < SUBROWS; ++k) a[k] = pv[k];
+        quality_of_tile(a, L, Q, tile, worker, n_valid, S);
+    }
     compress_mixed(pv, L, tile, n_valid, A.signs + (int64_t)worker * A.signs_stride,
                    A.scales + (int64_t)worker * A.scales_stride, e, X, worker, S);
 }
@@ -304,12 +312,14 @@ struct TilesShared<true> {
     typedef TileShared type;
 };
 
-template <bool MOM, bool MIXED>
+// QUAL = true: the compressor-quality sums of p (Section 3.2: Proposition 1's phi, Eq. (1)'s delta)
+// are taken on the way, from the values the kernel holds anyway (see ef_quality.h).
+template <bool MOM, bool MIXED, bool QUAL>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void k_worker_tiles(Layout L, ScratchRef R, WorkerArgs A)
+void k_worker_tiles(Layout L, ScratchRef R, WorkerArgs A, QualityArgs Q)
 {
     const Scratch X = open_call(R);
-    __shared__ typename TilesShared<MIXED>::type S;
+    __shared__ typename TilesShared<MIXED || QUAL>::type S;
     const bool whole = !MIXED || (int)blockIdx.x >= L.n_mixed;
     const int32_t tile = whole ? L.uniform_tiles[blockIdx.x - (MIXED ? L.n_mixed : 0)] : L.mixed_tiles[blockIdx.x];
     const int worker = blockIdx.y;
@@ -330,6 +340,12 @@ void k_worker_tiles(Layout L, ScratchRef R, WorkerArgs A)
         correct_loaded_residual(pv, corr);
         worker_values<MOM>(gv, mv, pv, A.mu, A.r);
         if (MOM) store_tile(m, mv, TILE);
+        if constexpr (QUAL) {
+            float4 a[SUBROWS];
+#pragma unroll
+            for (int k = 0; k < SUBROWS; ++k) a[k] = pv[k];
+            quality_of_tile(a, L, Q, tile, worker, TILE, S);
+        }
         const int kind = compress_uniform(pv, L, tile, TILE, signs, scales_out, e, X, worker, S, P, true);
         resolve_posted(P, L, X, worker, scales_out, S);
         if (kind == UNI_PENDING) {
@@ -339,7 +355,7 @@ void k_worker_tiles(Layout L, ScratchRef R, WorkerArgs A)
             store_tile(e, pv, TILE);
         }
     } else if constexpr (MIXED) {
-        worker_mixed_tile<MOM>(L, X, A, tile, worker, n_valid, S);
+        worker_mixed_tile<MOM, QUAL>(L, X, A, Q, tile, worker, n_valid, S);
     }
 }
 

@@ -51,6 +51,7 @@ int main()
     REQUIRE(ef_plan_d(nullptr) == 0 && ef_plan_blocks(nullptr) == 0 && ef_sign_words(nullptr) == 0);
     REQUIRE(ef_payload_bytes(nullptr) == 0 && ef_payload_scales_offset(nullptr) == 0);
     REQUIRE(ef_worker_step(nullptr, 1, buf, 64, buf, buf, 64, 0.9f, 0.f, 0.1f, words, buf, nullptr) == EF_ERR_NULL);
+    REQUIRE(ef_worker_step_quality(nullptr, 1, buf, 64, buf, buf, 64, 0.9f, 0.f, 0.1f, words, buf, q, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_worker_step_sgd(nullptr, 1, buf, 64, buf, 64, 0.f, 0.1f, words, buf, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_server_step(nullptr, 1, words, buf, buf, 0.f, 0.1f, words, buf, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_apply(nullptr, buf, words, buf, 0.1f, nullptr) == EF_ERR_NULL);

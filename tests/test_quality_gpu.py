@@ -106,3 +106,71 @@ def test_quality_rejects_bad_arguments():
         ef.ef_compressor_quality(plan, v, out)          # more vectors than the plan allows
     assert ei.value.code == ef.EF_ERR_ARG
     plan.close()
+
+
+# ---- the same figures taken inside the worker kernel (ef_worker_step_quality)
+
+def _p_of(g, m_new, e_old, mu, r):
+    """The worker's corrected gradient p = (mu*m_new + g) + r*e_old in unfused fp32, from the
+    momentum the oracle's worker step has written (numpy float32 arithmetic rounds every
+    operation once, as the oracle's C does)."""
+    return (F(mu) * m_new + g) + F(r) * e_old
+
+
+@pytest.mark.parametrize("layout", ["ragged", "tiny_blocks", "one_block", "aligned"])
+def test_worker_step_quality_matches_the_oracle_on_p(layout):
+    """ef_worker_step_quality = ef_worker_step bit for bit, plus phi and delta of every worker's
+    p within 1e-9 of the oracle's efo_quality on p (and equal to what ef_compressor_quality gives
+    on p: the same sums in the same order), over two steps so that momentum, residual and the
+    stepsize ratio are in play."""
+    import oracle
+    sizes = {"ragged": [1, 5, 64, 3 * 4096 + 17, 700, 9 * 4096 - 3, 4096, 2 * 4096 + 1, 33, 40000, 11],
+             "tiny_blocks": list(np.random.default_rng(3).integers(1, 65, 900)),
+             "one_block": [7 * 4096 + 5],
+             "aligned": [4096, 2 * 4096, 8 * 4096, 4096]}[layout]
+    offs = _offs(sizes)
+    d, B, M = int(offs[-1]), len(sizes), 3
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(11)
+    plans = [ef.Plan(offs, M), ef.Plan(offs, M)]
+    plans[1].set_persistent(False)       # the plain call on the same kernel family, for the bit-for-bit comparison
+    W = plans[0].W
+    ds = (d + 3) // 4 * 4
+    st = []
+    for _ in range(2):
+        st.append(dict(g=torch.zeros((M, ds), device=dev), m=torch.zeros((M, ds), device=dev),
+                       e=torch.zeros((M, ds), device=dev), ws=torch.zeros((M, W), dtype=torch.int64, device=dev),
+                       wc=torch.zeros((M, B), device=dev)))
+    q = torch.zeros((M, 2), dtype=torch.float64, device=dev)
+    q2 = torch.zeros((M, 2), dtype=torch.float64, device=dev)
+    m_o, e_o = np.zeros((M, d), F), np.zeros((M, d), F)
+    eta_prev = 0.0
+    for t, eta in enumerate([0.1, 0.05]):
+        g = rng.standard_normal((M, d)).astype(F)
+        g[:, : d // 3] *= 1e-3
+        g[rng.random((M, d)) < 0.05] = 0.0
+        for s in st:
+            s["g"][:, :d].copy_(torch.as_tensor(g))
+        q.fill_(-1.0)
+        ef.ef_worker_step_quality(plans[0], st[0]["g"], st[0]["m"], st[0]["e"], 0.9, eta_prev, eta, st[0]["ws"], st[0]["wc"], q)
+        ef.ef_worker_step(plans[1], st[1]["g"], st[1]["m"], st[1]["e"], 0.9, eta_prev, eta, st[1]["ws"], st[1]["wc"])
+        torch.cuda.synchronize()
+        for key in ("m", "e", "ws", "wc"):
+            assert torch.equal(st[0][key], st[1][key]), "step %d: %s differs from the plain call" % (t, key)
+        got = q.cpu().numpy()
+        p_dev = torch.zeros((M, ds), device=dev)
+        for i in range(M):
+            e_old = e_o[i].copy()
+            oracle.worker_step(np.ascontiguousarray(g[i]), m_o[i], e_o[i], offs, F(0.9), F(eta_prev), F(eta))
+            r = F(eta_prev) / F(eta)
+            p = _p_of(g[i], m_o[i], e_old, 0.9, r)
+            phi, delta = oracle.quality(np.ascontiguousarray(p), offs)
+            assert abs(got[i, 0] - phi) <= 1e-9 * phi, (layout, t, i, got[i], phi)
+            assert abs(got[i, 1] - delta) <= 1e-9 * delta, (layout, t, i, got[i], delta)
+            p_dev[i, :d].copy_(torch.as_tensor(p))
+        ef.ef_compressor_quality(plans[0], p_dev, q2)
+        torch.cuda.synchronize()
+        assert torch.equal(q, q2), "step %d: not the figures ef_compressor_quality gives on p" % t
+        eta_prev = eta
+    for p_ in plans:
+        p_.close()
