@@ -67,7 +67,8 @@ extern "C" {
 
 #define EF_MAX_WORKERS 64
 
-typedef struct ef_plan ef_plan; /* opaque */
+typedef struct ef_plan ef_plan;   /* opaque */
+typedef struct ef_state ef_state; /* opaque: optimizer state held by the library, see ef_state_create */
 
 /*
  * Build the per-layout plan: a device copy of the partition, the tile -> block
@@ -276,6 +277,53 @@ int ef_apply_fused(const ef_plan *plan, float *params, const void *payload, floa
  */
 int ef_compressor_quality(ef_plan *plan, int n_vectors, const float *v, int64_t stride, double *out,
                           void *stream);
+
+/*
+ * Optimizer state held by the library.  Algorithm 4 keeps, between iterations,
+ * the momentum m_i and the residual e_i of every worker and the residual e~ of
+ * the server (all zero before the first iteration).  With ef_worker_step and
+ * ef_server_step the caller owns those buffers and sees e after every call,
+ * which for blocks beyond the one-pass limit costs a second pass, or the
+ * caveats of ef_plan_set_lazy.  A caller that never looks at the residuals can
+ * leave the buffers to the library instead: the calls below then always run
+ * in the deferred mode (no second pass, no workgroup waiting for the scale of
+ * a large block; on 2^28 elements in 256 blocks with 8 workers 7.5 instead of
+ * 7.9 ms per step), with nothing for the caller to keep track of.  Payloads and
+ * parameters are bit-equal to those of the caller-owned calls.
+ *
+ *   ef_state_create   allocates (hipMalloc) and zeroes m, e for n_workers
+ *                     workers and e~; turns the plan's deferred mode on and
+ *                     keeps it on (ef_plan_set_lazy then returns EF_ERR_ARG).
+ *                     One state per plan (EF_ERR_ARG for a second one, for
+ *                     n_workers outside [1, max_workers], or while
+ *                     caller-owned buffers of this plan wait for a correction:
+ *                     ef_flush them first).  Synchronises `stream`.
+ *   ef_state_destroy  frees it and turns the mode off; synchronises the
+ *                     device.  Destroy the state before its plan.
+ *   ef_worker_step_state / ef_server_step_state
+ *                     ef_worker_step (all n_workers of the state) and
+ *                     ef_server_step on the held buffers; the other arguments,
+ *                     the results and the errors are those calls'.
+ *   ef_state_export   writes the true m, e (rows state_stride elements apart,
+ *                     >= d) and e~ of Algorithm 4 into caller buffers, for a
+ *                     checkpoint or a look at them; any of the three may be
+ *                     NULL.  The held state is unchanged in value.
+ *   ef_state_import   the reverse: overwrites the held m, e, e~ (those given)
+ *                     with finished state, e.g. from a checkpoint.
+ * Both copies are device-to-device on `stream` and allocate nothing.
+ */
+int ef_state_create(ef_plan *plan, int n_workers, ef_state **out, void *stream);
+int ef_state_destroy(ef_state *state);
+int ef_worker_step_state(const ef_plan *plan, ef_state *state, const float *grad, int64_t grad_stride,
+                         float mu, float eta_prev, float eta, uint64_t *packed_signs, float *scales,
+                         void *stream);
+int ef_server_step_state(const ef_plan *plan, ef_state *state, int M, const uint64_t *packed_signs,
+                         const float *scales, float eta_prev, float eta, uint64_t *out_signs,
+                         float *out_scales, void *stream);
+int ef_state_export(const ef_plan *plan, ef_state *state, float *mom, float *err, int64_t state_stride,
+                    float *server_err, void *stream);
+int ef_state_import(const ef_plan *plan, ef_state *state, const float *mom, const float *err,
+                    int64_t state_stride, const float *server_err, void *stream);
 
 /*
  * ef_worker_step that also reports how well the compressor approximated what

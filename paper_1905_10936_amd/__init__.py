@@ -30,6 +30,8 @@ ABI_SYMBOLS = (
     "ef_payload_bytes", "ef_payload_scales_offset", "ef_worker_step_fused", "ef_server_step_fused", "ef_apply_fused",
     "ef_compressor_quality", "ef_compressor_quality_static", "ef_worker_step_quality",
     "ef_plan_set_lazy", "ef_plan_is_lazy", "ef_flush",
+    "ef_state_create", "ef_state_destroy", "ef_worker_step_state", "ef_server_step_state", "ef_state_export",
+    "ef_state_import",
 )
 # ... and what include/ef_debug.h declares (tuning and diagnostics the tests use)
 DEBUG_SYMBOLS = (
@@ -111,6 +113,17 @@ def lib():
         getattr(L, name).argtypes = [vp, c_int, vp, i64, vp, vp]
     L.ef_apply_wd.restype = c_int
     L.ef_apply_wd.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, vp]
+    L.ef_state_create.restype = c_int
+    L.ef_state_create.argtypes = [vp, c_int, ctypes.POINTER(vp), vp]
+    L.ef_state_destroy.restype = c_int
+    L.ef_state_destroy.argtypes = [vp]
+    L.ef_worker_step_state.restype = c_int
+    L.ef_worker_step_state.argtypes = [vp, vp, vp, i64, f32, f32, f32, vp, vp, vp]
+    L.ef_server_step_state.restype = c_int
+    L.ef_server_step_state.argtypes = [vp, vp, c_int, vp, vp, f32, f32, vp, vp, vp]
+    for name in ("ef_state_export", "ef_state_import"):
+        getattr(L, name).restype = c_int
+        getattr(L, name).argtypes = [vp, vp, vp, vp, i64, vp, vp]
     L.ef_strerror.restype = ctypes.c_char_p
     L.ef_strerror.argtypes = [c_int]
     _lib = L
@@ -381,3 +394,80 @@ def ef_compressor_quality(plan, v, out, stream=None, static_scratch=False):
 
 def ef_compressor_quality_static(plan, v, out, stream=None):
     ef_compressor_quality(plan, v, out, stream, static_scratch=True)
+
+
+class State:
+    """ef_state: Algorithm 4's m_i, e_i and e~ held by the library (see ef_state_create in
+    include/ef.h).  Close it before its plan."""
+
+    def __init__(self, plan, n_workers, stream=None):
+        self.plan, self.n = plan, int(n_workers)
+        self._h = ctypes.c_void_p()
+        _check(lib().ef_state_create(plan._h, self.n, ctypes.byref(self._h), _stream_ptr(stream)))
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().ef_state_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def ef_state_create(plan, n_workers, stream=None):
+    return State(plan, n_workers, stream)
+
+
+def ef_state_destroy(state):
+    state.close()
+
+
+def ef_worker_step_state(plan, state, grad, mu, eta_prev, eta, packed_signs, scales, stream=None):
+    n = 1 if grad.dim() == 1 else grad.shape[0]
+    if n != state.n or packed_signs.numel() != n * plan.W or scales.numel() != n * plan.B:
+        raise TypeError("grad must hold the state's workers; packed_signs n*W words, scales n*B floats")
+    rc = lib().ef_worker_step_state(plan._h, state._h, _ptr(grad, torch.float32, "grad"), _stride(grad, plan.d, "grad"),
+                                    float(mu), float(eta_prev), float(eta),
+                                    _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                                    _ptr(scales, torch.float32, "scales"), _stream_ptr(stream))
+    _check(rc)
+
+
+def ef_server_step_state(plan, state, M, packed_signs, scales, eta_prev, eta, out_signs, out_scales, stream=None):
+    if packed_signs.numel() != M * plan.W or scales.numel() != M * plan.B:
+        raise TypeError("packed_signs must hold M*W words and scales M*B floats")
+    if out_signs.numel() != plan.W or out_scales.numel() != plan.B:
+        raise TypeError("out_signs/out_scales must hold W/B entries")
+    rc = lib().ef_server_step_state(plan._h, state._h, int(M), _ptr(packed_signs, packed_signs.dtype, "packed_signs"),
+                                    _ptr(scales, torch.float32, "scales"), float(eta_prev), float(eta),
+                                    _ptr(out_signs, out_signs.dtype, "out_signs"),
+                                    _ptr(out_scales, torch.float32, "out_scales"), _stream_ptr(stream))
+    _check(rc)
+
+
+def _state_copy(fn, plan, state, mom, err, server_err, stream):
+    stride = plan.d
+    for t, name in ((mom, "mom"), (err, "err")):
+        if t is not None:
+            if (1 if t.dim() == 1 else t.shape[0]) != state.n:
+                raise TypeError("%s must hold the state's workers" % name)
+            stride = _stride(t, plan.d, name)
+    if mom is not None and err is not None and _stride(mom, plan.d, "mom") != _stride(err, plan.d, "err"):
+        raise TypeError("mom and err must share their row stride")
+    if server_err is not None and server_err.numel() != plan.d:
+        raise TypeError("server_err must hold d entries")
+    p = [None if t is None else _ptr(t, torch.float32, n) for t, n in ((mom, "mom"), (err, "err"), (server_err, "server_err"))]
+    _check(fn(plan._h, state._h, p[0], p[1], stride, p[2], _stream_ptr(stream)))
+
+
+def ef_state_export(plan, state, mom=None, err=None, server_err=None, stream=None):
+    """Writes the true m, e ([n][>=d]) and e~ ([d]) into the given tensors (any may be None)."""
+    _state_copy(lib().ef_state_export, plan, state, mom, err, server_err, stream)
+
+
+def ef_state_import(plan, state, mom=None, err=None, server_err=None, stream=None):
+    """Overwrites the held m, e, e~ with the given finished state (any may be None)."""
+    _state_copy(lib().ef_state_import, plan, state, mom, err, server_err, stream)

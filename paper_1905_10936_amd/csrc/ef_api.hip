@@ -37,6 +37,7 @@ struct ef_plan {
     } role[3];
     int sync_group;                 // tiles of a large block that are written out in step (ef_plan_set_sync_group)
     int lazy;                       // deferred correction on (ef_plan_set_lazy)
+    ef_state *state;                // the library-held state that lives on this plan, if any
     // Host-side guard of the deferred mode: the residual buffers (workers, server) the last calls
     // left waiting for their correction, so that a call with other buffers is refused.  The
     // device-side CallState is what the kernels go by; this only catches misuse at the boundary.
@@ -72,6 +73,17 @@ struct ef_plan {
 // stand-in for the symbol; the memory is reached through the per-device address that
 // static_scratch() looks up once per device.
 static __device__ __align__(256) double scratch[(size_t)EF_QUALITY_STATIC_MAX_TILE_VECTORS * 6];
+
+// Optimizer state held by the library (ef_state_create): Algorithm 4's m_i and e_i of n_workers
+// workers and the server's e~, in device memory the caller never addresses, which lets every call
+// on it run in the deferred-correction mode.
+struct ef_state {
+    ef_plan *plan;
+    int n_workers;
+    int64_t stride;                 // elements between two workers' rows: d rounded up to a multiple of 4
+    float *mom, *err;               // [n_workers][stride]
+    float *server_err;              // [d]
+};
 
 namespace {
 
@@ -549,6 +561,7 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
     p->d_state = nullptr;
     p->d_lazy_scales = nullptr;
     p->lazy = 0;
+    p->state = nullptr;
     p->sync_group = 16;
     p->lazy_buf[0] = p->lazy_buf[1] = nullptr;
     p->lazy_stride_seen = 0;
@@ -585,6 +598,7 @@ int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, 
 int ef_plan_destroy(ef_plan *plan)
 {
     if (!plan) return EF_ERR_NULL;
+    if (plan->state) return EF_ERR_ARG;     // ef_state_destroy first
     (void)hipDeviceSynchronize();
     destroy_device(plan);
     delete plan;
@@ -602,9 +616,17 @@ static int residuals_pending(ef_plan *plan, bool *pending)
     return EF_OK;
 }
 
+static int set_lazy(ef_plan *plan, int on);
+
 int ef_plan_set_lazy(ef_plan *plan, int on)
 {
     if (!plan) return EF_ERR_NULL;
+    if (plan->state) return EF_ERR_ARG;     // a library-held state keeps the mode on
+    return set_lazy(plan, on);
+}
+
+static int set_lazy(ef_plan *plan, int on)
+{
     bool pending = false;
     int rc = residuals_pending(plan, &pending);
     if (rc) return rc;
@@ -1052,6 +1074,136 @@ int ef_compressor_quality_static(const ef_plan *plan, int n_vectors, const float
     // [n][ntiles][2] tile sums, then [n][2*ntiles][2] sums of open segments; every word the kernels read
     // is written earlier in the same call, so nothing has to be cleared
     return quality_launch(plan, n_vectors, v, stride, out, base, base + 2 * tile_vectors, static_cast<hipStream_t>(stream));
+}
+
+int ef_state_create(ef_plan *plan, int n_workers, ef_state **out, void *stream)
+{
+    if (!plan || !out) return EF_ERR_NULL;
+    *out = nullptr;
+    if (n_workers < 1 || n_workers > plan->max_workers || plan->state) return EF_ERR_ARG;
+    int rc = set_lazy(plan, 1);             // refused (EF_ERR_ARG) while caller-owned buffers wait for a correction
+    if (rc) return rc;
+    ef_state *st = new (std::nothrow) ef_state();
+    if (!st) return EF_ERR_ARG;
+    st->plan = plan;
+    st->n_workers = n_workers;
+    st->stride = (plan->L.d + 3) / 4 * 4;
+    st->mom = st->err = st->server_err = nullptr;
+    const size_t rows = sizeof(float) * (size_t)st->stride * (size_t)n_workers, one = sizeof(float) * (size_t)plan->L.d;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMalloc(&st->mom, rows);
+    if (e == hipSuccess) e = hipMalloc(&st->err, rows);
+    if (e == hipSuccess) e = hipMalloc(&st->server_err, one);
+    // m_0 = e_0 = e~_0 = 0 (Algorithm 4, input line)
+    if (e == hipSuccess) e = hipMemsetAsync(st->mom, 0, rows, s);
+    if (e == hipSuccess) e = hipMemsetAsync(st->err, 0, rows, s);
+    if (e == hipSuccess) e = hipMemsetAsync(st->server_err, 0, one, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        if (st->mom) (void)hipFree(st->mom);
+        if (st->err) (void)hipFree(st->err);
+        if (st->server_err) (void)hipFree(st->server_err);
+        delete st;
+        (void)set_lazy(plan, 0);
+        return hip_fail(e);
+    }
+    plan->state = st;
+    *out = st;
+    return EF_OK;
+}
+
+int ef_state_destroy(ef_state *state)
+{
+    if (!state) return EF_ERR_NULL;
+    ef_plan *plan = state->plan;
+    (void)hipDeviceSynchronize();
+    (void)hipFree(state->mom);
+    (void)hipFree(state->err);
+    (void)hipFree(state->server_err);
+    plan->state = nullptr;
+    delete state;
+    // the buffers that waited for a correction are gone: clear the marks, leave the mode
+    hipLaunchKernelGGL(ef::k_flush_done, dim3(1), dim3(64), 0, nullptr, plan->d_state, 0, plan->max_workers);
+    hipLaunchKernelGGL(ef::k_flush_done, dim3(1), dim3(64), 0, nullptr, plan->d_state, plan->max_workers, 1);
+    EF_HIP(hipGetLastError());
+    plan->lazy_buf[0] = plan->lazy_buf[1] = nullptr;
+    plan->lazy_sets_seen = 0;
+    return set_lazy(plan, 0);
+}
+
+int ef_worker_step_state(const ef_plan *plan, ef_state *state, const float *grad, int64_t grad_stride, float mu,
+                         float eta_prev, float eta, uint64_t *packed_signs, float *scales, void *stream)
+{
+    if (!plan || !state) return EF_ERR_NULL;
+    if (state->plan != plan) return EF_ERR_ARG;
+    return worker_step_impl(plan, state->n_workers, grad, grad_stride, state->mom, state->err, state->stride, mu,
+                            eta_prev, eta, packed_signs, plan->L.W, scales, plan->L.B, stream);
+}
+
+int ef_server_step_state(const ef_plan *plan, ef_state *state, int M, const uint64_t *packed_signs, const float *scales,
+                         float eta_prev, float eta, uint64_t *out_signs, float *out_scales, void *stream)
+{
+    if (!plan || !state) return EF_ERR_NULL;
+    if (state->plan != plan) return EF_ERR_ARG;
+    return server_step_impl(plan, M, packed_signs, plan->L.W, scales, plan->L.B, state->server_err, eta_prev, eta,
+                            out_signs, out_scales, stream);
+}
+
+// Copies between the library-held state and caller buffers, row by row (the strides may differ).
+static int copy_state(const ef_plan *plan, ef_state *state, float *mom, float *err, int64_t state_stride,
+                      float *server_err, bool to_caller, hipStream_t s)
+{
+    const size_t row = sizeof(float) * (size_t)plan->L.d;
+    const size_t mine = sizeof(float) * (size_t)state->stride, theirs = sizeof(float) * (size_t)state_stride;
+    float *pairs[2][2] = {{state->mom, mom}, {state->err, err}};
+    for (auto &pr : pairs) {
+        if (!pr[1]) continue;
+        if (to_caller)
+            EF_HIP(hipMemcpy2DAsync(pr[1], theirs, pr[0], mine, row, (size_t)state->n_workers, hipMemcpyDeviceToDevice, s));
+        else
+            EF_HIP(hipMemcpy2DAsync(pr[0], mine, pr[1], theirs, row, (size_t)state->n_workers, hipMemcpyDeviceToDevice, s));
+    }
+    if (server_err) {
+        if (to_caller)
+            EF_HIP(hipMemcpyAsync(server_err, state->server_err, row, hipMemcpyDeviceToDevice, s));
+        else
+            EF_HIP(hipMemcpyAsync(state->server_err, server_err, row, hipMemcpyDeviceToDevice, s));
+    }
+    return EF_OK;
+}
+
+static int state_copy_args(const ef_plan *plan, const ef_state *state, const float *mom, const float *err,
+                           int64_t state_stride, const float *server_err)
+{
+    if (!plan || !state) return EF_ERR_NULL;
+    if (state->plan != plan) return EF_ERR_ARG;
+    if ((mom || err) && state->n_workers > 1 && state_stride < plan->L.d) return EF_ERR_ARG;
+    if ((mom && !aligned(mom, 4)) || (err && !aligned(err, 4)) || (server_err && !aligned(server_err, 4))) return EF_ERR_ALIGN;
+    return EF_OK;
+}
+
+int ef_state_export(const ef_plan *plan, ef_state *state, float *mom, float *err, int64_t state_stride,
+                    float *server_err, void *stream)
+{
+    int rc = state_copy_args(plan, state, mom, err, state_stride, server_err);
+    if (rc) return rc;
+    // write the corrections that are still waiting, then the buffers hold m, e and e~ of Algorithm 4
+    rc = ef_flush(plan, state->n_workers, state->err, state->stride, state->server_err, stream);
+    if (rc) return rc;
+    return copy_state(plan, state, mom, err, state_stride, server_err, true, static_cast<hipStream_t>(stream));
+}
+
+int ef_state_import(const ef_plan *plan, ef_state *state, const float *mom, const float *err, int64_t state_stride,
+                    const float *server_err, void *stream)
+{
+    int rc = state_copy_args(plan, state, mom, err, state_stride, server_err);
+    if (rc) return rc;
+    // what is brought in is finished state: no correction may be left waiting for the buffers it replaces
+    rc = ef_flush(plan, state->n_workers, err ? state->err : nullptr, state->stride, server_err ? state->server_err : nullptr,
+                  stream);
+    if (rc) return rc;
+    return copy_state(plan, state, const_cast<float *>(mom), const_cast<float *>(err), state_stride,
+                      const_cast<float *>(server_err), false, static_cast<hipStream_t>(stream));
 }
 
 const char *ef_strerror(int code)

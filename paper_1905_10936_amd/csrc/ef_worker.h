@@ -321,7 +321,8 @@ void k_worker_tiles(Layout L, ScratchRef R, WorkerArgs A, QualityArgs Q)
     const Scratch X = open_call(R);
     __shared__ typename TilesShared<MIXED || QUAL>::type S;
     const bool whole = !MIXED || (int)blockIdx.x >= L.n_mixed;
-    const int32_t tile = whole ? L.uniform_tiles[blockIdx.x - (MIXED ? L.n_mixed : 0)] : L.mixed_tiles[blockIdx.x];
+    // without mixed tiles the list of whole tiles is 0, 1, 2, ...: one dependent load less
+    const int32_t tile = !MIXED ? (int32_t)blockIdx.x : whole ? L.uniform_tiles[blockIdx.x - L.n_mixed] : L.mixed_tiles[blockIdx.x];
     const int worker = blockIdx.y;
     const int n_valid = whole ? TILE : tile_valid(L, tile);
     const int64_t tile_start = (int64_t)tile * TILE;

@@ -60,6 +60,15 @@ int main()
     REQUIRE(ef_server_step_fused(nullptr, 1, words, buf, 0.f, 0.1f, words, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_apply_fused(nullptr, buf, words, 0.1f, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_flush(nullptr, 1, buf, 64, buf, nullptr) == EF_ERR_NULL);
+    {
+        ef_state *st = nullptr;
+        REQUIRE(ef_state_create(nullptr, 1, &st, nullptr) == EF_ERR_NULL && st == nullptr);
+        REQUIRE(ef_state_destroy(nullptr) == EF_ERR_NULL);
+        REQUIRE(ef_worker_step_state(nullptr, nullptr, buf, 64, 0.9f, 0.f, 0.1f, words, buf, nullptr) == EF_ERR_NULL);
+        REQUIRE(ef_server_step_state(nullptr, nullptr, 1, words, buf, 0.f, 0.1f, words, buf, nullptr) == EF_ERR_NULL);
+        REQUIRE(ef_state_export(nullptr, nullptr, buf, buf, 64, buf, nullptr) == EF_ERR_NULL);
+        REQUIRE(ef_state_import(nullptr, nullptr, buf, buf, 64, buf, nullptr) == EF_ERR_NULL);
+    }
     REQUIRE(ef_compressor_quality(nullptr, 1, buf, 64, q, nullptr) == EF_ERR_NULL);
     REQUIRE(ef_compressor_quality_static(nullptr, 1, buf, 64, q, nullptr) == EF_ERR_NULL);
 
