@@ -64,7 +64,9 @@ def collect(workload, lazy):
         if rc != 0:
             print(open(os.path.join(out, "last_run.log")).read()[-3000:])
             sys.exit(rc)
-    head = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True, text=True).stdout.strip()
+    # the commit the tree was at: from git, or from EF_COMMIT where the tree travels without its history
+    head = os.environ.get("EF_COMMIT") or subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"],
+                                                         capture_output=True, text=True).stdout.strip()
     with open(os.path.join(out, "meta.json"), "w") as f:
         json.dump({"commit": head or None}, f)
 
