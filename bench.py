@@ -57,7 +57,7 @@ def measured_traffic(workload, kernel):
                 rec = json.loads(m.group(1))
             except ValueError:
                 continue
-            if rec.get("workload") == workload and kernel in rec.get("kernels", {}):
+            if rec.get("workload") == workload and rec.get("mode", "default") == "default" and kernel in rec.get("kernels", {}):
                 k = rec["kernels"][kernel]
                 return {"bytes_per_launch": k["traffic_bytes"], "ratio_to_algorithmic": k.get("ratio"),
                         "measured_at_commit": rec.get("commit"), "summary": os.path.relpath(path, ROOT)}

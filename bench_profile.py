@@ -122,7 +122,7 @@ def algorithmic(kernel, w, c):
         return 8.0 * d + (M + 1) * d / 8.0 + 4.0 * B * (M + 1)
     if kernel == "ef::k_apply":
         return 8.125 * d + 4.0 * B
-    if kernel.startswith("ef::k_probe"):
+    if kernel in ("ef::k_probe_stream", "ef::k_probe_grouped"):
         return 20.0 * (M * ((d + 3) // 4 * 4) // TILE) * TILE
     return None
 
