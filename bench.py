@@ -113,6 +113,8 @@ class Run:
             self.smsg = torch.zeros(pb, dtype=torch.uint8, device=dev)
         if variant == "wd":
             self.decay_mom = torch.zeros(d, dtype=torch.float32, device=dev)
+        if variant == "quality":
+            self.quality = torch.zeros((M, 2), dtype=torch.float64, device=dev)
         torch.cuda.synchronize()
         self.stream = torch.cuda.current_stream()
         self.eta_prev, self.t = 0.0, 0
@@ -150,6 +152,8 @@ class Run:
             ef.ef_worker_step_fused(plan, g, self.mom, self.err, w.mu, self.eta_prev, w.eta, self.wmsg)
         elif variant == "sgd":
             ef.ef_worker_step_sgd(plan, g, self.err, self.eta_prev, w.eta, self.ws, self.wc)
+        elif variant == "quality":
+            ef.ef_worker_step_quality(plan, g, self.mom, self.err, w.mu, self.eta_prev, w.eta, self.ws, self.wc, self.quality)
         else:
             ef.ef_worker_step(plan, g, self.mom, self.err, w.mu, self.eta_prev, w.eta, self.ws, self.wc)
         if ev:
@@ -194,9 +198,11 @@ class Run:
         w = self.w
         mixed = bool(np.any(w.offsets[1:] % TILE != 0))
         mom = "false" if self.variant == "sgd" else "true"
+        if self.variant == "quality":
+            return "ef::k_worker_tiles<true, true, true>"
         if self.plan.persistent and self.variant != "sgd":
             return "ef::k_worker_uniform<%s>" % mom
-        return "ef::k_worker_tiles<%s, %s>" % (mom, "true" if mixed else "false")
+        return "ef::k_worker_tiles<%s, %s, false>" % (mom, "true" if mixed else "false")
 
     def close(self):
         self.plan.close()
@@ -257,10 +263,11 @@ def main():
                     help="deferred residual correction for blocks beyond the one-pass limit (ef_plan_set_lazy)")
     ap.add_argument("--no-deferred", action="store_true",
                     help="skip the extra leg that times the same steps in the deferred-correction mode")
-    ap.add_argument("--variant", default="sgdm", choices=["sgdm", "sgd", "fused", "wd"],
+    ap.add_argument("--variant", default="sgdm", choices=["sgdm", "sgd", "fused", "wd", "quality"],
                     help="sgdm: Algorithm 4 (the default, the metric's configuration); sgd: Algorithm 3 worker "
                          "without a momentum buffer; fused: one message per worker (Section 4.2); wd: parameter "
-                         "update with weight decay (Appendix A)")
+                         "update with weight decay (Appendix A); quality: worker call that also reports phi and "
+                         "delta of p (ef_worker_step_quality), plus one untimed ef_compressor_quality pass")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of a captured HIP graph of the step (one graph per resident gradient set) "
                          "instead of eager calls; per-call times then come from an untimed eager pass")
@@ -323,6 +330,9 @@ def main():
     else:
         ms_per_step, calls, first_payload = run.timed(args.steps, args.warmup, first_payload=variant in ("sgdm", "wd"))
 
+    if variant == "quality":
+        # untimed: the stand-alone diagnostics pass over the gradients, so that its kernels show in a trace
+        ef.ef_compressor_quality(plan, run.grads[0], run.quality)
     fuse_limit_used = plan.fuse_limit
     # untimed diagnostic: one more worker and server call, asking each how many tiles left the one-pass route
     g = run.grads[run.t % n_sets]

@@ -31,13 +31,16 @@ HBM_PEAK = 8.0e12
 CALIB_KIB = 1048576.0           # the calibration kernel reads 2^28 floats and writes 2^28 floats
 
 
+VARIANT = "sgdm"                # bench.py --variant of the run being collected or summarized
+
+
 def tag_of(workload, lazy):
-    return workload + ("_deferred" if lazy else "")
+    return workload + ("_deferred" if lazy else "") + ("" if VARIANT == "sgdm" else "_" + VARIANT)
 
 
 def bench_args(workload, lazy, steps):
     a = ["python3", os.path.join(ROOT, "bench.py"), "--workload", workload, "--steps", str(steps), "--warmup", "1",
-         "--no-cpu", "--no-others", "--calib"]
+         "--no-cpu", "--no-others", "--calib", "--variant", VARIANT]
     return a + (["--lazy"] if lazy else ["--no-deferred"])
 
 
@@ -112,6 +115,8 @@ def algorithmic(kernel, w, c):
     """Bytes one launch of `kernel` must move on workload w (what the method itself needs: state read
     once and written once, sign bits, scales); None where no simple count applies."""
     d, B, M = w.d, w.B, w.M
+    if kernel.startswith("ef::k_worker_tiles<false"):       # Algorithm 3: no momentum buffer
+        return M * (12.125 * d + 4.0 * B)
     if kernel.startswith("ef::k_worker_tiles"):
         return M * (20.125 * d + 4.0 * B)
     if kernel.startswith("ef::k_worker_uniform"):
@@ -122,6 +127,10 @@ def algorithmic(kernel, w, c):
         return 8.0 * d + (M + 1) * d / 8.0 + 4.0 * B * (M + 1)
     if kernel == "ef::k_apply":
         return 8.125 * d + 4.0 * B
+    if kernel == "ef::k_apply_wd":
+        return 16.125 * d + 4.0 * B
+    if kernel == "ef::k_quality_tiles":                     # one read of every vector
+        return 4.0 * d * M
     if kernel in ("ef::k_probe_stream", "ef::k_probe_grouped"):
         return 20.0 * (M * ((d + 3) // 4 * 4) // TILE) * TILE
     return None
@@ -158,12 +167,13 @@ def summarize(workload, lazy):
     cal = "torch add (calibration, 1 GiB -> 1 GiB)"
     f_scale, w_scale = CALIB_KIB / mean[("fetch", cal)], CALIB_KIB / mean[("write", cal)]
 
-    lines = ["# rocprofv3 summary: %s%s (d = %d, B = %d, M = %d), MI355X" %
-             (workload, ", deferred-correction mode" if lazy else "", w.d, w.B, w.M), "",
+    lines = ["# rocprofv3 summary: %s%s%s (d = %d, B = %d, M = %d), MI355X" %
+             (workload, ", deferred-correction mode" if lazy else "",
+              "" if VARIANT == "sgdm" else ", bench.py --variant " + VARIANT, w.d, w.B, w.M), "",
              "Layout: %d tiles of 4096 elements, %d whole (inside one block), %d mixed.  Measured at commit %s."
              % (c["ntiles"], c["n_whole"], c["n_mixed"], meta.get("commit")),
-             "Commands (from /tmp with TMPDIR=/tmp; `python bench_profile.py collect %s%s` runs them):" %
-             (workload, " --lazy" if lazy else ""), ""]
+             "Commands (from /tmp with TMPDIR=/tmp; `python bench_profile.py collect %s%s%s` runs them):" %
+             (workload, " --lazy" if lazy else "", "" if VARIANT == "sgdm" else " --variant " + VARIANT), ""]
     lines += ["    " + " ".join(cmd).replace(ROOT, "$R") for cmd in cmds]
     lines += ["", "bench.py here runs 1 warm-up step, the timed steps, one untimed diagnostic worker + server call and, last, the",
               "two bandwidth probes (1 warm-up + 3 timed passes each); `achieved` = algorithmic bytes / average duration.", "",
@@ -182,7 +192,8 @@ def summarize(workload, lazy):
               "and WRITE_SIZE = %.1f, so the counters are scaled by %.5f (fetch) and %.5f (write)." %
               (mean[("write", cal)], f_scale, w_scale), "",
               "| kernel | FETCH_SIZE | WRITE_SIZE | read GB | written GB | total GB | algorithmic GB | ratio |", "|---|---|---|---|---|---|---|---|"]
-    record = {"workload": workload, "mode": "deferred" if lazy else "default", "commit": meta.get("commit"), "kernels": {}}
+    record = {"workload": workload, "mode": ("deferred" if lazy else "default") + ("" if VARIANT == "sgdm" else "/" + VARIANT),
+              "commit": meta.get("commit"), "kernels": {}}
     for s in sorted(stats, key=lambda k: -stats[k][2]):
         if s == cal or ("fetch", s) not in mean or ("write", s) not in mean:
             continue
@@ -206,7 +217,10 @@ def main():
     ap.add_argument("what", choices=["collect", "summarize"])
     ap.add_argument("workload")
     ap.add_argument("--lazy", action="store_true", help="the deferred-correction mode (ef_plan_set_lazy)")
+    ap.add_argument("--variant", default="sgdm", choices=["sgdm", "sgd", "wd", "quality"], help="bench.py --variant")
     args = ap.parse_args()
+    global VARIANT
+    VARIANT = args.variant
     (collect if args.what == "collect" else summarize)(args.workload, args.lazy)
 
 
