@@ -106,7 +106,7 @@ struct Layout {
 // arguments of a call are the same every time (a captured HIP graph of the
 // calls can be replayed): the number of calls made on the plan and the tag each
 // scratch set's partial words carry since the last call that used the set.
-// The last kernel of a call (k_advance) moves it on.
+// The last workgroup of the kernel that ends a call (k_tail) moves it on.
 struct CallState {
     unsigned int calls;
     unsigned int server_tag;            // bit 0
@@ -811,7 +811,7 @@ __device__ __forceinline__ void correct_loaded_residual(float4 (&e)[SUBROWS], co
 // Returns what is left to do with it:
 //   UNI_DONE    the block is this tile alone: scale and residual written;
 //   UNI_PARKED  block larger than fuse_limit: partial posted, p parked for the
-//               second-pass kernels;
+//               kernel that ends the call;
 //   UNI_PENDING partial posted: p stays with the caller until the block's
 //               scale is posted; P says whether this tile must form it.
 //   UNI_HELD    (only with hold = true) as UNI_PARKED, but p is still to be written by the caller,
