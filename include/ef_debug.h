@@ -22,7 +22,9 @@ extern "C" {
  * that larger blocks always take.  Results are identical on either route.
  * Negative values leave a setting unchanged; fuse_limit = 0 sends every block
  * through two passes, spin_limit = 0 makes every wait give up at once (used by
- * tests to exercise the fallback).  Synchronises the device.  By default each
+ * tests to exercise the fallback).  The default spin_limit is 2048 polls of
+ * about 1.2 us: waits on an idle GPU were measured to end within 64, so a wait
+ * that cannot succeed costs about 2.5 ms.  Synchronises the device.  By default each
  * kernel gets its own limit: half the tiles its workgroups can hold at once
  * (resident workgroups; times six for the persistent worker kernel, which
  * keeps three tiles in registers and three in LDS), at most 4096 tiles.  A

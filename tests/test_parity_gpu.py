@@ -361,11 +361,17 @@ def test_kernel_choice_follows_the_block_sizes():
     import ef_workloads as wl
     expect = {"flat_2p28": False, "odd_tiles": False, "resnet50_like": False, "resnet20_like": False,
               "transformer_like": True, "skewed_blocks": True}
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
     for name, persistent in expect.items():
         w = wl.get(name)
         plan = ef.ef_plan_create(w.offsets, w.M)
         assert plan.persistent == persistent, name
-        assert plan.fuse_limit == (2304 if persistent else 1024), name
+        # half of what the kernel's workgroups hold at once: resident workgroups per compute unit
+        # (1 to 8 of 256 threads) x compute units, x 6 tiles each in the persistent kernel
+        per_cu, rest = divmod(2 * plan.fuse_limit, cus * (6 if persistent else 1))
+        assert rest == 0 and 1 <= per_cu <= 8, (name, plan.fuse_limit)
+        if cus == 256:
+            assert plan.fuse_limit == (2304 if persistent else 1024), name     # 3 and 8 workgroups per unit
         plan.set_lazy(True)                  # deferred mode: one workgroup per tile unless asked otherwise
         assert not plan.persistent and plan.fuse_limit == 64, name
         plan.set_persistent(True)
