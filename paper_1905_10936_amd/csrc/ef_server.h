@@ -15,6 +15,8 @@ __device__ __forceinline__ float mean_of(float acc, float Mf, float Minv)
 }
 
 constexpr int SERVER_CHUNK = 8;     // workers whose sign words are in flight together
+constexpr int SCALE_GROUP = 4;      // mixed tiles: workers whose scales are staged in LDS together ...
+constexpr int SCALE_STAGE = 2048;   // ... in this many floats
 
 // p~ of a tile that lies inside one block b (Algorithm 4, server: decode and add the M payloads
 // in worker order, divide by M, add the rescaled server residual tv).  The sign words of
@@ -107,20 +109,62 @@ __device__ __forceinline__ void server_values_mixed(const Layout &L, const Serve
     const int64_t n_hw = 2 * L.W;
     const int64_t in_hw = 2 * A.in_signs_stride;
 
-    build_segment_index(L, tile, n_valid, fb, lb - fb + 1, S);
+    const int nseg = lb - fb + 1;
+    build_segment_index(L, tile, n_valid, fb, nseg, S);
     const int4 *seg4 = reinterpret_cast<const int4 *>(S.val);
-    for (int i = 0; i < A.M; ++i) {
-        const float *sc_i = A.scales_in + (int64_t)i * A.in_scales_stride + fb;
+    // The scales of the tile's segments are staged in LDS, SCALE_GROUP workers at a time where
+    // they fit (one coalesced read per worker instead of a gather per element), and looked up
+    // there; a tile with more segments than the stage holds gathers them from global memory.
+    __shared__ float seg_scale[SCALE_STAGE];
+    const int group = nseg * SCALE_GROUP <= SCALE_STAGE ? SCALE_GROUP : nseg <= SCALE_STAGE ? 1 : 0;
+    if (group) {
+        for (int i0 = 0; i0 < A.M; i0 += group) {
+            uint32_t word[SCALE_GROUP][SUBROWS];
 #pragma unroll
-        for (int k = 0; k < SUBROWS; ++k) {
-            const int64_t hw = hw0 + 8 * k;
-            const uint32_t word = (hw < n_hw) ? s32[(int64_t)i * in_hw + hw] : 0u;
-            const unsigned nibble = (word >> sh) & 0xFu;
-            const int4 sg = seg4[local_base(k) >> 2];
-            acc[k][0] = acc[k][0] + signed_scale(sc_i[sg.x], nibble & 1u);
-            acc[k][1] = acc[k][1] + signed_scale(sc_i[sg.y], nibble & 2u);
-            acc[k][2] = acc[k][2] + signed_scale(sc_i[sg.z], nibble & 4u);
-            acc[k][3] = acc[k][3] + signed_scale(sc_i[sg.w], nibble & 8u);
+            for (int u = 0; u < SCALE_GROUP; ++u) {
+                const int i = min(i0 + u, A.M - 1);      // past the group or M: loaded, not used
+#pragma unroll
+                for (int k = 0; k < SUBROWS; ++k) {
+                    const int64_t hw = hw0 + 8 * k;
+                    word[u][k] = (hw < n_hw) ? s32[(int64_t)i * in_hw + hw] : 0u;
+                }
+            }
+            if (i0 > 0) __syncthreads();                 // the stage is read no more
+            for (int u = 0; u < group && i0 + u < A.M; ++u) {
+                const float *sc_i = A.scales_in + (int64_t)(i0 + u) * A.in_scales_stride + fb;
+                for (int j = threadIdx.x; j < nseg; j += THREADS) seg_scale[u * nseg + j] = sc_i[j];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < SCALE_GROUP; ++u) {
+                if (u < group && i0 + u < A.M) {
+                    const float *sc_u = seg_scale + u * nseg;
+#pragma unroll
+                    for (int k = 0; k < SUBROWS; ++k) {
+                        const unsigned nibble = (word[u][k] >> sh) & 0xFu;
+                        const int4 sg = seg4[local_base(k) >> 2];
+                        acc[k][0] = acc[k][0] + signed_scale(sc_u[sg.x], nibble & 1u);
+                        acc[k][1] = acc[k][1] + signed_scale(sc_u[sg.y], nibble & 2u);
+                        acc[k][2] = acc[k][2] + signed_scale(sc_u[sg.z], nibble & 4u);
+                        acc[k][3] = acc[k][3] + signed_scale(sc_u[sg.w], nibble & 8u);
+                    }
+                }
+            }
+        }
+    } else {
+        for (int i = 0; i < A.M; ++i) {
+            const float *sc_i = A.scales_in + (int64_t)i * A.in_scales_stride + fb;
+#pragma unroll
+            for (int k = 0; k < SUBROWS; ++k) {
+                const int64_t hw = hw0 + 8 * k;
+                const uint32_t word = (hw < n_hw) ? s32[(int64_t)i * in_hw + hw] : 0u;
+                const unsigned nibble = (word >> sh) & 0xFu;
+                const int4 sg = seg4[local_base(k) >> 2];
+                acc[k][0] = acc[k][0] + signed_scale(sc_i[sg.x], nibble & 1u);
+                acc[k][1] = acc[k][1] + signed_scale(sc_i[sg.y], nibble & 2u);
+                acc[k][2] = acc[k][2] + signed_scale(sc_i[sg.z], nibble & 4u);
+                acc[k][3] = acc[k][3] + signed_scale(sc_i[sg.w], nibble & 8u);
+            }
         }
     }
     __syncthreads();            // S.val is free again

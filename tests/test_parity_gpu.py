@@ -42,6 +42,7 @@ def _layouts():
         "aligned_tiles": [4096] * 6,
         "blocks_1000": [1000] * 37 + [123],
         "all_ones": [1] * 9000,
+        "threes": [3] * 5000,                    # 1366 segments per tile: more than a quarter of the server's scale stage
         "tiny_blocks": tiny,
         "mixed_tiny_and_big": mixed,
         "two_big": [3 * 4096 + 5, 7 * 4096 - 5],
