@@ -85,7 +85,9 @@ typedef struct ef_state ef_state; /* opaque: optimizer state held by the library
  *
  * Offsets are validated first (EF_ERR_OFFSETS) before any GPU call is made, so
  * the check also works on a host without a GPU.  Allocates device memory with
- * hipMalloc on the current device; the plan must be used on that device only.
+ * hipMalloc on the current device; the plan must be used on that device only:
+ * every call that enqueues work on a plan returns EF_ERR_ARG if another device
+ * is current.
  */
 int ef_plan_create(ef_plan **out, const int64_t *block_offsets_host, int64_t B, int max_workers,
                    void *stream);

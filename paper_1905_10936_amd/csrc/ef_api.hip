@@ -108,6 +108,15 @@ int hip_fail(hipError_t e)
         if (e_ != hipSuccess) return hip_fail(e_);    \
     } while (0)
 
+// A plan's tables, scratch and state live on the device it was created on: a call made with another
+// device current would launch kernels there on memory they cannot reach.
+int on_plan_device(const ef_plan *plan)
+{
+    int device = -1;
+    EF_HIP(hipGetDevice(&device));
+    return device == plan->device ? EF_OK : EF_ERR_ARG;
+}
+
 // Address of the static scratch on the current device (which must be `device`).  The first call
 // per device asks the runtime for the symbol's address; no memory is allocated.
 int static_scratch(int device, double **out)
@@ -654,6 +663,7 @@ int ef_plan_set_sync_group(ef_plan *plan, int tiles)
 int ef_flush(const ef_plan *plan, int n_workers, float *err, int64_t state_stride, float *server_err, void *stream)
 {
     if (!plan) return EF_ERR_NULL;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     if (err && (n_workers < 1 || n_workers > plan->max_workers ||
                 (n_workers > 1 && (state_stride < plan->L.d || state_stride % 4))))
         return EF_ERR_ARG;
@@ -824,6 +834,7 @@ int worker_step_impl(const ef_plan *plan, int n_workers, const float *grad, int6
     // mom == nullptr selects Algorithm 3 (callers of the momentum entry points have checked theirs)
     const bool has_mom = mom != nullptr;
     if (!plan || !grad || !err || !packed_signs || !scales) return EF_ERR_NULL;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     if (n_workers < 1 || n_workers > plan->max_workers) return EF_ERR_ARG;
     if (!(mu >= 0.0f && mu < 1.0f) || !good_eta(eta_prev, eta)) return EF_ERR_ARG;
     // with one worker the strides are never used
@@ -936,6 +947,7 @@ int server_step_impl(const ef_plan *plan, int M, const uint64_t *packed_signs, i
                      uint64_t *out_signs, float *out_scales, void *stream)
 {
     if (!plan || !packed_signs || !scales || !server_err || !out_signs || !out_scales) return EF_ERR_NULL;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     if (M < 1 || M > plan->max_workers) return EF_ERR_ARG;
     if (!good_eta(eta_prev, eta)) return EF_ERR_ARG;
     {
@@ -999,6 +1011,7 @@ int ef_apply(const ef_plan *plan, float *params, const uint64_t *packed_signs, c
              void *stream)
 {
     if (!plan || !params || !packed_signs || !scales) return EF_ERR_NULL;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     if (!(std::isfinite(eta) && eta > 0.0f)) return EF_ERR_ARG;
     if (!aligned(params, 16) || !aligned(packed_signs, 8) || !aligned(scales, 4)) return EF_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1012,6 +1025,7 @@ int ef_apply_wd(const ef_plan *plan, float *params, float *decay_mom, const uint
                 const float *scales, float eta, float mu, float lambda, void *stream)
 {
     if (!plan || !params || !decay_mom || !packed_signs || !scales) return EF_ERR_NULL;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     if (!(std::isfinite(eta) && eta > 0.0f)) return EF_ERR_ARG;
     if (!(mu >= 0.0f && mu < 1.0f)) return EF_ERR_ARG;
     if (!(std::isfinite(lambda) && lambda >= 0.0f)) return EF_ERR_ARG;
@@ -1048,6 +1062,7 @@ static int quality_launch(const ef_plan *plan, int n_vectors, const float *v, in
 static int quality_args(const ef_plan *plan, int n_vectors, const float *v, int64_t stride, const double *out)
 {
     if (!plan || !v || !out) return EF_ERR_NULL;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     if (n_vectors < 1 || n_vectors > plan->max_workers) return EF_ERR_ARG;
     if (n_vectors > 1 && (stride < plan->L.d || stride % 4)) return EF_ERR_ARG;
     if (!aligned(v, 16) || !aligned(out, 8)) return EF_ERR_ALIGN;
@@ -1068,11 +1083,8 @@ int ef_compressor_quality_static(const ef_plan *plan, int n_vectors, const float
     if (rc) return rc;
     const int64_t tile_vectors = (int64_t)plan->L.ntiles * n_vectors;
     if (tile_vectors > (int64_t)EF_QUALITY_STATIC_MAX_TILE_VECTORS) return EF_ERR_SIZE;
-    int device = -1;
-    EF_HIP(hipGetDevice(&device));
-    if (device != plan->device) return EF_ERR_ARG;      // the plan's tables live on its own device
     double *base = nullptr;
-    rc = static_scratch(device, &base);
+    rc = static_scratch(plan->device, &base);      // quality_args has checked that the plan's device is current
     if (rc) return rc;
     // [n][ntiles][2] tile sums, then [n][2*ntiles][2] sums of open segments; every word the kernels read
     // is written earlier in the same call, so nothing has to be cleared
@@ -1084,6 +1096,7 @@ int ef_state_create(ef_plan *plan, int n_workers, ef_state **out, void *stream)
     if (!plan || !out) return EF_ERR_NULL;
     *out = nullptr;
     if (n_workers < 1 || n_workers > plan->max_workers || plan->state) return EF_ERR_ARG;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     int rc = set_lazy(plan, 1);             // refused (EF_ERR_ARG) while caller-owned buffers wait for a correction
     if (rc) return rc;
     ef_state *st = new (std::nothrow) ef_state();
@@ -1180,6 +1193,7 @@ static int state_copy_args(const ef_plan *plan, const ef_state *state, const flo
 {
     if (!plan || !state) return EF_ERR_NULL;
     if (state->plan != plan) return EF_ERR_ARG;
+    { const int rc_dev = on_plan_device(plan); if (rc_dev) return rc_dev; }
     if ((mom || err) && state->n_workers > 1 && state_stride < plan->L.d) return EF_ERR_ARG;
     if ((mom && !aligned(mom, 4)) || (err && !aligned(err, 4)) || (server_err && !aligned(server_err, 4))) return EF_ERR_ALIGN;
     return EF_OK;
