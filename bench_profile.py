@@ -2,8 +2,10 @@
 """rocprofv3 evidence for bench.py: collects a kernel trace and the HBM traffic counters of one
 workload on the GPU machine, and turns them into the short summary kept under profiles/.
 
-    python bench_profile.py collect  <workload> [--lazy]     on an MI355X; raw output -> gpurun_out/prof_<tag>/
-    python bench_profile.py summarize <workload> [--lazy]    anywhere; gpurun_out/prof_<tag>/ -> profiles/ef_step_<tag>.md
+    python bench_profile.py collect  <workload> [--lazy]     on an MI355X; raw output -> <raw>/prof_<tag>/
+    python bench_profile.py summarize <workload> [--lazy]    anywhere; <raw>/prof_<tag>/ -> profiles/ef_step_<tag>.md
+
+<raw> is the folder named by EF_PROFILE_RAW (default: an untracked scratch folder of the checkout).
 
 `collect` starts three rocprofv3 runs of bench.py as child processes, the program itself after
 `--`, counters in runs of their own: --kernel-trace --stats, --pmc FETCH_SIZE, --pmc WRITE_SIZE.
@@ -28,6 +30,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 TILE = 4096
 HBM_PEAK = 8.0e12
+RAW = os.environ.get("EF_PROFILE_RAW") or os.path.join(ROOT, "gpurun_out")      # raw profiler output (not tracked)
 CALIB_KIB = 1048576.0           # the calibration kernel reads 2^28 floats and writes 2^28 floats
 
 
@@ -45,7 +48,7 @@ def bench_args(workload, lazy, steps):
 
 
 def commands(workload, lazy):
-    out = os.path.join(ROOT, "gpurun_out", "prof_" + tag_of(workload, lazy))
+    out = os.path.join(RAW, "prof_" + tag_of(workload, lazy))
     return out, [
         ["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", os.path.join(out, "kt"), "-o", "kt", "--"]
         + bench_args(workload, lazy, 5),

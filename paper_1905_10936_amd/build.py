@@ -13,7 +13,7 @@ BENCH_LIB = os.path.join(HERE, "libef_bench.so")
 TARGETS = {
     LIB: (os.path.join(CSRC, "ef_api.hip"),
           [os.path.join(CSRC, h) for h in ("ef_device.h", "ef_tile.h", "ef_worker.h", "ef_server.h", "ef_finish.h",
-                                           "ef_quality.h", "ef_small.h")] +
+                                           "ef_quality.h")] +
           [os.path.join(ROOT, "include", h) for h in ("ef.h", "ef_debug.h")]),
     BENCH_LIB: (os.path.join(CSRC, "ef_bench.hip"),
                 [os.path.join(CSRC, h) for h in ("ef_tile.h", "ef_probe.h")] +
