@@ -235,6 +235,25 @@ def other_workload(name, dev, steps, warmup):
     ms, calls, _ = run.timed(steps, warmup)
     out = dict(summary_of(run, ms, calls, "sgdm"), d=w.d, B=w.B, M=w.M, steps=steps, warmup=warmup,
                worker_fuse_limit_tiles=run.plan.fuse_limit)
+    if ms < 0.2:
+        # launch-bound layouts: the same step as one captured HIP graph, replayed (untimed capture, wall clock
+        # around the replays)
+        side = torch.cuda.Stream()
+        gr = torch.cuda.CUDAGraph()
+        run.t = 0
+        with torch.cuda.graph(gr, stream=side):
+            run.step()
+        torch.cuda.synchronize()
+        reps = max(steps, 50)
+        for _ in range(5):
+            gr.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            gr.replay()
+        torch.cuda.synchronize()
+        out["hip_graph_replay"] = {"ms_per_step": round((time.perf_counter() - t0) * 1e3 / reps, 4), "replays": reps}
+        del gr
     ms2, calls2 = run.timed_with_held_state(steps, max(warmup, 1))
     out["held_state_mode"] = {"ms_per_step": round(ms2, 4),
                                        "per_call_ms": {"ef_worker_step": round(calls2[0], 4),
